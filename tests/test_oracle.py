@@ -1,0 +1,266 @@
+"""Pins for the fp64 CPU oracle (no GPU).
+
+The paper prints no worked numeric example, so the oracle is pinned by:
+  * a hand-evaluated example with exact fractions (tests/golden/),
+  * definition == running-sum factorisation (an exact identity, Sec. 3.1/3.2),
+  * central finite differences of L = sum(O * dO) (pins the corrected gradient
+    formulas of Sec. 3.2),
+  * closed forms (b = 0, N = 1, first causal row),
+  * invariants (weights sum to one, scale invariances, column sums of dV),
+  * the augmented-vector dense form evaluated with library matrix products,
+    and PyTorch fp64 autograd through that dense form,
+  * a = 0: normalised linear attention with the identity feature map
+    (App. B.1), evaluated with library cumulative sums.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import la_workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "tiny_hand_example.txt")
+
+
+def rand_inputs(BH, N, D, seed, normalise=True):
+    x = wl.make_inputs(1, BH, N, D, "f32", seed, normalise)
+    return tuple(x[n][1][0] for n in ("Q", "K", "V", "dO"))
+
+
+def relerr(x, y):
+    return float(np.max(np.abs(x - y)) / (np.max(np.abs(y)) + 1e-300))
+
+
+# --------------------------------------------------------------------------
+# hand example
+# --------------------------------------------------------------------------
+def _golden():
+    out = {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        mode, name, *vals = line.split()
+        out[(mode, name)] = np.array([float(Fraction(v)) for v in vals])
+    return out
+
+
+@pytest.mark.parametrize("mode", ["causal", "noncausal"])
+def test_hand_example(oracle_mod, mode):
+    gold = _golden()
+    causal = mode == "causal"
+    q = np.array([[1.0], [2.0]]); k = np.array([[3.0], [4.0]])
+    v = np.array([[5.0], [6.0]]); do = np.array([[1.0], [1.0]])
+    for fwd in (oracle_mod.forward_def, oracle_mod.forward_rec):
+        O, G = fwd(q, k, v, 1.0, 0.5, causal)
+        np.testing.assert_allclose(O[:, 0], gold[(mode, "O")], rtol=1e-14)
+        np.testing.assert_allclose(G, gold[(mode, "G")], rtol=1e-14)
+    O, G = oracle_mod.forward_def(q, k, v, 1.0, 0.5, causal)
+    grads = [oracle_mod.backward_def(q, k, v, do, 1.0, 0.5, causal),
+             oracle_mod.backward_rec(q, k, v, O, G, do, 1.0, 0.5, causal)]
+    for dq, dk, dv in grads:
+        np.testing.assert_allclose(dq[:, 0], gold[(mode, "dQ")], rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(dk[:, 0], gold[(mode, "dK")], rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(dv[:, 0], gold[(mode, "dV")], rtol=1e-13, atol=1e-16)
+
+
+# --------------------------------------------------------------------------
+# definition == factorisation
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("BH,N,D", [(1, 1, 1), (2, 7, 3), (3, 65, 16), (1, 256, 16), (2, 300, 64)])
+def test_def_equals_rec(oracle_mod, causal, BH, N, D):
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=11 + N)
+    for a, b in ((1.0, 0.5), (2.0, -0.7), (1.0, 0.9)):
+        O1, G1 = oracle_mod.forward_def(Q, K, V, a, b, causal)
+        O2, G2 = oracle_mod.forward_rec(Q, K, V, a, b, causal)
+        assert relerr(O2, O1) < 1e-11 and relerr(G2, G1) < 1e-12
+        g1 = oracle_mod.backward_def(Q, K, V, dO, a, b, causal)
+        g2 = oracle_mod.backward_rec(Q, K, V, O1, G1, dO, a, b, causal)
+        for x, y in zip(g2, g1):
+            assert relerr(x, y) < 1e-10
+
+
+def test_def_rows_matches_full(oracle_mod):
+    Q, K, V, _ = rand_inputs(1, 97, 8, seed=5)
+    rows = np.array([0, 1, 50, 96])
+    for causal in (True, False):
+        O, G = oracle_mod.forward_def(Q, K, V, 1.0, 0.5, causal)
+        o, g = oracle_mod.forward_def_rows(Q[0], K[0], V[0], rows, 1.0, 0.5, causal)
+        np.testing.assert_allclose(o, O[0][rows], rtol=1e-14)
+        np.testing.assert_allclose(g, G[0][rows], rtol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# finite differences
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("N,D", [(1, 1), (5, 2), (8, 4)])
+def test_finite_differences(oracle_mod, causal, N, D):
+    a, b = 1.0, 0.5
+    Q, K, V, dO = rand_inputs(1, N, D, seed=3)
+    O, G = oracle_mod.forward_def(Q, K, V, a, b, causal)
+    g_def = oracle_mod.backward_def(Q, K, V, dO, a, b, causal)
+    g_rec = oracle_mod.backward_rec(Q, K, V, O, G, dO, a, b, causal)
+
+    def loss(q, k, v):
+        o, _ = oracle_mod.forward_def(q, k, v, a, b, causal)
+        return float(np.sum(o * dO))
+
+    h = 1e-6
+    args = [Q, K, V]
+    for t in range(3):
+        fd = np.zeros_like(args[t])
+        it = np.nditer(args[t], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            plus = [x.copy() for x in args]
+            minus = [x.copy() for x in args]
+            plus[t][idx] += h
+            minus[t][idx] -= h
+            fd[idx] = (loss(*plus) - loss(*minus)) / (2 * h)
+        scale = np.max(np.abs(fd)) + 1e-12
+        assert np.max(np.abs(g_def[t] - fd)) / scale < 1e-6, ("def", t)
+        assert np.max(np.abs(g_rec[t] - fd)) / scale < 1e-6, ("rec", t)
+
+
+# --------------------------------------------------------------------------
+# closed forms
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+def test_b_zero_is_mean_of_v(oracle_mod, causal):
+    BH, N, D, a = 2, 33, 5, 1.7
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=9)
+    cnt = np.arange(1, N + 1, dtype=np.float64) if causal else np.full(N, float(N))
+    if causal:
+        mean = np.cumsum(V, axis=1) / cnt[None, :, None]
+    else:
+        mean = np.broadcast_to(V.mean(axis=1, keepdims=True), V.shape)
+    # dv_p = sum over rows i that attend to p of dO_i / n_i   (w = a, g = a n)
+    sc = dO / cnt[None, :, None]
+    if causal:
+        dv_ref = np.flip(np.cumsum(np.flip(sc, axis=1), axis=1), axis=1)
+    else:
+        dv_ref = np.broadcast_to(sc.sum(axis=1, keepdims=True), sc.shape)
+    for fwd in (oracle_mod.forward_def, oracle_mod.forward_rec):
+        O, G = fwd(Q, K, V, a, 0.0, causal)
+        np.testing.assert_allclose(O, mean, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(G, np.broadcast_to(a * cnt, G.shape), rtol=1e-14)
+    O, G = oracle_mod.forward_def(Q, K, V, a, 0.0, causal)
+    for dq, dk, dv in (oracle_mod.backward_def(Q, K, V, dO, a, 0.0, causal),
+                       oracle_mod.backward_rec(Q, K, V, O, G, dO, a, 0.0, causal)):
+        assert np.all(dq == 0) and np.all(dk == 0)
+        np.testing.assert_allclose(dv, dv_ref, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_single_row(oracle_mod, causal):
+    Q, K, V, dO = rand_inputs(3, 1, 6, seed=2)
+    O, G = oracle_mod.forward_rec(Q, K, V, 1.0, 0.5, causal)
+    np.testing.assert_allclose(O, V, rtol=1e-14)
+    for dq, dk, dv in (oracle_mod.backward_def(Q, K, V, dO, 1.0, 0.5, causal),
+                       oracle_mod.backward_rec(Q, K, V, O, G, dO, 1.0, 0.5, causal)):
+        np.testing.assert_allclose(dv, dO, rtol=1e-13)
+        assert np.max(np.abs(dq)) < 1e-14 and np.max(np.abs(dk)) < 1e-14
+
+
+def test_first_causal_row(oracle_mod):
+    Q, K, V, dO = rand_inputs(2, 9, 4, seed=4)
+    O, G = oracle_mod.forward_rec(Q, K, V, 1.0, 0.5, True)
+    np.testing.assert_allclose(O[:, 0], V[:, 0], rtol=1e-14)
+    dq, _, _ = oracle_mod.backward_rec(Q, K, V, O, G, dO, 1.0, 0.5, True)
+    assert np.max(np.abs(dq[:, 0])) < 1e-14
+
+
+# --------------------------------------------------------------------------
+# invariants
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+def test_invariants(oracle_mod, causal):
+    BH, N, D, a, b = 2, 40, 6, 1.0, 0.5
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=21)
+    O, G = oracle_mod.forward_rec(Q, K, V, a, b, causal)
+    dq, dk, dv = oracle_mod.backward_rec(Q, K, V, O, G, dO, a, b, causal)
+
+    # attention weights sum to one: constant V rows give the same constant rows
+    c = np.linspace(-1, 2, D)
+    Vc = np.broadcast_to(c, V.shape).copy()
+    Oc, _ = oracle_mod.forward_rec(Q, K, Vc, a, b, causal)
+    np.testing.assert_allclose(Oc, Vc, rtol=1e-12)
+
+    # (a, b) -> (lambda a, lambda b) changes nothing but G
+    lam = 3.25
+    O2, G2 = oracle_mod.forward_rec(Q, K, V, lam * a, lam * b, causal)
+    np.testing.assert_allclose(O2, O, rtol=1e-12)
+    np.testing.assert_allclose(G2, lam * G, rtol=1e-12)
+    g2 = oracle_mod.backward_rec(Q, K, V, O2, G2, dO, lam * a, lam * b, causal)
+    for x, y in zip(g2, (dq, dk, dv)):
+        np.testing.assert_allclose(x, y, rtol=1e-10, atol=1e-14)
+
+    # b can be folded into Q
+    O3, G3 = oracle_mod.forward_rec(b * Q, K, V, a, 1.0, causal)
+    np.testing.assert_allclose(O3, O, rtol=1e-12)
+    np.testing.assert_allclose(G3, G, rtol=1e-12)
+
+    # shifting every v by a constant shifts every o by it: column sums of dV
+    np.testing.assert_allclose(dv.sum(axis=1), dO.sum(axis=1), rtol=1e-11)
+
+    # sum_n c_in w_in = 0 per row, hence q_i . dq_i = -a sum_n c_in
+    oh = dO / G[..., None]
+    delta = np.sum(O * oh, axis=-1)
+    cmat = np.einsum("bij,bnj->bin", oh, V) - delta[..., None]
+    if causal:
+        cmat = np.tril(cmat)
+    np.testing.assert_allclose(np.sum(Q * dq, axis=-1), -a * cmat.sum(axis=-1),
+                               rtol=1e-9, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# dense augmented form with library matrix products; autograd through it
+# --------------------------------------------------------------------------
+def dense_augmented(Q, K, V, a, b, causal):
+    """q' = [b q, a], k' = [k, 1], v' = [v, 1]:  F = mask(Q'K'^T) V',
+    O = F[:, :D] / F[:, D], G = F[:, D]."""
+    ones = torch.ones_like(Q[..., :1])
+    Qa = torch.cat([b * Q, a * ones], dim=-1)
+    Ka = torch.cat([K, ones], dim=-1)
+    Va = torch.cat([V, ones], dim=-1)
+    W = Qa @ Ka.transpose(-1, -2)
+    if causal:
+        W = torch.tril(W)
+    F = W @ Va
+    return F[..., :-1] / F[..., -1:], F[..., -1]
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("BH,N,D", [(2, 19, 4), (1, 130, 16)])
+def test_dense_form_and_autograd(oracle_mod, causal, BH, N, D):
+    a, b = 1.0, 0.5
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=31)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    O_t, G_t = dense_augmented(tq, tk, tv, a, b, causal)
+    (O_t * torch.tensor(dO)).sum().backward()
+    O, G = oracle_mod.forward_rec(Q, K, V, a, b, causal)
+    np.testing.assert_allclose(O, O_t.detach().numpy(), rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(G, G_t.detach().numpy(), rtol=1e-12)
+    for grads in (oracle_mod.backward_def(Q, K, V, dO, a, b, causal),
+                  oracle_mod.backward_rec(Q, K, V, O, G, dO, a, b, causal)):
+        for x, t in zip(grads, (tq, tk, tv)):
+            np.testing.assert_allclose(x, t.grad.numpy(), rtol=1e-9, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# a = 0: identity-feature-map normalised linear attention via cumulative sums
+# --------------------------------------------------------------------------
+def test_a_zero_matches_cumsum_rnn_form(oracle_mod):
+    BH, N, D = 2, 50, 5
+    Q, K, V, _ = rand_inputs(BH, N, D, seed=41, normalise=False)
+    Q, K = np.abs(Q) + 0.1, np.abs(K) + 0.1      # keep q.z > 0
+    S = np.cumsum(np.einsum("bnm,bnj->bnmj", K, V), axis=1)
+    z = np.cumsum(K, axis=1)
+    ref = np.einsum("bnm,bnmj->bnj", Q, S) / np.einsum("bnm,bnm->bn", Q, z)[..., None]
+    for fwd in (oracle_mod.forward_def, oracle_mod.forward_rec):
+        O, _ = fwd(Q, K, V, 0.0, 1.0, True)
+        np.testing.assert_allclose(O, ref, rtol=1e-11)
