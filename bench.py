@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark: linear-attention forward + backward on one MI355X.
+
+A step is one la_forward followed by one la_backward over one batch of
+synthetic input that is already resident in device memory.  Prints one JSON
+line with the tokens/s of the step, the roofline of the dominant kernel
+(measured with HIP events recorded by the library between its kernels) and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime torch already loaded."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = (ctypes.c_void_p * n)()
+        for i in range(n):
+            h = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(h))
+            if rc != 0:
+                raise RuntimeError("hipEventCreate failed: %d" % rc)
+            self.handles[i] = h
+
+    def elapsed_ms(self, i, j):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j])
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+    def destroy(self):
+        for h in self.handles:
+            self.hip.hipEventDestroy(h)
+
+
+def make_device_inputs(cfg, torch, n_sets):
+    """Synthetic inputs with the workload's recipe, drawn on the device: Q, K
+    Gaussian with unit-norm rows, V and dO standard Gaussian, cast to the I/O type."""
+    td = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(251021956)
+    sets = []
+    shape = (cfg.B, cfg.H, cfg.N, cfg.D)
+    for _ in range(n_sets):
+        t = {}
+        for name in ("Q", "K", "V", "dO"):
+            x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen)
+            if name in ("Q", "K"):
+                x = x / x.norm(dim=-1, keepdim=True)
+            t[name] = x.to(td).contiguous()
+        t["O"] = torch.empty(shape, device="cuda", dtype=td)
+        t["G"] = torch.empty(shape[:3], device="cuda", dtype=torch.float32)
+        for name in ("dQ", "dK", "dV"):
+            t[name] = torch.empty(shape, device="cuda", dtype=td)
+        sets.append(t)
+    return sets
+
+
+def cpu_baseline(cfg, budget_slices):
+    """Time the fp64 oracle (running-sum forward + backward) on a bounded sample
+    of (batch, head) slices of the same workload, on the host cores."""
+    import numpy as np
+
+    import la_workloads as wl
+    import oracle
+
+    idx = wl.CONFIGS.index(cfg)
+    n = min(budget_slices, cfg.B * cfg.H)
+    x = wl.config_inputs(idx, bh_subset=list(range(n)))
+    Q, K, V, dO = (x[k][1] for k in ("Q", "K", "V", "dO"))
+    oracle.forward_rec(Q[:1, :64], K[:1, :64], V[:1, :64], cfg.a, cfg.b, cfg.causal)  # load lib
+    t0 = time.perf_counter()
+    O, G = oracle.forward_rec(Q, K, V, cfg.a, cfg.b, cfg.causal)
+    oracle.backward_rec(Q, K, V, O, G, dO, cfg.a, cfg.b, cfg.causal)
+    dt = time.perf_counter() - t0
+    tokens = n * cfg.N / cfg.H  # a token is one (batch, position); it has H heads
+    return {
+        "value": tokens / dt,
+        "unit": "tokens/s",
+        "cores": min(oracle.num_threads(), n),
+        "kind": "oracle",
+        "sample": "%d of %d (batch,head) slices of %s, fp64 running-sum forward+backward, "
+                  "%.1f s wall" % (n, cfg.B * cfg.H, cfg.name, dt),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into la_workloads.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-slices", type=int, default=64)
+    ap.add_argument("--buffer-sets", type=int, default=0,
+                    help="independent input/output sets rotated through (0: enough to exceed "
+                         "the 256 MB last-level cache)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU only: this build has no multi-GPU path "
+                 "(run with --gpus 1)")
+
+    import torch
+
+    import la_workloads as wl
+    import paper_2510_21956_amd as la
+
+    la.load_library()  # raises if the HIP library has not been built; no fallback
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    B, H, N, D = cfg.B, cfg.H, cfg.N, cfg.D
+    e = 4 if cfg.dtype == "f32" else 2
+    dt = la.LA_F32 if cfg.dtype == "f32" else la.LA_BF16
+    T = cfg.token_heads
+
+    # Rotate through several buffer sets so that a step cannot find its inputs in
+    # the 256 MB memory-side cache left there by the previous step.
+    set_bytes = 8 * T * D * e + 4 * T
+    n_sets = args.buffer_sets or max(2, min(8, int(1.5 * 1024 ** 3 // set_bytes) or 1))
+    free0 = torch.cuda.mem_get_info()[0]
+    sets = make_device_inputs(cfg, torch, n_sets)
+    wsf = torch.empty(max(256, la.la_workspace_bytes(B, H, N, D, dt, cfg.causal, 0)),
+                      dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(max(256, la.la_workspace_bytes(B, H, N, D, dt, cfg.causal, 1)),
+                      dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(t, trf=None, trb=None):
+        la.la_forward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b, cfg.causal,
+                             wsf, None, trf)
+        la.la_backward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
+                              t["dV"], cfg.a, cfg.b, cfg.causal, wsb, None, trb)
+
+    for i in range(args.warmup):
+        step(sets[i % n_sets])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % n_sets])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    peak_bytes = free0 - torch.cuda.mem_get_info()[0]
+
+    # Per-kernel durations: a second timed loop of the same steps with the library
+    # recording HIP events between its kernels on the stream it launches on.
+    evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
+    trf, trb = la.la_trace(), la.la_trace()
+    trf.events, trf.capacity = ctypes.cast(evf.handles, ctypes.POINTER(ctypes.c_void_p)), \
+        la.LA_MAX_TRACE + 1
+    trb.events, trb.capacity = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p)), \
+        la.LA_MAX_TRACE + 1
+    ksum, kcount = {}, {}
+    reps = max(5, min(args.steps, 30))
+    for i in range(reps):
+        step(sets[i % n_sets], trf, trb)
+        torch.cuda.synchronize()
+        for tr, ev, tag in ((trf, evf, "fwd"), (trb, evb, "bwd")):
+            for k in range(tr.recorded - 1):
+                name = tag + ":" + tr.names[k].decode()
+                ksum[name] = ksum.get(name, 0.0) + ev.elapsed_ms(k, k + 1)
+                kcount[name] = kcount.get(name, 0) + 1
+    kernels_ms = {k: ksum[k] / kcount[k] for k in ksum}
+    evf.destroy()
+    evb.destroy()
+
+    # Roofline of the dominant kernel.  Algorithmic bytes per token-head of each
+    # step of the path (every operand it needs read once, every result written once):
+    #   forward  apply: Q,K,V in, O out, G out            (4 D e + 4)
+    #   backward apply: Q,K,V,dO in, dQ,dK,dV out, G,delta in   (7 D e + 8)
+    #   forward  state: K,V in                            (2 D e)
+    #   backward state: Q,K,V,O,dO,G in, delta out        (5 D e + 8)
+    alg_bytes = {"fwd_apply": 4 * D * e + 4, "bwd_apply": 7 * D * e + 8, "fwd_state": 2 * D * e,
+                 "bwd_state": 5 * D * e + 8}
+    dom = max(kernels_ms, key=kernels_ms.get)
+    dom_key = next((k for k in alg_bytes if dom.endswith(k)), None)
+    dom_ms = kernels_ms[dom]
+    roofline = None
+    if dom_key:
+        achieved = alg_bytes[dom_key] * T / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T}
+    pass_bytes = (12 * D * e + 8) * T  # every input once, every output once, forward + backward
+    pass_gbs = pass_bytes / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "fwd+bwd tokens/s",
+        "value": cfg.tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 I/O, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": B, "H": H, "N": N, "D": D, "causal": cfg.causal,
+                   "a": cfg.a, "b": cfg.b, "buffer_sets": n_sets},
+        "token_heads_per_s": T / (ms_per_step * 1e-3),
+        "whole_pass": {"compulsory_bytes": pass_bytes, "achieved_GBs": pass_gbs,
+                       "frac_of_hbm_peak": pass_gbs / HBM_PEAK_GBS},
+        "kernels_ms": kernels_ms,
+        "peak_device_bytes": int(peak_bytes),
+        "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel()},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_slices)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,151 @@
+/*
+ * la.h -- C ABI of the MI355X (gfx950) linear-attention library.
+ *
+ * Linear attention with kernel f(x) = a + b*x (Sec. 2.2): for every (batch,
+ * head) slice with rows q_i, k_i, v_i in R^D, i = 0..N-1,
+ *
+ *     w_in = a + b * (q_i . k_n)
+ *     g_i  = sum_{n in A(i)} w_in
+ *     o_i  = sum_{n in A(i)} w_in * v_n / g_i
+ *
+ * where A(i) = {0..i} with the causal mask and {0..N-1} without it.  The
+ * library evaluates this in O(N D^2) time and O(N D) memory through the
+ * running sums of Sec. 3.1 (forward, Eq. fglast / xy) and Sec. 3.2 (backward,
+ * Eq. back1 / back2 / endd), carried chunk by chunk.
+ *
+ * Conventions common to every entry point
+ *   - All tensor arguments are DEVICE pointers to dense row-major arrays
+ *     [B, H, N, D] with D contiguous (the paper's [B*H, N, D] storage, Sec. 4);
+ *     G is [B, H, N] float32.  Every pointer must be 16-byte aligned.
+ *   - `dt` is the element type of Q, K, V, O, dO, dQ, dK, dV: LA_F32 (float) or
+ *     LA_BF16 (bfloat16 bit patterns, round-to-nearest-even on store).  All
+ *     accumulation is float32; G is always float32.
+ *   - The caller owns every buffer, including the workspace.  The library
+ *     allocates no memory, keeps no state between calls and is re-entrant.
+ *     Calls that share a workspace must not overlap in time.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  The call returns without synchronising.
+ *   - Outputs are overwritten, never accumulated into.  No output may alias
+ *     an input or another output.
+ *   - Supported: D in {16, 32, 64, 128}; B, H, N >= 1 with B*H*N*D < 2^40;
+ *     any N (a ragged last chunk is handled).
+ *   - Errors are reported by return code only.  Every argument check happens
+ *     before anything is enqueued, so a failed call has no side effect.
+ *     LA_ERR_LAUNCH carries a failed kernel enqueue (hipGetLastError).
+ *   - Numerical precondition (not checked): g_i != 0.  It holds when
+ *     a > |b| * max|q.k|, e.g. unit-norm rows of Q and K (the normalisation of
+ *     Sec. 3.3, which is the caller's job) with a = 1, b = 0.5.
+ */
+#ifndef LA_H_
+#define LA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LA_API __attribute__((visibility("default")))
+
+typedef enum la_status {
+    LA_OK = 0,
+    LA_ERR_NULL = 1,        /* a required pointer is NULL                      */
+    LA_ERR_SHAPE = 2,       /* B, H, N or D out of range                       */
+    LA_ERR_UNSUPPORTED = 3, /* D or dtype not supported                        */
+    LA_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                */
+    LA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than required         */
+    LA_ERR_LAUNCH = 6       /* a kernel enqueue failed                         */
+} la_status;
+
+typedef enum la_dtype {
+    LA_F32 = 0,
+    LA_BF16 = 1
+} la_dtype;
+
+/* Library version: major*10000 + minor*100 + patch. */
+LA_API int la_version(void);
+
+/* Static, human-readable name of a status code. */
+LA_API const char *la_status_string(la_status s);
+
+/*
+ * Bytes of device workspace la_forward (is_backward = 0) or la_backward
+ * (is_backward != 0) needs for this problem.  Returns 0 for invalid or
+ * unsupported arguments.  The workspace holds the per-segment running-sum
+ * states (S = sum k v^T, z = sum k, p = sum v of Eq. xy; and the reverse sums
+ * of Eq. endd for the backward pass) that let segments of one sequence run in
+ * parallel; its size is O(B*H*(N/segment)*D^2 + B*H*N).
+ */
+LA_API size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal,
+                          int is_backward);
+
+/*
+ * Forward pass (Sec. 3.1: Eq. div, fglast, xy).
+ *   in : Q, K, V   [B,H,N,D] of `dt`
+ *   out: O         [B,H,N,D] of `dt`      o_i = f_i / g_i
+ *        G         [B,H,N]   float32      g_i, the denominators; part of the
+ *                                         set {Q,K,V,O,g} kept for the
+ *                                         backward pass (Sec. 3.2)
+ *   a, b   : kernel coefficients; causal != 0 applies the causal mask.
+ *   workspace / workspace_bytes: device scratch of at least
+ *            la_workspace_bytes(..., 0) bytes, 256-byte aligned.
+ */
+LA_API la_status la_forward(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward pass (Sec. 3.2: Eq. bound, back1, back2, endd).
+ *   in : Q, K, V, O, dO [B,H,N,D] of `dt`; G [B,H,N] float32 -- O and G exactly
+ *        as written by la_forward for the same Q, K, V, a, b, causal.
+ *   out: dQ, dK, dV     [B,H,N,D] of `dt`: gradients of sum(O * dO).
+ *   workspace: at least la_workspace_bytes(..., 1) bytes, 256-byte aligned.
+ */
+LA_API la_status la_backward(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-kernel timing hook for benchmarks and profiles.  The caller creates
+ * `capacity` hipEvent_t handles (timing enabled) and passes them in `events`;
+ * the traced entry points record events[0] on the stream before their first
+ * kernel and events[k] right after their k-th kernel, and fill `names[k-1]`
+ * with a static string naming that kernel.  `recorded` receives the number of
+ * events recorded (kernels + 1); if `capacity` is too small only the first
+ * `capacity` events are recorded.  The caller synchronises and reads the
+ * intervals with hipEventElapsedTime.  The library never waits on the events.
+ */
+#define LA_MAX_TRACE 8
+typedef struct la_trace {
+    void **events;                    /* in : caller-owned hipEvent_t handles     */
+    int capacity;                     /* in : number of handles in `events`       */
+    int recorded;                     /* out: number of events recorded           */
+    const char *names[LA_MAX_TRACE];  /* out: names[k] = kernel between events k, k+1 */
+} la_trace;
+
+/* la_forward / la_backward with the timing hook; `trace` may be NULL, which
+ * makes them identical to the plain entry points. */
+LA_API la_status la_forward_traced(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt,
+                     void *workspace, size_t workspace_bytes, void *hip_stream,
+                     la_trace *trace);
+
+LA_API la_status la_backward_traced(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes, void *hip_stream,
+                      la_trace *trace);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_H_ */

@@ -1,0 +1,163 @@
+"""ctypes binding with the same names as the C ABI in include/la.h.
+
+Argument marshalling only.  There is no CPU fallback: if libla.so has not been
+built, loading fails with an error that says how to build it.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libla.so")
+_lib = None
+
+LA_F32 = 0
+LA_BF16 = 1
+
+LA_MAX_TRACE = 8
+
+EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
+           "la_forward_traced", "la_backward_traced")
+
+
+class la_trace(ctypes.Structure):
+    """struct la_trace of include/la.h."""
+    _fields_ = [("events", ctypes.POINTER(ctypes.c_void_p)),
+                ("capacity", ctypes.c_int),
+                ("recorded", ctypes.c_int),
+                ("names", ctypes.c_char_p * LA_MAX_TRACE)]
+
+
+class LaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__("%s failed: %s" % (where, la_status_string(code)))
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libla.so (built by paper_2510_21956_amd/build.py).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "HIP library %s not found; build it with "
+            "`python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or python paper_2510_21956_amd/build.py).  There is no CPU fallback." % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i, f = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+    lib.la_version.restype = i
+    lib.la_version.argtypes = []
+    lib.la_status_string.restype = ctypes.c_char_p
+    lib.la_status_string.argtypes = [i]
+    lib.la_workspace_bytes.restype = sz
+    lib.la_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.la_forward.restype = i
+    lib.la_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, f, f, i, i, vp, sz, vp]
+    lib.la_backward.restype = i
+    lib.la_backward.argtypes = [vp] * 9 + [i, i, i, i, f, f, i, i, vp, sz, vp]
+    tp = ctypes.POINTER(la_trace)
+    lib.la_forward_traced.restype = i
+    lib.la_forward_traced.argtypes = lib.la_forward.argtypes + [tp]
+    lib.la_backward_traced.restype = i
+    lib.la_backward_traced.argtypes = lib.la_backward.argtypes + [tp]
+    _lib = lib
+    return lib
+
+
+def la_version():
+    return int(load_library().la_version())
+
+
+def la_status_string(code):
+    return load_library().la_status_string(int(code)).decode()
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return LA_F32
+    if t.dtype == torch.bfloat16:
+        return LA_BF16
+    raise TypeError("Q/K/V must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def la_workspace_bytes(B, H, N, D, dt, causal, is_backward):
+    return int(load_library().la_workspace_bytes(B, H, N, D, dt, int(bool(causal)),
+                                                 int(bool(is_backward))))
+
+
+def _check_tensors(ref, *ts):
+    for t in ts:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+        if t.device != ref.device:
+            raise ValueError("tensors must live on one device")
+
+
+def _stream_ptr(stream, device):
+    s = torch.cuda.current_stream(device) if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def la_forward(Q, K, V, O, G, a, b, causal, workspace, stream=None):
+    """la_forward of include/la.h on torch device tensors.
+
+    Q, K, V, O: [B, H, N, D] float32 or bfloat16; G: [B, H, N] float32;
+    workspace: uint8 device tensor of at least la_workspace_bytes(..., 0) bytes."""
+    la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream, None)
+
+
+def la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream=None, trace=None):
+    """la_forward_traced of include/la.h; ``trace`` is a la_trace structure or None."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, N, D]")
+    B, H, N, D = Q.shape
+    _check_tensors(Q, K, V, O, G, workspace)
+    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape or G.shape != Q.shape[:3]:
+        raise ValueError("shape mismatch")
+    if not (K.dtype == V.dtype == O.dtype == Q.dtype) or G.dtype != torch.float32:
+        raise TypeError("dtype mismatch")
+    rc = load_library().la_forward_traced(
+        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), B, H, N, D, float(a), float(b),
+        int(bool(causal)), _dtype_code(Q), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream, Q.device),
+        ctypes.byref(trace) if trace is not None else None)
+    if rc != 0:
+        raise LaError(rc, "la_forward")
+
+
+def la_backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=None):
+    """la_backward of include/la.h on torch device tensors (see la_forward)."""
+    la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream, None)
+
+
+def la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=None,
+                       trace=None):
+    """la_backward_traced of include/la.h; ``trace`` is a la_trace structure or None."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, N, D]")
+    B, H, N, D = Q.shape
+    _check_tensors(Q, K, V, O, G, dO, dQ, dK, dV, workspace)
+    for t in (K, V, O, dO, dQ, dK, dV):
+        if t.shape != Q.shape:
+            raise ValueError("shape mismatch")
+        if t.dtype != Q.dtype:
+            raise TypeError("dtype mismatch")
+    if G.shape != Q.shape[:3] or G.dtype != torch.float32:
+        raise ValueError("G must be [B, H, N] float32")
+    rc = load_library().la_backward_traced(
+        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
+        B, H, N, D, float(a), float(b), int(bool(causal)), _dtype_code(Q), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream, Q.device),
+        ctypes.byref(trace) if trace is not None else None)
+    if rc != 0:
+        raise LaError(rc, "la_backward")

@@ -1,0 +1,144 @@
+// C ABI entry points: argument validation, segment plan, dispatch.
+#include <stdlib.h>
+
+#include "la_common.h"
+
+namespace la {
+
+static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128; }
+
+// Segment length: enough workgroups to fill 256 compute units a few times over,
+// but segments long enough that the D*D state a segment hands over stays small
+// next to the rows it covers.  LA_SEG_LEN (rows, rounded up to 64) overrides it.
+Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
+{
+    (void)dt;
+    (void)causal;
+    Plan p;
+    const long BH = (long)B * H;
+    const int min_len = (D >= 128) ? 512 : 256;
+    long want = (768 + BH - 1) / BH;  // segments per slice to reach ~3 workgroups per CU
+    long max_by_len = N / min_len;
+    if (max_by_len < 1) max_by_len = 1;
+    if (want > max_by_len) want = max_by_len;
+    if (want < 1) want = 1;
+    long seg_len = (N + want - 1) / want;
+    const char *env = getenv("LA_SEG_LEN");
+    if (env) {
+        long v = atol(env);
+        if (v > 0) seg_len = v;
+    }
+    seg_len = (long)round_up((size_t)seg_len, 64);
+    p.seg_len = (int)seg_len;
+    p.nseg = (int)((N + seg_len - 1) / seg_len);
+    const size_t DD = (size_t)D * D;
+    p.slot_floats = round_up(is_backward ? 2 * DD + 3 * D : DD + 2 * D, 64);
+    const size_t slots = (size_t)BH * p.nseg * p.slot_floats;
+    p.delta_offset_floats = round_up(slots, 64);
+    p.total_bytes = is_backward ? (p.delta_offset_floats + round_up((size_t)BH * N, 64)) * 4
+                                : round_up(slots, 64) * 4;
+    return p;
+}
+
+static la_status check_shape(int B, int H, int N, int D, la_dtype dt)
+{
+    if (B < 1 || H < 1 || N < 1 || D < 1) return LA_ERR_SHAPE;
+    if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_UNSUPPORTED;
+    if (!supported_d(D)) return LA_ERR_UNSUPPORTED;
+    const double elems = (double)B * H * N * D;
+    if (elems >= 1099511627776.0) return LA_ERR_SHAPE;  // 2^40
+    if ((double)B * H > 2147483647.0 / 4096.0) return LA_ERR_SHAPE;
+    return LA_OK;
+}
+
+static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+}  // namespace la
+
+extern "C" {
+
+int la_version(void) { return 100; }
+
+const char *la_status_string(la_status s)
+{
+    switch (s) {
+        case LA_OK: return "LA_OK";
+        case LA_ERR_NULL: return "LA_ERR_NULL: required pointer is NULL";
+        case LA_ERR_SHAPE: return "LA_ERR_SHAPE: B, H, N or D out of range";
+        case LA_ERR_UNSUPPORTED: return "LA_ERR_UNSUPPORTED: head size or dtype not supported";
+        case LA_ERR_ALIGN: return "LA_ERR_ALIGN: pointer not 16-byte aligned";
+        case LA_ERR_WORKSPACE: return "LA_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case LA_ERR_LAUNCH: return "LA_ERR_LAUNCH: kernel enqueue failed";
+    }
+    return "unknown la_status";
+}
+
+size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
+{
+    if (la::check_shape(B, H, N, D, dt) != LA_OK) return 0;
+    return la::make_plan(B, H, N, D, dt, causal, is_backward).total_bytes;
+}
+
+la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,
+                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                            void *workspace, size_t workspace_bytes, void *hip_stream,
+                            la_trace *trace)
+{
+    la_status s = la::check_shape(B, H, N, D, dt);
+    if (s != LA_OK) return s;
+    if (!Q || !K || !V || !O || !G) return LA_ERR_NULL;
+    if (!la::aligned16(Q) || !la::aligned16(K) || !la::aligned16(V) || !la::aligned16(O) ||
+        !la::aligned16(G))
+        return LA_ERR_ALIGN;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 0);
+    if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
+        return LA_ERR_WORKSPACE;
+    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
+    if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
+    la::Tracer tc(trace, (hipStream_t)hip_stream);
+    return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
+                               (hipStream_t)hip_stream, tc);
+}
+
+la_status la_forward(const void *Q, const void *K, const void *V, void *O, float *G, int B, int H,
+                     int N, int D, float a, float b, int causal, la_dtype dt, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    return la_forward_traced(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace,
+                             workspace_bytes, hip_stream, nullptr);
+}
+
+la_status la_backward_traced(const void *Q, const void *K, const void *V, const void *O,
+                             const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
+                             int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                             void *workspace, size_t workspace_bytes, void *hip_stream,
+                             la_trace *trace)
+{
+    la_status s = la::check_shape(B, H, N, D, dt);
+    if (s != LA_OK) return s;
+    if (!Q || !K || !V || !O || !G || !dO || !dQ || !dK || !dV) return LA_ERR_NULL;
+    const void *ptrs[] = {Q, K, V, O, G, dO, dQ, dK, dV};
+    for (const void *p : ptrs)
+        if (!la::aligned16(p)) return LA_ERR_ALIGN;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 1);
+    if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
+        return LA_ERR_WORKSPACE;
+    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
+    if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
+    la::Tracer tc(trace, (hipStream_t)hip_stream);
+    return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
+                                (hipStream_t)hip_stream, tc);
+}
+
+la_status la_backward(const void *Q, const void *K, const void *V, const void *O, const float *G,
+                      const void *dO, void *dQ, void *dK, void *dV, int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt, void *workspace,
+                      size_t workspace_bytes, void *hip_stream)
+{
+    return la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt,
+                              workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the library's translation units (not part
+// of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "la.h"
+
+namespace la {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_float(bf16_t h)
+{
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// Round-to-nearest-even; NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ bf16_t float_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_elem(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const bf16_t *p, size_t i) { return bf16_to_float(p[i]); }
+__device__ __forceinline__ void store_elem(float *p, size_t i, float x) { p[i] = x; }
+__device__ __forceinline__ void store_elem(bf16_t *p, size_t i, float x) { p[i] = float_to_bf16(x); }
+
+// How one call is cut into segments and where its scratch lives.
+//
+// A sequence of N rows is cut into `nseg` segments of `seg_len` rows (the last
+// may be shorter).  Each (slice, segment) owns one state slot in the
+// workspace.  A forward slot is [S (D*D) | z (D) | p (D)]; a backward slot is
+// [S (D*D) | z (D) | R (D*D) | u (D) | w (D)], both padded to `slot_floats`.
+// S = sum k v^T, z = sum k, p = sum v are the running sums of Eq. xy (without
+// the factors a, b); R = sum q OmegaHat^T, u = sum delta q, w = sum OmegaHat
+// are those of Eq. endd.  The backward workspace also holds delta_i =
+// o_i . OmegaHat_i, one float per row, after the slots.
+struct Plan {
+    int nseg;
+    int seg_len;
+    size_t slot_floats;
+    size_t delta_offset_floats;  // backward only
+    size_t total_bytes;
+};
+
+Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward);
+
+struct Problem {
+    int BH, N, D;
+    float a, b;
+    int causal;
+    la_dtype dt;
+};
+
+// Records the caller's timing events between kernels (see la_trace in la.h).
+struct Tracer {
+    la_trace *tr;
+    hipStream_t st;
+    Tracer(la_trace *t, hipStream_t s) : tr(t), st(s)
+    {
+        if (tr) {
+            tr->recorded = 0;
+            mark(nullptr);
+        }
+    }
+    // Call right after enqueuing the kernel called `name` (nullptr: start mark).
+    void mark(const char *name)
+    {
+        if (!tr || tr->recorded >= tr->capacity || tr->recorded > LA_MAX_TRACE) return;
+        if (name && tr->recorded >= 1) tr->names[tr->recorded - 1] = name;
+        (void)hipEventRecord((hipEvent_t)tr->events[tr->recorded], st);
+        tr->recorded++;
+    }
+};
+
+// Generic (plain-ALU, any supported D) path.
+la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                          const void *V, void *O, float *G, float *ws, hipStream_t st,
+                          Tracer &tc);
+la_status generic_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                           const void *V, const void *O, const float *G, const void *dO,
+                           void *dQ, void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
+
+}  // namespace la

@@ -1,0 +1,82 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared
+symbol, and rejects bad arguments before touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2510_21956_amd as la
+    if not os.path.exists(la.library_path()):
+        from paper_2510_21956_amd import build
+        build.build_library()
+    return la.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "la.h")).read()
+    return sorted(set(re.findall(r"LA_API[^;(]*?\b(la_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(lib):
+    names = declared_symbols()
+    import paper_2510_21956_amd as la
+    assert names == sorted(la.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_strings(lib):
+    import paper_2510_21956_amd as la
+    assert la.la_version() >= 100
+    assert la.la_status_string(0) == "LA_OK"
+    for code in range(1, 7):
+        assert la.la_status_string(code).startswith("LA_ERR_")
+
+
+def test_workspace_bytes(lib):
+    import paper_2510_21956_amd as la
+    assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0) > 0
+    assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 1) > \
+        la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0)
+    assert la.la_workspace_bytes(4, 16, 4096, 48, la.LA_F32, 1, 0) == 0      # unsupported D
+    assert la.la_workspace_bytes(0, 16, 4096, 64, la.LA_F32, 1, 0) == 0      # bad shape
+    assert la.la_workspace_bytes(1, 1, 1, 64, 7, 1, 0) == 0                  # bad dtype
+
+
+def test_argument_checks_precede_any_launch(lib):
+    """Bad arguments are rejected on the host: these calls must return an error
+    code without a GPU being present."""
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)  # never dereferenced: validation fails first
+    # NULL pointer
+    rc = lib.la_forward(vp(0), fake, fake, fake, fake, 1, 1, 64, 16, 1.0, 0.5, 1, 0, fake, 1 << 20,
+                        vp(0))
+    assert rc == 1
+    # bad shape
+    rc = lib.la_forward(fake, fake, fake, fake, fake, 1, 1, 0, 16, 1.0, 0.5, 1, 0, fake, 1 << 20,
+                        vp(0))
+    assert rc == 2
+    # unsupported D
+    rc = lib.la_forward(fake, fake, fake, fake, fake, 1, 1, 64, 20, 1.0, 0.5, 1, 0, fake, 1 << 20,
+                        vp(0))
+    assert rc == 3
+    # misaligned
+    rc = lib.la_forward(vp(0x1004), fake, fake, fake, fake, 1, 1, 64, 16, 1.0, 0.5, 1, 0, fake,
+                        1 << 20, vp(0))
+    assert rc == 4
+    # workspace too small
+    rc = lib.la_forward(fake, fake, fake, fake, fake, 4, 16, 4096, 64, 1.0, 0.5, 1, 0, fake, 16,
+                        vp(0))
+    assert rc == 5
+    rc = lib.la_backward(fake, fake, fake, fake, fake, fake, fake, fake, vp(0), 1, 1, 64, 16, 1.0,
+                         0.5, 1, 0, fake, 1 << 20, vp(0))
+    assert rc == 1
+    rc = lib.la_backward(fake, fake, fake, fake, fake, fake, fake, fake, fake, 4, 16, 4096, 64,
+                         1.0, 0.5, 1, 0, fake, 16, vp(0))
+    assert rc == 5
