@@ -55,6 +55,14 @@ static la_status check_shape(int B, int H, int N, int D, la_dtype dt)
 
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 
+// LA_PATH=generic forces the plain-ALU kernels (for A/B comparison and debugging).
+static bool use_fast(const Problem &pr)
+{
+    const char *env = getenv("LA_PATH");
+    if (env && env[0] == 'g') return false;
+    return fast_supported(pr);
+}
+
 }  // namespace la
 
 extern "C" {
@@ -98,6 +106,9 @@ la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
     la::Tracer tc(trace, (hipStream_t)hip_stream);
+    if (la::use_fast(pr))
+        return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
+                                (hipStream_t)hip_stream, tc);
     return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
                                (hipStream_t)hip_stream, tc);
 }

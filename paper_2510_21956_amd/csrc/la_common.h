@@ -79,6 +79,18 @@ struct Tracer {
     }
 };
 
+// Phase 2, shared by both paths: running sums over the state slots of every slice,
+// element-wise over floats [off, off+len) of each slot, over slots lo..hi.
+//   mode 0: slot[s] += slot[s-1], s = lo+1..hi;  mode 1: slot[s] += slot[s+1], s = hi-1..lo;
+//   mode 2: slot[0] = sum of slots lo..hi.
+void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off, int len, int mode,
+                       int lo, int hi, hipStream_t st);
+
+// Matrix-core path (la_fast.hip): D in {64, 128} for fp32, D = 128 for bf16.
+bool fast_supported(const Problem &pr);
+la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                       const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
+
 // Generic (plain-ALU, any supported D) path.
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                           const void *V, void *O, float *G, float *ws, hipStream_t st,

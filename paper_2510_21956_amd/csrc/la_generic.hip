@@ -560,6 +560,13 @@ la_status bwd_by_d(const Problem &pr, const Plan &pl, const void *Q, const void 
 
 }  // namespace
 
+void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off, int len, int mode,
+                       int lo, int hi, hipStream_t st)
+{
+    k_scan_slots<<<dim3(BH, (len + NT - 1) / NT), dim3(NT), 0, st>>>(ws, nseg, slot_floats, off,
+                                                                    len, mode, lo, hi);
+}
+
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                           const void *V, void *O, float *G, float *ws, hipStream_t st,
                           Tracer &tc)

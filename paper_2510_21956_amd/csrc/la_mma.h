@@ -1,0 +1,208 @@
+// Matrix-core (MFMA) building blocks for gfx950, shared by the fast kernels.
+//
+// Every contraction in the chunked linear-attention algebra is written as
+//     C[i][j] += sum_k X[i][k] * Y[j][k]
+// on two LDS tiles whose rows hold the contraction index contiguously, or with
+// one operand taken straight from an accumulator block of an earlier product.
+//
+// Block size BS (16 or 32) is the MFMA output tile edge; a 64-lane wave is
+// NG = 64 / BS lane groups of BS lanes.  Lane (c = lane % BS, g = lane / BS):
+//   * as an operand, supplies row c of X (or Y) and, per k-tile, the contraction
+//     indices  4g..4g+3  (fp32) or  4g..4g+3 and KT/2+4g..KT/2+4g+3  (bf16);
+//     KT = 4*NG (fp32) or 8*NG (bf16) contraction indices per k-tile;
+//   * holds, in accumulator register v of a block, C[(v%4) + 4g + 4*NG*(v/4)][c].
+// The accumulator rows a lane holds in one group of four registers are exactly
+// the four contiguous contraction indices it must supply as an operand, so a
+// finished block can be fed back as X or Y of the next product (contracting
+// over the block's row index) without passing through LDS.  This k-ordering is
+// a permutation of the hardware's natural one; it is harmless because both
+// operands of every MFMA use it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace la {
+
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+
+// ---- accumulator blocks -----------------------------------------------------
+template <int BS>
+struct Acc;
+
+template <>
+struct Acc<32> {
+    f16v v;
+    static constexpr int GROUPS = 4;  // groups of four registers
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = 0.f;
+    }
+    __device__ __forceinline__ f4v group(int q) const
+    {
+        f4v r = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+        return r;
+    }
+    __device__ __forceinline__ float get(int i) const { return v[i]; }
+    __device__ __forceinline__ void set(int i, float x) { v[i] = x; }
+};
+
+template <>
+struct Acc<16> {
+    f4v v;
+    static constexpr int GROUPS = 1;
+    __device__ __forceinline__ void zero() { v = f4v{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ f4v group(int) const { return v; }
+    __device__ __forceinline__ float get(int i) const { return v[i]; }
+    __device__ __forceinline__ void set(int i, float x) { v[i] = x; }
+};
+
+// Row of the block that register i of lane-group g holds.
+template <int BS>
+__device__ __forceinline__ int acc_row(int i, int g)
+{
+    constexpr int NG = 64 / BS;
+    return (i % 4) + 4 * g + 4 * NG * (i / 4);
+}
+
+// ---- operand fragments and the MFMA itself ------------------------------------
+template <typename T, int BS>
+struct Mma;
+
+template <int BS>
+struct Mma<float, BS> {
+    static constexpr int NG = 64 / BS;
+    static constexpr int KT = 4 * NG;   // contraction indices per k-tile
+    static constexpr int GPT = 1;       // accumulator groups per k-tile when used as operand
+    static constexpr int PLANES = 1;    // fp32 intermediates are used as they are
+    typedef f4v Frag;
+    struct Frag2 {
+        Frag hi;
+    };
+    // p points at element [row][k0] of a tile with contiguous contraction index.
+    static __device__ __forceinline__ Frag load(const float *p, int g)
+    {
+        return *reinterpret_cast<const f4v *>(p + 4 * g);
+    }
+    static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v) { return Frag2{g0}; }
+    static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
+    {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if constexpr (BS == 32)
+                c.v = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], c.v, 0, 0, 0);
+            else
+                c.v = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], c.v, 0, 0, 0);
+        }
+    }
+    // X operand exact, Y operand an intermediate (possibly split): c += a * b.
+    static __device__ __forceinline__ void mma2(Acc<BS> &c, Frag a, const Frag2 &b)
+    {
+        mma(c, a, b.hi);
+    }
+    // Split a float intermediate for storage in an LDS tile: plane 0 (and 1).
+    static __device__ __forceinline__ void split(float x, float &hi, float &lo)
+    {
+        hi = x;
+        lo = 0.f;
+    }
+};
+
+template <int BS>
+struct Mma<__bf16, BS> {
+    static constexpr int NG = 64 / BS;
+    static constexpr int KT = 8 * NG;
+    static constexpr int GPT = 2;
+    // Intermediates (attention-weight blocks, running states) are fp32 values that
+    // become bf16 MFMA operands.  One bf16 keeps 8 significant bits, which is not
+    // enough next to the exact bf16 inputs they multiply, so each is split into
+    // hi = bf16(x) and lo = bf16(x - hi) (16 bits together) and multiplied twice.
+    static constexpr int PLANES = 2;
+    typedef bf8v Frag;
+    struct Frag2 {
+        Frag hi, lo;
+    };
+    static __device__ __forceinline__ Frag load(const __bf16 *p, int g)
+    {
+        bf4v lo = *reinterpret_cast<const bf4v *>(p + 4 * g);
+        bf4v hi = *reinterpret_cast<const bf4v *>(p + KT / 2 + 4 * g);
+        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return r;
+    }
+    static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v g1)
+    {
+        Frag2 r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            r.hi[e] = (__bf16)g0[e];
+            r.lo[e] = (__bf16)(g0[e] - (float)r.hi[e]);
+            r.hi[4 + e] = (__bf16)g1[e];
+            r.lo[4 + e] = (__bf16)(g1[e] - (float)r.hi[4 + e]);
+        }
+        return r;
+    }
+    static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
+    {
+        if constexpr (BS == 32)
+            c.v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c.v, 0, 0, 0);
+        else
+            c.v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c.v, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void mma2(Acc<BS> &c, Frag a, const Frag2 &b)
+    {
+        mma(c, a, b.hi);
+        mma(c, a, b.lo);
+    }
+    static __device__ __forceinline__ void split(float x, float &hi, float &lo)
+    {
+        hi = (float)(__bf16)x;
+        lo = x - hi;
+    }
+};
+
+// A column of NRB accumulator blocks (NRB*BS rows) seen as a flat list of
+// register groups; group q covers rows [4*NG*q, 4*NG*(q+1)).
+template <int BS, int NRB>
+__device__ __forceinline__ f4v column_group(const Acc<BS> (&col)[NRB], int q)
+{
+    return col[q / Acc<BS>::GROUPS].group(q % Acc<BS>::GROUPS);
+}
+
+// Operand fragment for k-tile kt of a contraction over the rows of `col`.
+template <typename T, int BS, int NRB>
+__device__ __forceinline__ typename Mma<T, BS>::Frag2 column_frag(const Acc<BS> (&col)[NRB],
+                                                                   int kt)
+{
+    typedef Mma<T, BS> M;
+    if constexpr (M::GPT == 1)
+        return M::from_groups(column_group<BS, NRB>(col, kt), f4v{0.f, 0.f, 0.f, 0.f});
+    else
+        return M::from_groups(column_group<BS, NRB>(col, 2 * kt),
+                              column_group<BS, NRB>(col, 2 * kt + 1));
+}
+
+// ---- element helpers -----------------------------------------------------------
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(__bf16 x) { return (float)x; }
+template <typename T>
+__device__ __forceinline__ T from_float(float x)
+{
+    return (T)x;
+}
+
+template <typename T>
+struct Vec4;
+template <>
+struct Vec4<float> {
+    typedef f4v type;
+};
+template <>
+struct Vec4<__bf16> {
+    typedef bf4v type;
+};
+
+}  // namespace la
