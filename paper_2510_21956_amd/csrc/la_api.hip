@@ -34,7 +34,7 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     p.seg_len = (int)seg_len;
     p.nseg = (int)((N + seg_len - 1) / seg_len);
     const size_t DD = (size_t)D * D;
-    p.slot_floats = round_up(is_backward ? 2 * DD + 3 * D : DD + 2 * D, 64);
+    p.slot_floats = round_up(is_backward ? 3 * DD + 3 * D : DD + 2 * D, 64);
     const size_t slots = (size_t)BH * p.nseg * p.slot_floats;
     p.delta_offset_floats = round_up(slots, 64);
     p.total_bytes = is_backward ? (p.delta_offset_floats + round_up((size_t)BH * N, 64)) * 4
@@ -56,11 +56,11 @@ static la_status check_shape(int B, int H, int N, int D, la_dtype dt)
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 
 // LA_PATH=generic forces the plain-ALU kernels (for A/B comparison and debugging).
-static bool use_fast(const Problem &pr)
+static bool use_fast(const Problem &pr, int is_backward)
 {
     const char *env = getenv("LA_PATH");
     if (env && env[0] == 'g') return false;
-    return fast_supported(pr);
+    return fast_supported(pr, is_backward);
 }
 
 }  // namespace la
@@ -106,7 +106,7 @@ la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
     la::Tracer tc(trace, (hipStream_t)hip_stream);
-    if (la::use_fast(pr))
+    if (la::use_fast(pr, 0))
         return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
                                 (hipStream_t)hip_stream, tc);
     return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
@@ -139,6 +139,9 @@ la_status la_backward_traced(const void *Q, const void *K, const void *V, const 
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
     la::Tracer tc(trace, (hipStream_t)hip_stream);
+    if (la::use_fast(pr, 1))
+        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
+                                 (hipStream_t)hip_stream, tc);
     return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
                                 (hipStream_t)hip_stream, tc);
 }

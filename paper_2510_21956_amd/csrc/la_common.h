@@ -36,7 +36,8 @@ __device__ __forceinline__ void store_elem(bf16_t *p, size_t i, float x) { p[i] 
 // A sequence of N rows is cut into `nseg` segments of `seg_len` rows (the last
 // may be shorter).  Each (slice, segment) owns one state slot in the
 // workspace.  A forward slot is [S (D*D) | z (D) | p (D)]; a backward slot is
-// [S (D*D) | z (D) | R (D*D) | u (D) | w (D)], both padded to `slot_floats`.
+// [S (D*D) | z (D) | R (D*D) | u (D) | w (D)] (the matrix-core path stores S
+// transposed and appends R transposed), both padded to `slot_floats`.
 // S = sum k v^T, z = sum k, p = sum v are the running sums of Eq. xy (without
 // the factors a, b); R = sum q OmegaHat^T, u = sum delta q, w = sum OmegaHat
 // are those of Eq. endd.  The backward workspace also holds delta_i =
@@ -86,8 +87,11 @@ struct Tracer {
 void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off, int len, int mode,
                        int lo, int hi, hipStream_t st);
 
-// Matrix-core path (la_fast.hip): D in {64, 128} for fp32, D = 128 for bf16.
-bool fast_supported(const Problem &pr);
+// Matrix-core path (la_fast.hip): fp32 D = 64 (and D = 128 forward only), bf16 D = 128.
+bool fast_supported(const Problem &pr, int is_backward);
+la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                        const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                        void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
 la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                        const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
 

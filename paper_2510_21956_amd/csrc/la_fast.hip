@@ -7,9 +7,10 @@
 // running state, which stays in its accumulator registers for the whole segment
 // and is fed back as an MFMA operand directly (see la_mma.h).
 //
-// The state is kept pre-multiplied as the paper defines it (Eq. xy):
-//   S' = b sum k v^T (= x^(2)),  z' = b sum k (= y^(2)),  p' = a sum v (= x^(1)),
-// by scaling K with b when it is staged into LDS.
+// LDS tiles hold the inputs exactly as given; the coefficients a, b and the
+// row factors 1/g_i are applied in fp32 to accumulators and intermediates, never
+// to a bf16 tile of inputs, so that bf16 I/O loses nothing beyond its own
+// storage rounding.  Intermediates that become bf16 operands are split hi + lo.
 #include "la_common.h"
 #include "la_mma.h"
 
@@ -76,10 +77,12 @@ struct Stager {
     }
 
     // Write the row-major tile [C][LDR] and/or the transposed tile [D][LDT], each
-    // element multiplied by row_scale_lds[row] (nullptr: by `uniform`).
-    template <bool ROWMAJOR, bool TRANSPOSED>
-    __device__ __forceinline__ void store(T *rm, T *tr, float uniform,
-                                          const float *row_scale_lds) const
+    // element multiplied by row_scale_lds[row] (nullptr: by `uniform`).  With
+    // NPL = 2 the transposed tile gets a second plane at tr + tr_plane holding the
+    // part of the scaled value that the first plane's rounding lost.
+    template <bool ROWMAJOR, bool TRANSPOSED, int NPL = 1>
+    __device__ __forceinline__ void store(T *rm, T *tr, float uniform, const float *row_scale_lds,
+                                          int tr_plane = 0) const
     {
         const int dg = threadIdx.x % F::GPR;
         typedef typename Vec4<T>::type V4;
@@ -116,9 +119,17 @@ struct Stager {
                 if constexpr (TRANSPOSED) {
 #pragma unroll
                     for (int e = 0; e < F::EPV; ++e) {
-                        V4 v = {from_float<T>(s0 * elem(u0, e)), from_float<T>(s1 * elem(u1, e)),
-                                from_float<T>(s2 * elem(u2, e)), from_float<T>(s3 * elem(u3, e))};
-                        *reinterpret_cast<V4 *>(tr + (dg * F::EPV + e) * F::LDT + 4 * rq) = v;
+                        const float x0 = s0 * elem(u0, e), x1 = s1 * elem(u1, e),
+                                    x2 = s2 * elem(u2, e), x3 = s3 * elem(u3, e);
+                        V4 v = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2),
+                                from_float<T>(x3)};
+                        T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * rq;
+                        *reinterpret_cast<V4 *>(dst) = v;
+                        if constexpr (NPL == 2) {
+                            V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
+                                     from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
+                            *reinterpret_cast<V4 *>(dst + tr_plane) = vl;
+                        }
                     }
                 }
             }
@@ -206,8 +217,8 @@ __global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, cons
 
 // ---------------------------------------------------------------------------
 // Phase 3 (forward): Eq. fglast / div chunk by chunk.
-//   f = tril(a + b Q_c K_c^T) V_c + 1 p'^T + Q_c S' ;  g = rowsum(tril) + a n + Q_c z'
-//   then S' += (b K_c)^T V_c, z' += sum b k, p' += a sum v
+//   f = tril(a + b Q_c K_c^T) V_c + a 1 p^T + b Q_c S ;  g = rowsum(tril) + a n + b Q_c z
+//   then S += K_c^T V_c, z += sum k, p += sum v
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, const T *__restrict__ K,
@@ -239,7 +250,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
     const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
 
-    // initial state from the scanned slot (unscaled sums), scaled to S', z', p'
+    // initial state from the scanned slot
     const bool zero_init = CAUSAL && seg == 0;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
     Acc<BS> st[NRB];
@@ -247,10 +258,9 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
         for (int i = 0; i < NREG; ++i)
-            st[rb].set(i, zero_init ? 0.f
-                                    : b * slot[(rb * BS + acc_row<BS>(i, g)) * D + w * BS + c]);
-    float p_reg = zero_init ? 0.f : a * slot[D * D + D + w * BS + c];
-    if (t < D) zs[t] = zero_init ? 0.f : b * slot[D * D + t];
+            st[rb].set(i, zero_init ? 0.f : slot[(rb * BS + acc_row<BS>(i, g)) * D + w * BS + c]);
+    float p_reg = zero_init ? 0.f : a * slot[D * D + D + w * BS + c];  // a * p
+    if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
 
     Stager<T, D> sq, sk, sv;
     for (long c0 = row0; c0 < row1; c0 += C) {
@@ -262,12 +272,12 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
         __syncthreads();  // every wave is done with the previous chunk's tiles
         sq.template store<true, false>(Qs, nullptr, 1.f, nullptr);
         if constexpr (CAUSAL) {
-            sk.template store<true, true>(Ks, KTt, b, nullptr);
+            sk.template store<true, true>(Ks, KTt, 1.f, nullptr);
             sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
         }
         __syncthreads();
 
-        // ---- phase A: P = tril(a + (bK) Q^T)^T blocks, q.z', column sums, Q S' ----
+        // ---- phase A: P = tril(a + b K Q^T)^T blocks, q.z, column sums, b Q S ----
         if constexpr (CAUSAL) {
             int pidx = 0;
 #pragma unroll
@@ -290,7 +300,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const int n_loc = acc_row<BS>(4 * q + e, g);
-                            float x = a + pa.get(4 * q + e);
+                            float x = a + b * pa.get(4 * q + e);
                             if (nb == ib && n_loc > c) x = 0.f;
                             rs += x;
                             M::split(x, hi[e], lo[e]);
@@ -327,7 +337,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
         for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
 #pragma unroll
         for (int kt = 0; kt < D / KT; ++kt) {
-            const typename M::Frag2 fb = column_frag<T, BS, NRB>(st, kt);
+            const typename M::Frag2 fb = column_frag<T, BS, NRB>(st, kt, b);
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) {
                 typename M::Frag fa = M::load(Qs + (ib * BS + c) * LDR + kt * KT, g);
@@ -338,7 +348,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
 
         // ---- phase B: denominators, P V, normalise and store, state update ----
         {
-            float gv = qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
+            float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
             if constexpr (CAUSAL) {
                 for (int nb = 0; nb <= l / BS; ++nb) gv += psum[nb][l];
             }
@@ -387,6 +397,539 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
     }
 }
 
+// Write a BS x BS accumulator block, after the caller's element-wise map, into an
+// LDS tile with the block's ROW index contiguous: value of (row r, column c) goes
+// to tile[(col0 + c) * ld + row0 + r].  A lane's four registers of a group are
+// four consecutive rows, so each group is one 4-element vector store.  Values
+// that will be bf16 MFMA operands are split into a hi and a lo plane.
+template <typename T, int BS>
+__device__ __forceinline__ void store_block_rows_contiguous(T *tile, int plane_stride, int ld,
+                                                            int col0, int row0, int c, int g,
+                                                            const float *vals)
+{
+    typedef Mma<T, BS> M;
+    typedef typename Vec4<T>::type V4;
+    constexpr int NREG = BS * BS / 64;
+#pragma unroll
+    for (int q = 0; q < NREG / 4; ++q) {
+        float hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) M::split(vals[4 * q + e], hi[e], lo[e]);
+        T *dst = tile + (col0 + c) * ld + row0 + acc_row<BS>(4 * q, g);
+        V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]),
+                 from_float<T>(hi[3])};
+        *reinterpret_cast<V4 *>(dst) = vh;
+        if constexpr (M::PLANES == 2) {
+            V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
+                     from_float<T>(lo[3])};
+            *reinterpret_cast<V4 *>(dst + plane_stride) = vl;
+        }
+    }
+}
+
+// Fast-path backward slot: [S^T (D*D) | z (D) | R (D*D) | u (D) | w (D) | R^T (D*D)], all
+// unscaled sums: S = sum k v^T, z = sum k, R = sum q OmegaHat^T, u = sum delta q,
+// w = sum OmegaHat (Eq. endd without the factors a, b).
+template <int D>
+struct BwdSlot {
+    static constexpr int ST = 0, Z = D * D, R = D * D + D, U = 2 * D * D + D, W = 2 * D * D + 2 * D,
+                         RT = 2 * D * D + 3 * D, END = 3 * D * D + 3 * D;
+};
+
+// Row sum over the planes of a transposed tile.
+template <typename T, int D, int NPL>
+__device__ __forceinline__ float tile_row_sum_planes(const T *tr, int plane, int r)
+{
+    float s = tile_row_sum<T, D>(tr, r);
+    if constexpr (NPL == 2) s += tile_row_sum<T, D>(tr + plane, r);
+    return s;
+}
+
+// ---------------------------------------------------------------------------
+// Phase 1 (backward): per-segment sums of both directions, and
+// dprime_i = o_i . dO_i  (= g_i delta_i), written to the workspace.
+// ---------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(NT) void kf_bwd_state(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
+    const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
+    float *__restrict__ ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
+    size_t slot_floats, int causal)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    typedef BwdSlot<D> SL;
+    constexpr int BS = F::BS, NRB = F::NRB, KT = F::KT, LDT = F::LDT, NREG = BS * BS / 64;
+    constexpr int PP = M::PLANES, TSZ = D * LDT;
+    __shared__ __align__(16) T QTt[TSZ], OHt[PP * TSZ], KTt[TSZ], VTt[TSZ];
+    __shared__ float rs[C], dl[C];  // 1/g_i and delta_i = dprime_i / g_i
+    const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
+    const size_t base = (size_t)bh * N * D;
+    const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
+    const float *Gp = G + (size_t)bh * N;
+    float *dp = dprime + (size_t)bh * N;
+    const long row0 = (long)seg * seg_len;
+    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+    const bool need_S = causal ? (seg + 1 < nseg) : true;
+    const bool need_R = causal ? (seg > 0) : true;
+
+    Acc<BS> accST[NRB], accR[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        accST[rb].zero();
+        accR[rb].zero();
+    }
+    float vecW = 0.f, vecZ = 0.f, vecU = 0.f;  // t < D: w[t], z[t];  D <= t < 2D: u[t-D]
+
+    Stager<T, D> sq, sk, sv, sdo, so;
+    for (long c0 = row0; c0 < row1; c0 += C) {
+        sq.load(Qp, c0, row1);
+        sdo.load(dOp, c0, row1);
+        so.load(Op, c0, row1);
+        if (need_S) {
+            sk.load(Kp, c0, row1);
+            sv.load(Vp, c0, row1);
+        }
+        __syncthreads();
+        if (t < C) rs[t] = (c0 + t < row1) ? 1.f / Gp[c0 + t] : 0.f;
+        __syncthreads();
+        // o_i . dO_i : partial over this thread's columns, then over the F::GPR
+        // consecutive lanes that share the row
+#pragma unroll
+        for (int ps = 0; ps < F::PASSES; ++ps) {
+            const int rq = t / F::GPR + ps * F::RQP;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < F::EPV; ++e)
+                    s += Stager<T, D>::elem(so.raw[ps][i], e) * Stager<T, D>::elem(sdo.raw[ps][i], e);
+#pragma unroll
+                for (int m = 1; m < F::GPR; m <<= 1) s += __shfl_xor(s, m);
+                if (t % F::GPR == 0 && rq < C / 4) {
+                    const int r = 4 * rq + i;
+                    dl[r] = s * rs[r];
+                    if (c0 + r < row1) dp[c0 + r] = s;
+                }
+            }
+        }
+        sq.template store<false, true>(nullptr, QTt, 1.f, nullptr);
+        sdo.template store<false, true, PP>(nullptr, OHt, 1.f, rs, TSZ);
+        if (need_S) {
+            sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
+            sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
+        }
+        __syncthreads();
+        if (need_R) {
+#pragma unroll
+            for (int kt = 0; kt < C / KT; ++kt) {
+#pragma unroll
+                for (int pl = 0; pl < PP; ++pl) {
+                    typename M::Frag fb = M::load(OHt + pl * TSZ + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                    for (int rb = 0; rb < NRB; ++rb) {
+                        typename M::Frag fa = M::load(QTt + (rb * BS + c) * LDT + kt * KT, g);
+                        M::mma(accR[rb], fa, fb);
+                    }
+                }
+            }
+            if (t < D) {
+                vecW += tile_row_sum_planes<T, D, PP>(OHt, TSZ, t);
+            } else if (t < 2 * D) {
+                float s = 0.f;
+#pragma unroll 8
+                for (int n = 0; n < C; ++n) s += to_float(QTt[(t - D) * LDT + n]) * dl[n];
+                vecU += s;
+            }
+        }
+        if (need_S) {
+#pragma unroll
+            for (int kt = 0; kt < C / KT; ++kt) {
+                typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                for (int jb = 0; jb < NRB; ++jb) {
+                    typename M::Frag fa = M::load(VTt + (jb * BS + c) * LDT + kt * KT, g);
+                    M::mma(accST[jb], fa, fb);
+                }
+            }
+            if (t < D) vecZ += tile_row_sum<T, D>(KTt, t);
+        }
+    }
+    if (need_R) {
+        float *slot = ws + ((size_t)bh * nseg + seg - (causal ? 1 : 0)) * slot_floats;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const int r = rb * BS + acc_row<BS>(i, g), j = w * BS + c;
+                slot[SL::R + r * D + j] = accR[rb].get(i);
+                slot[SL::RT + j * D + r] = accR[rb].get(i);
+            }
+        if (t < D) slot[SL::W + t] = vecW;
+        else if (t < 2 * D) slot[SL::U + (t - D)] = vecU;
+    }
+    if (need_S) {
+        float *slot = ws + ((size_t)bh * nseg + seg + (causal ? 1 : 0)) * slot_floats;
+#pragma unroll
+        for (int jb = 0; jb < NRB; ++jb)
+#pragma unroll
+            for (int i = 0; i < NREG; ++i)
+                slot[SL::ST + (jb * BS + acc_row<BS>(i, g)) * D + w * BS + c] = accST[jb].get(i);
+        if (t < D) slot[SL::Z + t] = vecZ;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Phase 3 (backward), ascending sweep: dQ (Eq. back1).  With dprime_i = o_i . dO_i
+// and Cm'_in = dO_i . v_n - dprime_i (= g_i times the c_in of Eq. bound / b):
+//   dQ_c = diag(b / g) (tril(Cm') K_c + dO_c S^T - dprime z^T)
+//   then S += K_c^T V_c, z += sum k.   The state is held transposed (rows j,
+//   columns r) because this product contracts over j.
+// ---------------------------------------------------------------------------
+template <typename T, int D, bool CAUSAL>
+__global__ __launch_bounds__(NT) void kf_bwd_dq(
+    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ G,
+    const T *__restrict__ dO, T *__restrict__ dQ, const float *__restrict__ ws,
+    const float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    typedef BwdSlot<D> SL;
+    constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
+    constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
+    __shared__ __align__(16) T dOs[C * LDR];
+    __shared__ __align__(16) T Vs[TS * C * LDR + 4];
+    __shared__ __align__(16) T VTt[TS * D * LDT + 4];
+    __shared__ __align__(16) T KTt[TS * D * LDT + 4];
+    __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
+    __shared__ float rs[C], dl[C], csk[D];  // b/g_i, dprime_i, column sums of K
+
+    const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
+    const size_t base = (size_t)bh * N * D;
+    const T *Kp = K + base, *Vp = V + base, *dOp = dO + base;
+    T *dQp = dQ + base;
+    const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
+    const long row0 = (long)seg * seg_len;
+    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+
+    const bool zero_init = CAUSAL && seg == 0;
+    const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
+    Acc<BS> st[NRB];  // S^T: rows j, columns r = w*BS + c
+#pragma unroll
+    for (int jb = 0; jb < NRB; ++jb)
+#pragma unroll
+        for (int i = 0; i < NREG; ++i)
+            st[jb].set(i, zero_init ? 0.f
+                                    : slot[SL::ST + (jb * BS + acc_row<BS>(i, g)) * D + w * BS + c]);
+    float z_reg = zero_init ? 0.f : slot[SL::Z + w * BS + c];
+
+    Stager<T, D> sk, sv, sdo;
+    for (long c0 = row0; c0 < row1; c0 += C) {
+        sdo.load(dOp, c0, row1);
+        if constexpr (CAUSAL) {
+            sk.load(Kp, c0, row1);
+            sv.load(Vp, c0, row1);
+        }
+        __syncthreads();
+        sdo.template store<true, false>(dOs, nullptr, 1.f, nullptr);
+        if constexpr (CAUSAL) {
+            sv.template store<true, true>(Vs, VTt, 1.f, nullptr);
+            sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
+        }
+        if (t < C) {
+            const bool ok = c0 + t < row1;
+            rs[t] = ok ? b / Gp[c0 + t] : 0.f;
+            dl[t] = ok ? dp[c0 + t] : 0.f;
+        }
+        __syncthreads();
+
+        // ---- phase A: Cm' blocks (as Cm'^T: rows n, columns i), column sums, dO S^T ----
+        if constexpr (CAUSAL) {
+            int pidx = 0;
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+                for (int nb = 0; nb <= ib; ++nb, ++pidx) {
+                    if ((pidx & 3) != w) continue;
+                    Acc<BS> pa;
+                    pa.zero();
+#pragma unroll
+                    for (int kt = 0; kt < D / KT; ++kt) {
+                        typename M::Frag fa = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
+                        typename M::Frag fb = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
+                        M::mma(pa, fa, fb);
+                    }
+                    const float di = dl[ib * BS + c];
+                    float vals[NREG];
+#pragma unroll
+                    for (int i = 0; i < NREG; ++i) {
+                        float x = pa.get(i) - di;
+                        if (nb == ib && acc_row<BS>(i, g) > c) x = 0.f;
+                        vals[i] = x;
+                    }
+                    store_block_rows_contiguous<T, BS>(Cms, PSZ, LDT, ib * BS, nb * BS, c, g, vals);
+                }
+            }
+            if (t < D) csk[t] = tile_row_sum<T, D>(KTt, t);
+        }
+        Acc<BS> acc[NB];
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) acc[ib].zero();
+#pragma unroll
+        for (int kt = 0; kt < D / KT; ++kt) {
+            const typename M::Frag2 fb = column_frag<T, BS, NRB>(st, kt, 1.f);
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+                typename M::Frag fa = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
+                M::mma2(acc[ib], fa, fb);
+            }
+        }
+        __syncthreads();
+
+        // ---- phase B: Cm' K, scale and store, state update ----
+        if constexpr (CAUSAL) {
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+                for (int kt = 0; kt < ((ib + 1) * BS) / KT; ++kt) {
+                    typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                    for (int pl = 0; pl < PP; ++pl) {
+                        typename M::Frag fa =
+                            M::load(Cms + pl * PSZ + (ib * BS + c) * LDT + kt * KT, g);
+                        M::mma(acc[ib], fa, fb);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const int r_loc = ib * BS + acc_row<BS>(i, g);
+                const float val = rs[r_loc] * (acc[ib].get(i) - dl[r_loc] * z_reg);
+                if (c0 + r_loc < row1)
+                    dQp[(size_t)(c0 + r_loc) * D + w * BS + c] = from_float<T>(val);
+            }
+        }
+        if constexpr (CAUSAL) {
+#pragma unroll
+            for (int kt = 0; kt < C / KT; ++kt) {
+                typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                for (int jb = 0; jb < NRB; ++jb) {
+                    typename M::Frag fa = M::load(VTt + (jb * BS + c) * LDT + kt * KT, g);
+                    M::mma(st[jb], fa, fb);
+                }
+            }
+            z_reg += csk[w * BS + c];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Phase 3 (backward), descending sweep: dK and dV (Eq. back1 / back2).
+//   dK_c = b (tril(Cm)^T Q_c + V_c R^T - 1 u^T),   Cm_in = (dO_i . v_n - dprime_i) / g_i
+//   dV_c = tril(W)^T OmegaHat_c + a 1 w^T + b K_c R,  W_in = a + b q_i . k_n
+//   then R += Q_c^T OmegaHat_c, u += sum delta q, w += sum OmegaHat.
+// R is held twice: rows r x columns j for dV (contraction over r) and rows j x
+// columns r for dK (contraction over j).
+// ---------------------------------------------------------------------------
+template <typename T, int D, bool CAUSAL>
+__global__ __launch_bounds__(NT) void kf_bwd_dkv(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
+    const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
+    const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
+    size_t slot_floats, float a, float b)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    typedef BwdSlot<D> SL;
+    constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
+    constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
+    constexpr int TSZ = D * LDT;
+    __shared__ __align__(16) T Ks[C * LDR], Vs[C * LDR];
+    __shared__ __align__(16) T Qs[TS * C * LDR + 4], dOs[TS * C * LDR + 4];
+    __shared__ __align__(16) T QTt[TS * TSZ + 4], OHt[TS * PP * TSZ + 4];
+    __shared__ __align__(16) T CmT[TS * PP * PSZ + 4], WT[TS * PP * PSZ + 4];
+    __shared__ float rs[C], dl[C], csu[D], csw[D];  // 1/g_i, dprime_i
+
+    const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
+    const size_t base = (size_t)bh * N * D;
+    const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *dOp = dO + base;
+    T *dKp = dK + base, *dVp = dV + base;
+    const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
+    const long row0 = (long)seg * seg_len;
+    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+
+    const bool zero_init = CAUSAL && seg == nseg - 1;
+    const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
+    Acc<BS> Ra[NRB];  // R  : rows r, columns j = w*BS + c
+    Acc<BS> Rb[NRB];  // R^T: rows j, columns r = w*BS + c
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < NREG; ++i) {
+            const int row = rb * BS + acc_row<BS>(i, g), col = w * BS + c;
+            Ra[rb].set(i, zero_init ? 0.f : slot[SL::R + row * D + col]);
+            Rb[rb].set(i, zero_init ? 0.f : slot[SL::RT + row * D + col]);
+        }
+    float u_reg = zero_init ? 0.f : slot[SL::U + w * BS + c];
+    float w_reg = zero_init ? 0.f : a * slot[SL::W + w * BS + c];  // a * w
+
+    const long nchunks = (row1 - row0 + C - 1) / C;
+    Stager<T, D> sq, sk, sv, sdo;
+    for (long ci = nchunks - 1; ci >= 0; --ci) {
+        const long c0 = row0 + ci * C;
+        sk.load(Kp, c0, row1);
+        sv.load(Vp, c0, row1);
+        if constexpr (CAUSAL) {
+            sq.load(Qp, c0, row1);
+            sdo.load(dOp, c0, row1);
+        }
+        __syncthreads();
+        if constexpr (CAUSAL) {
+            if (t < C) {
+                const bool ok = c0 + t < row1;
+                rs[t] = ok ? 1.f / Gp[c0 + t] : 0.f;
+                dl[t] = ok ? dp[c0 + t] : 0.f;
+            }
+            __syncthreads();
+        }
+        sk.template store<true, false>(Ks, nullptr, 1.f, nullptr);
+        sv.template store<true, false>(Vs, nullptr, 1.f, nullptr);
+        if constexpr (CAUSAL) {
+            sq.template store<true, true>(Qs, QTt, 1.f, nullptr);
+            sdo.template store<true, false>(dOs, nullptr, 1.f, nullptr);
+            sdo.template store<false, true, PP>(nullptr, OHt, 1.f, rs, TSZ);
+        }
+        __syncthreads();
+
+        // ---- phase A: Cm and W blocks (rows i, columns n), column sums, V R^T and b K R ----
+        if constexpr (CAUSAL) {
+            int pidx = 0;
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) {
+#pragma unroll
+                for (int nb = 0; nb <= ib; ++nb, ++pidx) {
+                    if ((pidx & 3) != w) continue;
+                    Acc<BS> pc, pw;
+                    pc.zero();
+                    pw.zero();
+#pragma unroll
+                    for (int kt = 0; kt < D / KT; ++kt) {
+                        typename M::Frag fa = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
+                        typename M::Frag fb = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
+                        M::mma(pc, fa, fb);
+                        fa = M::load(Qs + (ib * BS + c) * LDR + kt * KT, g);
+                        fb = M::load(Ks + (nb * BS + c) * LDR + kt * KT, g);
+                        M::mma(pw, fa, fb);
+                    }
+                    float vc[NREG], vw[NREG];
+#pragma unroll
+                    for (int i = 0; i < NREG; ++i) {
+                        const int i_loc = acc_row<BS>(i, g);  // row i of the block, column n = c
+                        const bool off = (nb == ib && c > i_loc);
+                        vc[i] = off ? 0.f : rs[ib * BS + i_loc] * (pc.get(i) - dl[ib * BS + i_loc]);
+                        vw[i] = off ? 0.f : a + b * pw.get(i);
+                    }
+                    store_block_rows_contiguous<T, BS>(CmT, PSZ, LDT, nb * BS, ib * BS, c, g, vc);
+                    store_block_rows_contiguous<T, BS>(WT, PSZ, LDT, nb * BS, ib * BS, c, g, vw);
+                }
+            }
+            if (t < D) {
+                csw[t] = tile_row_sum_planes<T, D, PP>(OHt, TSZ, t);
+            } else if (t < 2 * D) {
+                float s = 0.f;
+#pragma unroll 8
+                for (int n = 0; n < C; ++n) s += to_float(QTt[(t - D) * LDT + n]) * (dl[n] * rs[n]);
+                csu[t - D] = s;
+            }
+        }
+        Acc<BS> ak[NB], av[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            ak[nb].zero();
+            av[nb].zero();
+        }
+#pragma unroll
+        for (int kt = 0; kt < D / KT; ++kt) {
+            const typename M::Frag2 fbk = column_frag<T, BS, NRB>(Rb, kt, 1.f);
+            const typename M::Frag2 fbv = column_frag<T, BS, NRB>(Ra, kt, b);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                typename M::Frag fa = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
+                M::mma2(ak[nb], fa, fbk);
+                fa = M::load(Ks + (nb * BS + c) * LDR + kt * KT, g);
+                M::mma2(av[nb], fa, fbv);
+            }
+        }
+        __syncthreads();
+
+        // ---- phase B: Cm^T Q and W^T OmegaHat, store, state update ----
+        if constexpr (CAUSAL) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int kt = (nb * BS) / KT; kt < C / KT; ++kt) {
+                    typename M::Frag fq = M::load(QTt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                    for (int pl = 0; pl < PP; ++pl) {
+                        typename M::Frag fa =
+                            M::load(CmT + pl * PSZ + (nb * BS + c) * LDT + kt * KT, g);
+                        M::mma(ak[nb], fa, fq);
+                    }
+                    // both operands are intermediates: hi*hi + hi*lo + lo*hi
+#pragma unroll
+                    for (int po = 0; po < PP; ++po) {
+                        typename M::Frag fo = M::load(OHt + po * TSZ + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                        for (int pl = 0; pl < PP - po; ++pl) {
+                            typename M::Frag fa =
+                                M::load(WT + pl * PSZ + (nb * BS + c) * LDT + kt * KT, g);
+                            M::mma(av[nb], fa, fo);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const int r_loc = nb * BS + acc_row<BS>(i, g);
+                if (c0 + r_loc < row1) {
+                    const size_t o = (size_t)(c0 + r_loc) * D + w * BS + c;
+                    dKp[o] = from_float<T>(b * (ak[nb].get(i) - u_reg));
+                    dVp[o] = from_float<T>(av[nb].get(i) + w_reg);
+                }
+            }
+        }
+        if constexpr (CAUSAL) {
+#pragma unroll
+            for (int kt = 0; kt < C / KT; ++kt) {
+                typename M::Frag fq = M::load(QTt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                for (int pl = 0; pl < PP; ++pl) {
+                    typename M::Frag fo = M::load(OHt + pl * TSZ + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+                    for (int rb = 0; rb < NRB; ++rb) {
+                        typename M::Frag fa = M::load(QTt + (rb * BS + c) * LDT + kt * KT, g);
+                        M::mma(Ra[rb], fa, fo);
+                        fa = M::load(OHt + pl * TSZ + (rb * BS + c) * LDT + kt * KT, g);
+                        M::mma(Rb[rb], fa, fq);
+                    }
+                }
+            }
+            u_reg += csu[w * BS + c];
+            w_reg += a * csw[w * BS + c];
+        }
+    }
+}
+
 inline la_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
@@ -418,12 +961,67 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     return launch_status();
 }
 
+template <typename T, int D>
+la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
+                   const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
+                   void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
+{
+    typedef BwdSlot<D> SL;
+    const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv, *O = (const T *)Ov,
+            *dO = (const T *)dOv;
+    T *dQ = (T *)dQv, *dK = (T *)dKv, *dV = (T *)dVv;
+    const int nseg = pl.nseg;
+    float *delta = ws + pl.delta_offset_floats;
+    const dim3 grid(pr.BH * nseg), block(NT);
+    kf_bwd_state<T, D><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, ws, delta, pr.N, nseg,
+                                               pl.seg_len, pl.slot_floats, pr.causal);
+    tc.mark("bwd_state");
+    if (pr.causal) {
+        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST, 0, 1, nseg - 1,
+                          st);
+        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 1, 0, nseg - 2,
+                          st);
+    } else {
+        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, SL::END, 2, 0, nseg - 1, st);
+    }
+    tc.mark("scan_slots");
+    if (pr.causal) {
+        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, delta, pr.N, nseg,
+                                                      pl.seg_len, pl.slot_floats, pr.b);
+        tc.mark("bwd_dq");
+        kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, delta, pr.N,
+                                                       nseg, pl.seg_len, pl.slot_floats, pr.a,
+                                                       pr.b);
+        tc.mark("bwd_dkv");
+    } else {
+        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, delta, pr.N, nseg,
+                                                       pl.seg_len, pl.slot_floats, pr.b);
+        tc.mark("bwd_dq");
+        kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, delta, pr.N,
+                                                        nseg, pl.seg_len, pl.slot_floats, pr.a,
+                                                        pr.b);
+        tc.mark("bwd_dkv");
+    }
+    return launch_status();
+}
+
 }  // namespace
 
-bool fast_supported(const Problem &pr)
+bool fast_supported(const Problem &pr, int is_backward)
 {
-    if (pr.dt == LA_F32) return pr.D == 64 || pr.D == 128;
+    if (pr.dt == LA_F32) return pr.D == 64 || (pr.D == 128 && !is_backward);
     return pr.D == 128;
+}
+
+la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                        const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                        void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc)
+{
+    if (pr.dt == LA_F32 && pr.D == 64)
+        return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+    if (pr.dt == LA_BF16 && pr.D == 128)
+        return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+    return LA_ERR_UNSUPPORTED;
 }
 
 la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,

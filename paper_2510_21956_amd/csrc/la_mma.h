@@ -172,17 +172,18 @@ __device__ __forceinline__ f4v column_group(const Acc<BS> (&col)[NRB], int q)
     return col[q / Acc<BS>::GROUPS].group(q % Acc<BS>::GROUPS);
 }
 
-// Operand fragment for k-tile kt of a contraction over the rows of `col`.
+// Operand fragment for k-tile kt of a contraction over the rows of `col`, each
+// value multiplied by `scale` in fp32 first.
 template <typename T, int BS, int NRB>
 __device__ __forceinline__ typename Mma<T, BS>::Frag2 column_frag(const Acc<BS> (&col)[NRB],
-                                                                   int kt)
+                                                                   int kt, float scale)
 {
     typedef Mma<T, BS> M;
     if constexpr (M::GPT == 1)
-        return M::from_groups(column_group<BS, NRB>(col, kt), f4v{0.f, 0.f, 0.f, 0.f});
+        return M::from_groups(column_group<BS, NRB>(col, kt) * scale, f4v{0.f, 0.f, 0.f, 0.f});
     else
-        return M::from_groups(column_group<BS, NRB>(col, 2 * kt),
-                              column_group<BS, NRB>(col, 2 * kt + 1));
+        return M::from_groups(column_group<BS, NRB>(col, 2 * kt) * scale,
+                              column_group<BS, NRB>(col, 2 * kt + 1) * scale);
 }
 
 // ---- element helpers -----------------------------------------------------------
