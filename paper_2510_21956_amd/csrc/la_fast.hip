@@ -3,7 +3,7 @@
 // Same chunk algebra and the same three phases as the generic kernels (per-
 // segment sums, scan over segments, apply), with every dense contraction on
 // MFMA.  A workgroup is four waves and handles one (slice, segment) in chunks
-// of C = 64 rows.  Wave w owns columns [w*BS, (w+1)*BS), BS = D/4, of the D x D
+// of C rows (32 for fp32, 64 for bf16).  Wave w owns columns [w*BS, (w+1)*BS), BS = D/4, of the D x D
 // running state, which stays in its accumulator registers for the whole segment
 // and is fed back as an MFMA operand directly (see la_mma.h).
 //
@@ -18,10 +18,14 @@ namespace la {
 namespace {
 
 constexpr int NT = 256;  // threads per workgroup (4 waves)
-constexpr int C = 64;    // chunk rows
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
 template <typename T, int D>
 struct FC {
+    // Chunk rows.  fp32 runs at the fp32 MFMA rate, where the work spent on the
+    // chunk's own C x C blocks counts, and its tiles are twice as large per row
+    // block, so it takes the smaller chunk; bf16 takes the larger.
+    static constexpr int C = sizeof(T) == 4 ? 32 : 64;
     static constexpr int BS = D / 4;
     static constexpr int NG = 64 / BS;
     static constexpr int NB = C / BS;   // row blocks per chunk
@@ -38,7 +42,7 @@ struct FC {
 };
 
 // ---------------------------------------------------------------------------
-// Staging: 64 rows x D of one tensor, global -> registers -> LDS.
+// Staging: C rows x D of one tensor, global -> registers -> LDS.
 // Thread t handles 16-byte column unit dg = t % GPR of rows 4*rq .. 4*rq+3,
 // rq = t / GPR + pass * RQP, so that it can write the transposed tile with
 // 4-element vectors along the row index.
@@ -46,7 +50,8 @@ struct FC {
 template <typename T, int D>
 struct Stager {
     typedef FC<T, D> F;
-    uint4 raw[F::PASSES][4];
+    static constexpr int C = F::C;
+    u4v raw[F::PASSES][4];
 
     __device__ __forceinline__ void load(const T *X, long c0, long row_end)
     {
@@ -57,21 +62,24 @@ struct Stager {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const long r = c0 + 4 * rq + i;
-                uint4 z = {0u, 0u, 0u, 0u};
-                raw[ps][i] = (rq < C / 4 && r < row_end)
-                                 ? *reinterpret_cast<const uint4 *>(X + (size_t)r * D + dg * F::EPV)
-                                 : z;
+                const bool ok = rq < C / 4 && r < row_end;
+                // one 16-byte load per unit; rows past the end read row 0 and are zeroed
+                const u4v *src =
+                    reinterpret_cast<const u4v *>(X + (size_t)(ok ? r : 0) * D + dg * F::EPV);
+                u4v v = *src;
+                if (!ok) v = u4v{0u, 0u, 0u, 0u};
+                raw[ps][i] = v;
             }
         }
     }
 
     // Element e of unit u as a float.
-    static __device__ __forceinline__ float elem(const uint4 &u, int e)
+    static __device__ __forceinline__ float elem(const u4v &u, int e)
     {
         if constexpr (sizeof(T) == 4) {
-            return __uint_as_float(e == 0 ? u.x : e == 1 ? u.y : e == 2 ? u.z : u.w);
+            return __uint_as_float(u[e]);
         } else {
-            const uint32_t wd = (e / 2 == 0) ? u.x : (e / 2 == 1) ? u.y : (e / 2 == 2) ? u.z : u.w;
+            const uint32_t wd = u[e / 2];
             return __uint_as_float((e & 1) ? (wd & 0xffff0000u) : (wd << 16));
         }
     }
@@ -97,7 +105,7 @@ struct Stager {
                     s2 = row_scale_lds[4 * rq + 2];
                     s3 = row_scale_lds[4 * rq + 3];
                 }
-                const uint4 u0 = raw[ps][0], u1 = raw[ps][1], u2 = raw[ps][2], u3 = raw[ps][3];
+                const u4v u0 = raw[ps][0], u1 = raw[ps][1], u2 = raw[ps][2], u3 = raw[ps][3];
                 if constexpr (ROWMAJOR) {
 #pragma unroll
                     for (int h = 0; h < F::EPV / 4; ++h) {
@@ -137,11 +145,12 @@ struct Stager {
     }
 };
 
-// Sum of the 64 entries of row `r` of a transposed tile.
+// Sum of the C entries of row `r` of a transposed tile.
 template <typename T, int D>
 __device__ __forceinline__ float tile_row_sum(const T *tr, int r)
 {
     typedef FC<T, D> F;
+    constexpr int C = F::C;
     typedef typename Vec4<T>::type V4;
     float s = 0.f;
 #pragma unroll
@@ -160,6 +169,138 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
     return x;
 }
 
+// Fragment bundles of one pipeline step.
+template <typename M, int NX>
+struct XsY {
+    typename M::Frag x[NX];
+    typename M::Frag y;
+};
+template <typename M, int NX>
+struct Xs {
+    typename M::Frag x[NX];
+};
+
+// st[rb] += A_rb B^T over the C chunk rows: A = transposed tile `at` (row block rb),
+// B = transposed tile `bt` (rows w*BS + c), both [D][LDT] with the chunk row contiguous.
+// This is the rank-C update of a D x BS column of a running state.
+template <typename T, int D, int BS, int NRB>
+__device__ __forceinline__ void outer_update(Acc<BS> (&st)[NRB], const T *at, const T *bt, int w,
+                                             int c, int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, BS> M;
+    static_assert(BS == F::BS && NRB == F::NRB, "state column shape");
+    constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
+    typedef XsY<M, NRB> B;
+    pipeline<C / KT>(
+        C / KT,
+        [&](int kt) {
+            B b;
+            b.y = M::load(bt + (w * BS + c) * LDT + kt * KT, g);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) b.x[rb] = M::load(at + (rb * BS + c) * LDT + kt * KT, g);
+            return b;
+        },
+        [&](int, const B &b) {
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) M::mma(st[rb], b.x[rb], b.y);
+        });
+}
+
+// acc[m] += X_m col^T-contraction: X = row-major tile `xs` (row block m), the other
+// operand the accumulator-resident state column `col` (scaled), contraction over D.
+template <typename T, int D, int NM, int BS, int NRB>
+__device__ __forceinline__ void state_product(Acc<BS> (&acc)[NM], const T *xs,
+                                              const Acc<BS> (&col)[NRB], float scale, int c, int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, BS> M;
+    static_assert(BS == F::BS && NRB == F::NRB, "state column shape");
+    constexpr int KT = F::KT, LDR = F::LDR;
+    typedef Xs<M, NM> B;
+    pipeline<D / KT>(
+        D / KT,
+        [&](int kt) {
+            B b;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) b.x[m] = M::load(xs + (m * BS + c) * LDR + kt * KT, g);
+            return b;
+        },
+        [&](int kt, const B &b) {
+            const typename M::Frag2 fb = column_frag<T, BS, NRB>(col, kt, scale);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) M::mma2(acc[m], b.x[m], fb);
+        });
+}
+
+// One BS x BS block  X_rows(xr) . Y_rows(yr)^T  of two row-major tiles, contraction over D.
+template <typename T, int D>
+__device__ __forceinline__ void block_product(Acc<D / 4> &acc, const T *xs, int xr,
+                                              const T *ys, int yr, int c, int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    constexpr int KT = F::KT, LDR = F::LDR;
+    typedef XsY<M, 1> B;
+    pipeline<D / KT>(
+        D / KT,
+        [&](int kt) {
+            B b;
+            b.x[0] = M::load(xs + (xr + c) * LDR + kt * KT, g);
+            b.y = M::load(ys + (yr + c) * LDR + kt * KT, g);
+            return b;
+        },
+        [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
+}
+
+// acc += W_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T : W = weight-block tile with PP planes
+// ([C][LDT] each, plane stride psz), Y = transposed tile [D][LDT]; contraction over chunk rows.
+template <typename T, int D>
+__device__ __forceinline__ void weight_product(Acc<D / 4> &acc, const T *wt, int psz,
+                                               int xr, const T *yt, int yr, int kt0, int kt1,
+                                               int c, int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    constexpr int KT = F::KT, LDT = F::LDT, C = F::C, PP = M::PLANES;
+    typedef XsY<M, PP> B;
+    pipeline<C / KT>(
+        kt1 - kt0,
+        [&](int s) {
+            B b;
+            b.y = M::load(yt + (yr + c) * LDT + (kt0 + s) * KT, g);
+#pragma unroll
+            for (int pl = 0; pl < PP; ++pl)
+                b.x[pl] = M::load(wt + pl * psz + (xr + c) * LDT + (kt0 + s) * KT, g);
+            return b;
+        },
+        [&](int, const B &b) {
+#pragma unroll
+            for (int pl = 0; pl < PP; ++pl) M::mma(acc, b.x[pl], b.y);
+        });
+}
+
+// As weight_product, but only the first (hi) plane of W.
+template <typename T, int D>
+__device__ __forceinline__ void weight_product_hi(Acc<D / 4> &acc, const T *wt, int xr,
+                                                  const T *yt, int yr, int kt0, int kt1, int c,
+                                                  int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, F::BS> M;
+    constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
+    typedef XsY<M, 1> B;
+    pipeline<C / KT>(
+        kt1 - kt0,
+        [&](int s) {
+            B b;
+            b.y = M::load(yt + (yr + c) * LDT + (kt0 + s) * KT, g);
+            b.x[0] = M::load(wt + (xr + c) * LDT + (kt0 + s) * KT, g);
+            return b;
+        },
+        [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
+}
+
 // ---------------------------------------------------------------------------
 // Phase 1 (forward): per-segment S = sum k v^T, z = sum k, p = sum v (Eq. xy
 // without the factors), written to state slot `seg + slot_shift`.
@@ -172,6 +313,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, cons
 {
     typedef FC<T, D> F;
     typedef Mma<T, F::BS> M;
+    constexpr int C = F::C;
     __shared__ __align__(16) T KTt[D * F::LDT];
     __shared__ __align__(16) T VTt[D * F::LDT];
     const int bh = blockIdx.x / nseg_run, seg = blockIdx.x % nseg_run;
@@ -186,22 +328,16 @@ __global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, cons
     float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
 
     Stager<T, D> sk, sv;
+    sk.load(Kp, row0, row1);
+    sv.load(Vp, row0, row1);
     for (long c0 = row0; c0 < row1; c0 += C) {
-        sk.load(Kp, c0, row1);
-        sv.load(Vp, c0, row1);
         __syncthreads();
         sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
         sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
         __syncthreads();
-#pragma unroll
-        for (int kt = 0; kt < C / F::KT; ++kt) {
-            typename M::Frag fb = M::load(VTt + (w * F::BS + c) * F::LDT + kt * F::KT, g);
-#pragma unroll
-            for (int rb = 0; rb < F::NRB; ++rb) {
-                typename M::Frag fa = M::load(KTt + (rb * F::BS + c) * F::LDT + kt * F::KT, g);
-                M::mma(st[rb], fa, fb);
-            }
-        }
+        sk.load(Kp, c0 + C, row1);  // next chunk, in flight during the products below
+        sv.load(Vp, c0 + C, row1);
+        outer_update<T, D>(st, KTt, VTt, w, c, g);
         if (t < D) vec += tile_row_sum<T, D>(VTt, t);
         else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
     }
@@ -229,6 +365,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
 {
     typedef FC<T, D> F;
     typedef Mma<T, F::BS> M;
+    constexpr int C = F::C;
     typedef typename Vec4<T>::type V4;
     constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
     constexpr int NREG = BS * BS / 64;
@@ -263,12 +400,12 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
     if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
 
     Stager<T, D> sq, sk, sv;
+    sq.load(Qp, row0, row1);
+    if constexpr (CAUSAL) {
+        sk.load(Kp, row0, row1);
+        sv.load(Vp, row0, row1);
+    }
     for (long c0 = row0; c0 < row1; c0 += C) {
-        sq.load(Qp, c0, row1);
-        if constexpr (CAUSAL) {
-            sk.load(Kp, c0, row1);
-            sv.load(Vp, c0, row1);
-        }
         __syncthreads();  // every wave is done with the previous chunk's tiles
         sq.template store<true, false>(Qs, nullptr, 1.f, nullptr);
         if constexpr (CAUSAL) {
@@ -276,6 +413,11 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
             sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
         }
         __syncthreads();
+        sq.load(Qp, c0 + C, row1);  // next chunk, in flight during this chunk's work
+        if constexpr (CAUSAL) {
+            sk.load(Kp, c0 + C, row1);
+            sv.load(Vp, c0 + C, row1);
+        }
 
         // ---- phase A: P = tril(a + b K Q^T)^T blocks, q.z, column sums, b Q S ----
         if constexpr (CAUSAL) {
@@ -287,12 +429,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
                     if ((pidx & 3) != w) continue;
                     Acc<BS> pa;
                     pa.zero();
-#pragma unroll
-                    for (int kt = 0; kt < D / KT; ++kt) {
-                        typename M::Frag fa = M::load(Ks + (nb * BS + c) * LDR + kt * KT, g);
-                        typename M::Frag fb = M::load(Qs + (ib * BS + c) * LDR + kt * KT, g);
-                        M::mma(pa, fa, fb);
-                    }
+                    block_product<T, D>(pa, Ks, nb * BS, Qs, ib * BS, c, g);
                     float rs = 0.f;
 #pragma unroll
                     for (int q = 0; q < NREG / 4; ++q) {
@@ -323,53 +460,39 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
             else if (t < 2 * D) csk[t - D] = tile_row_sum<T, D>(KTt, t - D);
         }
         {
-            const int i = t / 4, part = t % 4;
+            constexpr int PARTS = NT / C;  // threads per row
+            const int i = t / PARTS, part = t % PARTS;
             float s = 0.f;
 #pragma unroll 8
-            for (int d = part * (D / 4); d < (part + 1) * (D / 4); ++d)
+            for (int d = part * (D / PARTS); d < (part + 1) * (D / PARTS); ++d)
                 s += to_float(Qs[i * LDR + d]) * zs[d];
-            s += __shfl_xor(s, 1);
-            s += __shfl_xor(s, 2);
+#pragma unroll
+            for (int m = 1; m < PARTS; m <<= 1) s += __shfl_xor(s, m);
             if (part == 0) qzs[i] = s;
         }
         Acc<BS> facc[NB];
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
-#pragma unroll
-        for (int kt = 0; kt < D / KT; ++kt) {
-            const typename M::Frag2 fb = column_frag<T, BS, NRB>(st, kt, b);
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-                typename M::Frag fa = M::load(Qs + (ib * BS + c) * LDR + kt * KT, g);
-                M::mma2(facc[ib], fa, fb);
-            }
-        }
+        state_product<T, D>(facc, Qs, st, b, c, g);
         __syncthreads();
 
         // ---- phase B: denominators, P V, normalise and store, state update ----
         {
-            float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
-            if constexpr (CAUSAL) {
-                for (int nb = 0; nb <= l / BS; ++nb) gv += psum[nb][l];
+            if (l < C) {
+                float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
+                if constexpr (CAUSAL) {
+                    for (int nb = 0; nb <= l / BS; ++nb) gv += psum[nb][l];
+                }
+                ginv[w][l] = 1.f / gv;
+                if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
             }
-            ginv[w][l] = 1.f / gv;
-            if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
             __builtin_amdgcn_wave_barrier();
         }
         if constexpr (CAUSAL) {
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-                for (int kt = 0; kt < ((ib + 1) * BS) / KT; ++kt) {
-                    typename M::Frag fb = M::load(VTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                    for (int pl = 0; pl < PP; ++pl) {
-                        typename M::Frag fa =
-                            M::load(Ps + pl * PSZ + (ib * BS + c) * LDT + kt * KT, g);
-                        M::mma(facc[ib], fa, fb);
-                    }
-                }
-            }
+            for (int ib = 0; ib < NB; ++ib)
+                weight_product<T, D>(facc[ib], Ps, PSZ, ib * BS, VTt, w * BS, 0,
+                                     ((ib + 1) * BS) / KT, c, g);
         }
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) {
@@ -382,15 +505,7 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
             }
         }
         if constexpr (CAUSAL) {
-#pragma unroll
-            for (int kt = 0; kt < C / KT; ++kt) {
-                typename M::Frag fb = M::load(VTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                for (int rb = 0; rb < NRB; ++rb) {
-                    typename M::Frag fa = M::load(KTt + (rb * BS + c) * LDT + kt * KT, g);
-                    M::mma(st[rb], fa, fb);
-                }
-            }
+            outer_update<T, D>(st, KTt, VTt, w, c, g);
             p_reg += a * csv[w * BS + c];
             if (t >= D && t < 2 * D) zs[t - D] += csk[t - D];
         }
@@ -458,6 +573,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
 {
     typedef FC<T, D> F;
     typedef Mma<T, F::BS> M;
+    constexpr int C = F::C;
     typedef BwdSlot<D> SL;
     constexpr int BS = F::BS, NRB = F::NRB, KT = F::KT, LDT = F::LDT, NREG = BS * BS / 64;
     constexpr int PP = M::PLANES, TSZ = D * LDT;
@@ -483,16 +599,17 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
     float vecW = 0.f, vecZ = 0.f, vecU = 0.f;  // t < D: w[t], z[t];  D <= t < 2D: u[t-D]
 
     Stager<T, D> sq, sk, sv, sdo, so;
+    sq.load(Qp, row0, row1);
+    sdo.load(dOp, row0, row1);
+    so.load(Op, row0, row1);
+    if (need_S) {
+        sk.load(Kp, row0, row1);
+        sv.load(Vp, row0, row1);
+    }
+    float g_next = (t < C && row0 + t < row1) ? Gp[row0 + t] : 0.f;
     for (long c0 = row0; c0 < row1; c0 += C) {
-        sq.load(Qp, c0, row1);
-        sdo.load(dOp, c0, row1);
-        so.load(Op, c0, row1);
-        if (need_S) {
-            sk.load(Kp, c0, row1);
-            sv.load(Vp, c0, row1);
-        }
         __syncthreads();
-        if (t < C) rs[t] = (c0 + t < row1) ? 1.f / Gp[c0 + t] : 0.f;
+        if (t < C) rs[t] = (c0 + t < row1) ? 1.f / g_next : 0.f;
         __syncthreads();
         // o_i . dO_i : partial over this thread's columns, then over the F::GPR
         // consecutive lanes that share the row
@@ -521,19 +638,17 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
             sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
         }
         __syncthreads();
+        sq.load(Qp, c0 + C, row1);  // next chunk, in flight during the products below
+        sdo.load(dOp, c0 + C, row1);
+        so.load(Op, c0 + C, row1);
+        if (need_S) {
+            sk.load(Kp, c0 + C, row1);
+            sv.load(Vp, c0 + C, row1);
+        }
+        g_next = (t < C && c0 + C + t < row1) ? Gp[c0 + C + t] : 0.f;
         if (need_R) {
 #pragma unroll
-            for (int kt = 0; kt < C / KT; ++kt) {
-#pragma unroll
-                for (int pl = 0; pl < PP; ++pl) {
-                    typename M::Frag fb = M::load(OHt + pl * TSZ + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                    for (int rb = 0; rb < NRB; ++rb) {
-                        typename M::Frag fa = M::load(QTt + (rb * BS + c) * LDT + kt * KT, g);
-                        M::mma(accR[rb], fa, fb);
-                    }
-                }
-            }
+            for (int pl = 0; pl < PP; ++pl) outer_update<T, D>(accR, QTt, OHt + pl * TSZ, w, c, g);
             if (t < D) {
                 vecW += tile_row_sum_planes<T, D, PP>(OHt, TSZ, t);
             } else if (t < 2 * D) {
@@ -544,15 +659,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
             }
         }
         if (need_S) {
-#pragma unroll
-            for (int kt = 0; kt < C / KT; ++kt) {
-                typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                for (int jb = 0; jb < NRB; ++jb) {
-                    typename M::Frag fa = M::load(VTt + (jb * BS + c) * LDT + kt * KT, g);
-                    M::mma(accST[jb], fa, fb);
-                }
-            }
+            outer_update<T, D>(accST, VTt, KTt, w, c, g);
             if (t < D) vecZ += tile_row_sum<T, D>(KTt, t);
         }
     }
@@ -595,6 +702,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
 {
     typedef FC<T, D> F;
     typedef Mma<T, F::BS> M;
+    constexpr int C = F::C;
     typedef BwdSlot<D> SL;
     constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
     constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
@@ -626,12 +734,17 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
     float z_reg = zero_init ? 0.f : slot[SL::Z + w * BS + c];
 
     Stager<T, D> sk, sv, sdo;
+    sdo.load(dOp, row0, row1);
+    if constexpr (CAUSAL) {
+        sk.load(Kp, row0, row1);
+        sv.load(Vp, row0, row1);
+    }
+    float g_next = 1.f, d_next = 0.f;
+    if (t < C && row0 + t < row1) {
+        g_next = Gp[row0 + t];
+        d_next = dp[row0 + t];
+    }
     for (long c0 = row0; c0 < row1; c0 += C) {
-        sdo.load(dOp, c0, row1);
-        if constexpr (CAUSAL) {
-            sk.load(Kp, c0, row1);
-            sv.load(Vp, c0, row1);
-        }
         __syncthreads();
         sdo.template store<true, false>(dOs, nullptr, 1.f, nullptr);
         if constexpr (CAUSAL) {
@@ -640,10 +753,19 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
         }
         if (t < C) {
             const bool ok = c0 + t < row1;
-            rs[t] = ok ? b / Gp[c0 + t] : 0.f;
-            dl[t] = ok ? dp[c0 + t] : 0.f;
+            rs[t] = ok ? b / g_next : 0.f;
+            dl[t] = ok ? d_next : 0.f;
         }
         __syncthreads();
+        sdo.load(dOp, c0 + C, row1);  // next chunk, in flight during this chunk's work
+        if constexpr (CAUSAL) {
+            sk.load(Kp, c0 + C, row1);
+            sv.load(Vp, c0 + C, row1);
+        }
+        if (t < C && c0 + C + t < row1) {
+            g_next = Gp[c0 + C + t];
+            d_next = dp[c0 + C + t];
+        }
 
         // ---- phase A: Cm' blocks (as Cm'^T: rows n, columns i), column sums, dO S^T ----
         if constexpr (CAUSAL) {
@@ -655,12 +777,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
                     if ((pidx & 3) != w) continue;
                     Acc<BS> pa;
                     pa.zero();
-#pragma unroll
-                    for (int kt = 0; kt < D / KT; ++kt) {
-                        typename M::Frag fa = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
-                        typename M::Frag fb = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
-                        M::mma(pa, fa, fb);
-                    }
+                    block_product<T, D>(pa, Vs, nb * BS, dOs, ib * BS, c, g);
                     const float di = dl[ib * BS + c];
                     float vals[NREG];
 #pragma unroll
@@ -677,32 +794,15 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
         Acc<BS> acc[NB];
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) acc[ib].zero();
-#pragma unroll
-        for (int kt = 0; kt < D / KT; ++kt) {
-            const typename M::Frag2 fb = column_frag<T, BS, NRB>(st, kt, 1.f);
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-                typename M::Frag fa = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
-                M::mma2(acc[ib], fa, fb);
-            }
-        }
+        state_product<T, D>(acc, dOs, st, 1.f, c, g);
         __syncthreads();
 
         // ---- phase B: Cm' K, scale and store, state update ----
         if constexpr (CAUSAL) {
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-                for (int kt = 0; kt < ((ib + 1) * BS) / KT; ++kt) {
-                    typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                    for (int pl = 0; pl < PP; ++pl) {
-                        typename M::Frag fa =
-                            M::load(Cms + pl * PSZ + (ib * BS + c) * LDT + kt * KT, g);
-                        M::mma(acc[ib], fa, fb);
-                    }
-                }
-            }
+            for (int ib = 0; ib < NB; ++ib)
+                weight_product<T, D>(acc[ib], Cms, PSZ, ib * BS, KTt, w * BS, 0,
+                                     ((ib + 1) * BS) / KT, c, g);
         }
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) {
@@ -715,15 +815,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
             }
         }
         if constexpr (CAUSAL) {
-#pragma unroll
-            for (int kt = 0; kt < C / KT; ++kt) {
-                typename M::Frag fb = M::load(KTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                for (int jb = 0; jb < NRB; ++jb) {
-                    typename M::Frag fa = M::load(VTt + (jb * BS + c) * LDT + kt * KT, g);
-                    M::mma(st[jb], fa, fb);
-                }
-            }
+            outer_update<T, D>(st, VTt, KTt, w, c, g);
             z_reg += csk[w * BS + c];
         }
     }
@@ -746,6 +838,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
 {
     typedef FC<T, D> F;
     typedef Mma<T, F::BS> M;
+    constexpr int C = F::C;
     typedef BwdSlot<D> SL;
     constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
     constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
@@ -782,20 +875,28 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
 
     const long nchunks = (row1 - row0 + C - 1) / C;
     Stager<T, D> sq, sk, sv, sdo;
+    float g_next = 1.f, d_next = 0.f;
+    {
+        const long cl = row0 + (nchunks - 1) * C;  // the sweep starts at the last chunk
+        sk.load(Kp, cl, row1);
+        sv.load(Vp, cl, row1);
+        if constexpr (CAUSAL) {
+            sq.load(Qp, cl, row1);
+            sdo.load(dOp, cl, row1);
+            if (t < C && cl + t < row1) {
+                g_next = Gp[cl + t];
+                d_next = dp[cl + t];
+            }
+        }
+    }
     for (long ci = nchunks - 1; ci >= 0; --ci) {
         const long c0 = row0 + ci * C;
-        sk.load(Kp, c0, row1);
-        sv.load(Vp, c0, row1);
-        if constexpr (CAUSAL) {
-            sq.load(Qp, c0, row1);
-            sdo.load(dOp, c0, row1);
-        }
         __syncthreads();
         if constexpr (CAUSAL) {
             if (t < C) {
                 const bool ok = c0 + t < row1;
-                rs[t] = ok ? 1.f / Gp[c0 + t] : 0.f;
-                dl[t] = ok ? dp[c0 + t] : 0.f;
+                rs[t] = ok ? 1.f / g_next : 0.f;
+                dl[t] = ok ? d_next : 0.f;
             }
             __syncthreads();
         }
@@ -807,6 +908,21 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
             sdo.template store<false, true, PP>(nullptr, OHt, 1.f, rs, TSZ);
         }
         __syncthreads();
+        {
+            // next chunk of the descending sweep (none after the first chunk of the segment)
+            const long cn = c0 - C;
+            const long end_n = ci > 0 ? row1 : cn;  // end <= start: nothing is loaded
+            sk.load(Kp, cn, end_n);
+            sv.load(Vp, cn, end_n);
+            if constexpr (CAUSAL) {
+                sq.load(Qp, cn, end_n);
+                sdo.load(dOp, cn, end_n);
+                if (t < C && ci > 0) {
+                    g_next = Gp[cn + t];
+                    d_next = dp[cn + t];
+                }
+            }
+        }
 
         // ---- phase A: Cm and W blocks (rows i, columns n), column sums, V R^T and b K R ----
         if constexpr (CAUSAL) {
@@ -819,15 +935,8 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
                     Acc<BS> pc, pw;
                     pc.zero();
                     pw.zero();
-#pragma unroll
-                    for (int kt = 0; kt < D / KT; ++kt) {
-                        typename M::Frag fa = M::load(dOs + (ib * BS + c) * LDR + kt * KT, g);
-                        typename M::Frag fb = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
-                        M::mma(pc, fa, fb);
-                        fa = M::load(Qs + (ib * BS + c) * LDR + kt * KT, g);
-                        fb = M::load(Ks + (nb * BS + c) * LDR + kt * KT, g);
-                        M::mma(pw, fa, fb);
-                    }
+                    block_product<T, D>(pc, dOs, ib * BS, Vs, nb * BS, c, g);
+                    block_product<T, D>(pw, Qs, ib * BS, Ks, nb * BS, c, g);
                     float vc[NREG], vw[NREG];
 #pragma unroll
                     for (int i = 0; i < NREG; ++i) {
@@ -855,45 +964,22 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
             ak[nb].zero();
             av[nb].zero();
         }
-#pragma unroll
-        for (int kt = 0; kt < D / KT; ++kt) {
-            const typename M::Frag2 fbk = column_frag<T, BS, NRB>(Rb, kt, 1.f);
-            const typename M::Frag2 fbv = column_frag<T, BS, NRB>(Ra, kt, b);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                typename M::Frag fa = M::load(Vs + (nb * BS + c) * LDR + kt * KT, g);
-                M::mma2(ak[nb], fa, fbk);
-                fa = M::load(Ks + (nb * BS + c) * LDR + kt * KT, g);
-                M::mma2(av[nb], fa, fbv);
-            }
-        }
+        state_product<T, D>(ak, Vs, Rb, 1.f, c, g);
+        state_product<T, D>(av, Ks, Ra, b, c, g);
         __syncthreads();
 
         // ---- phase B: Cm^T Q and W^T OmegaHat, store, state update ----
         if constexpr (CAUSAL) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-                for (int kt = (nb * BS) / KT; kt < C / KT; ++kt) {
-                    typename M::Frag fq = M::load(QTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                    for (int pl = 0; pl < PP; ++pl) {
-                        typename M::Frag fa =
-                            M::load(CmT + pl * PSZ + (nb * BS + c) * LDT + kt * KT, g);
-                        M::mma(ak[nb], fa, fq);
-                    }
-                    // both operands are intermediates: hi*hi + hi*lo + lo*hi
-#pragma unroll
-                    for (int po = 0; po < PP; ++po) {
-                        typename M::Frag fo = M::load(OHt + po * TSZ + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                        for (int pl = 0; pl < PP - po; ++pl) {
-                            typename M::Frag fa =
-                                M::load(WT + pl * PSZ + (nb * BS + c) * LDT + kt * KT, g);
-                            M::mma(av[nb], fa, fo);
-                        }
-                    }
-                }
+                weight_product<T, D>(ak[nb], CmT, PSZ, nb * BS, QTt, w * BS, (nb * BS) / KT, C / KT,
+                                     c, g);
+                // both operands are intermediates: (hi + lo) * hi, then hi * lo
+                weight_product<T, D>(av[nb], WT, PSZ, nb * BS, OHt, w * BS, (nb * BS) / KT, C / KT,
+                                     c, g);
+                if constexpr (PP == 2)
+                    weight_product_hi<T, D>(av[nb], WT, nb * BS, OHt + TSZ, w * BS, (nb * BS) / KT,
+                                            C / KT, c, g);
             }
         }
 #pragma unroll
@@ -910,19 +996,9 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
         }
         if constexpr (CAUSAL) {
 #pragma unroll
-            for (int kt = 0; kt < C / KT; ++kt) {
-                typename M::Frag fq = M::load(QTt + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                for (int pl = 0; pl < PP; ++pl) {
-                    typename M::Frag fo = M::load(OHt + pl * TSZ + (w * BS + c) * LDT + kt * KT, g);
-#pragma unroll
-                    for (int rb = 0; rb < NRB; ++rb) {
-                        typename M::Frag fa = M::load(QTt + (rb * BS + c) * LDT + kt * KT, g);
-                        M::mma(Ra[rb], fa, fo);
-                        fa = M::load(OHt + pl * TSZ + (rb * BS + c) * LDT + kt * KT, g);
-                        M::mma(Rb[rb], fa, fq);
-                    }
-                }
+            for (int pl = 0; pl < PP; ++pl) {
+                outer_update<T, D>(Ra, QTt, OHt + pl * TSZ, w, c, g);
+                outer_update<T, D>(Rb, OHt + pl * TSZ, QTt, w, c, g);
             }
             u_reg += csu[w * BS + c];
             w_reg += a * csw[w * BS + c];

@@ -186,6 +186,30 @@ __device__ __forceinline__ typename Mma<T, BS>::Frag2 column_frag(const Acc<BS> 
                               column_group<BS, NRB>(col, 2 * kt + 1) * scale);
 }
 
+// Software pipeline over the k-tiles of a product: the fragments of step s+1 are
+// requested from LDS before the MFMAs of step s are issued, so that the LDS
+// latency is covered by matrix work instead of stalling it.
+//   load(s)        -> a bundle of fragments for step s
+//   compute(s, b)  -> the MFMAs of step s on bundle b
+template <int MAXSTEPS, typename LoadFn, typename ComputeFn>
+__device__ __forceinline__ void pipeline(int steps, LoadFn load, ComputeFn compute)
+{
+    if (steps <= 0) return;
+    auto cur = load(0);
+#pragma unroll
+    for (int s = 0; s < MAXSTEPS; ++s) {
+        if (s < steps) {
+            decltype(cur) nxt = cur;
+            if (s + 1 < steps) nxt = load(s + 1);
+            // keep the order written here: next step's LDS reads, then this step's MFMAs
+            __builtin_amdgcn_sched_barrier(0);
+            compute(s, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
+        }
+    }
+}
+
 // ---- element helpers -----------------------------------------------------------
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(__bf16 x) { return (float)x; }
