@@ -112,7 +112,22 @@ def main():
     ap.add_argument("--buffer-sets", type=int, default=0,
                     help="independent input/output sets rotated through (0: enough to exceed "
                          "the 256 MB last-level cache)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark, run a plain 1 GiB device copy a few times "
+                         "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        n = 1 << 28  # 2^28 floats = 1 GiB
+        src = torch.full((n,), 1.0, device="cuda")
+        dst = torch.empty_like(src)
+        flush = torch.empty(1 << 28, device="cuda")
+        for _ in range(5):
+            flush.fill_(0.0)      # push src/dst out of the caches
+            dst.copy_(src)        # the copy kernel of known size: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": 4 * n}))
+        return
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this build has no multi-GPU path "
                  "(run with --gpus 1)")
@@ -183,22 +198,33 @@ def main():
     evf.destroy()
     evb.destroy()
 
-    # Roofline of the dominant kernel.  Algorithmic bytes per token-head of each
-    # step of the path (every operand it needs read once, every result written once):
-    #   forward  apply: Q,K,V in, O out, G out            (4 D e + 4)
-    #   backward apply: Q,K,V,dO in, dQ,dK,dV out, G,delta in   (7 D e + 8)
-    #   forward  state: K,V in                            (2 D e)
-    #   backward state: Q,K,V,O,dO,G in, delta out        (5 D e + 8)
-    alg_bytes = {"fwd_apply": 4 * D * e + 4, "bwd_apply": 7 * D * e + 8, "fwd_state": 2 * D * e,
-                 "bwd_state": 5 * D * e + 8}
+    # Roofline of the dominant kernel.  Algorithmic bytes per token-head of each step
+    # of the path (every operand the step needs read once, every result written once;
+    # G, delta' are one float per token-head):
+    #   fwd_state: K, V in                                   2 D e
+    #   fwd_apply: Q, K, V in; O, G out                      4 D e + 4
+    #   bwd_state: Q, K, V, O, dO, G in; delta' out          5 D e + 8
+    #   bwd_dq   : K, V, dO, G, delta' in; dQ out            4 D e + 8
+    #   bwd_dkv  : Q, K, V, dO, G, delta' in; dK, dV out     6 D e + 8
+    #   (generic path) bwd_apply: Q, K, V, dO, G, delta in; dQ, dK, dV out   7 D e + 8
+    alg_bytes = {"fwd_state": 2 * D * e, "fwd_apply": 4 * D * e + 4, "bwd_state": 5 * D * e + 8,
+                 "bwd_dq": 4 * D * e + 8, "bwd_dkv": 6 * D * e + 8, "bwd_apply": 7 * D * e + 8}
     dom = max(kernels_ms, key=kernels_ms.get)
     dom_key = next((k for k in alg_bytes if dom.endswith(k)), None)
     dom_ms = kernels_ms[dom]
     roofline = None
     if dom_key:
         achieved = alg_bytes[dom_key] * T / (dom_ms * 1e-3) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+            # scaled by a copy kernel of known size (see profiles/)
+            rec = json.load(open(tpath)).get(cfg.name, {}).get(dom.split(":")[1])
+            if rec:
+                traffic = rec["fetch_bytes"] + rec["write_bytes"]
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T}
     pass_bytes = (12 * D * e + 8) * T  # every input once, every output once, forward + backward
     pass_gbs = pass_bytes / (ms_per_step * 1e-3) / 1e9
