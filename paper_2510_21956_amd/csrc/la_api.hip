@@ -9,17 +9,21 @@ static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
 static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128; }
 
-// Segment length: enough workgroups to fill 256 compute units a few times over,
-// but segments long enough that the D*D state a segment hands over stays small
-// next to the rows it covers.  LA_SEG_LEN (rows, rounded up to 64) overrides it.
+// Segment length.  The apply kernels keep one (bf16, or D = 128) or two (fp32, D <= 64)
+// workgroups resident per compute unit, and a workgroup walks its segment serially, so
+// the launch is balanced when slices x segments is about 256 x that residency: every
+// compute unit then gets the same number of equally long segments in a single round.
+// Segments are also kept long enough that the D x D state a segment hands over stays
+// small next to the rows it covers.  LA_SEG_LEN (rows, rounded up to 64) overrides.
 Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
 {
-    (void)dt;
     (void)causal;
     Plan p;
     const long BH = (long)B * H;
     const int min_len = (D >= 128) ? 512 : 256;
-    long want = (768 + BH - 1) / BH;  // segments per slice to reach ~3 workgroups per CU
+    const long resident = (dt == LA_F32 && D <= 64) ? 2 : 1;
+    const long target = 256 * resident;
+    long want = (target + BH / 2) / BH;  // nearest number of segments per slice
     long max_by_len = N / min_len;
     if (max_by_len < 1) max_by_len = 1;
     if (want > max_by_len) want = max_by_len;

@@ -17,6 +17,9 @@
 namespace la {
 namespace {
 
+#ifndef LA_CHUNK_F32_OVERRIDE
+#define LA_CHUNK_F32_OVERRIDE(x) (x)
+#endif
 constexpr int NT = 256;  // threads per workgroup (4 waves)
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
 
@@ -25,7 +28,7 @@ struct FC {
     // Chunk rows.  fp32 runs at the fp32 MFMA rate, where the work spent on the
     // chunk's own C x C blocks counts, and its tiles are twice as large per row
     // block, so it takes the smaller chunk; bf16 takes the larger.
-    static constexpr int C = sizeof(T) == 4 ? 32 : 64;
+    static constexpr int C = LA_CHUNK_F32_OVERRIDE(sizeof(T) == 4 ? 32 : 64);
     static constexpr int BS = D / 4;
     static constexpr int NG = 64 / BS;
     static constexpr int NB = C / BS;   // row blocks per chunk
@@ -327,19 +330,31 @@ __global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, cons
     for (int rb = 0; rb < F::NRB; ++rb) st[rb].zero();
     float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
 
-    Stager<T, D> sk, sv;
-    sk.load(Kp, row0, row1);
-    sv.load(Vp, row0, row1);
-    for (long c0 = row0; c0 < row1; c0 += C) {
-        __syncthreads();
-        sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
-        sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
-        __syncthreads();
-        sk.load(Kp, c0 + C, row1);  // next chunk, in flight during the products below
-        sv.load(Vp, c0 + C, row1);
-        outer_update<T, D>(st, KTt, VTt, w, c, g);
-        if (t < D) vec += tile_row_sum<T, D>(VTt, t);
-        else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
+    // PF chunks are kept in flight.  (Two were measured no faster than one, and cost
+    // registers, so one it is.)
+    constexpr int PF = 1;
+    Stager<T, D> sk[PF], sv[PF];
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+        sk[p].load(Kp, row0 + p * C, row1);
+        sv[p].load(Vp, row0 + p * C, row1);
+    }
+    for (long cb = row0; cb < row1; cb += PF * C) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const long c0 = cb + p * C;
+            if (c0 < row1) {
+                __syncthreads();
+                sk[p].template store<false, true>(nullptr, KTt, 1.f, nullptr);
+                sv[p].template store<false, true>(nullptr, VTt, 1.f, nullptr);
+                __syncthreads();
+                sk[p].load(Kp, c0 + PF * C, row1);
+                sv[p].load(Vp, c0 + PF * C, row1);
+                outer_update<T, D>(st, KTt, VTt, w, c, g);
+                if (t < D) vec += tile_row_sum<T, D>(VTt, t);
+                else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
+            }
+        }
     }
     float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats;
 #pragma unroll
@@ -924,7 +939,7 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
             }
         }
 
-        // ---- phase A: Cm and W blocks (rows i, columns n), column sums, V R^T and b K R ----
+        // ---- phase A: Cm and W blocks (rows i, columns n), column sums ----
         if constexpr (CAUSAL) {
             int pidx = 0;
 #pragma unroll
@@ -958,39 +973,33 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
                 csu[t - D] = s;
             }
         }
-        Acc<BS> ak[NB], av[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            ak[nb].zero();
-            av[nb].zero();
-        }
-        state_product<T, D>(ak, Vs, Rb, 1.f, c, g);
-        state_product<T, D>(av, Ks, Ra, b, c, g);
         __syncthreads();
 
-        // ---- phase B: Cm^T Q and W^T OmegaHat, store, state update ----
-        if constexpr (CAUSAL) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                weight_product<T, D>(ak[nb], CmT, PSZ, nb * BS, QTt, w * BS, (nb * BS) / KT, C / KT,
-                                     c, g);
-                // both operands are intermediates: (hi + lo) * hi, then hi * lo
-                weight_product<T, D>(av[nb], WT, PSZ, nb * BS, OHt, w * BS, (nb * BS) / KT, C / KT,
-                                     c, g);
-                if constexpr (PP == 2)
-                    weight_product_hi<T, D>(av[nb], WT, nb * BS, OHt + TSZ, w * BS, (nb * BS) / KT,
-                                            C / KT, c, g);
-            }
-        }
+        // ---- phase B: per row block: V R^T, b K R, Cm^T Q, W^T OmegaHat; store; state update ----
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
+            Acc<BS> ak[1], av[1];
+            ak[0].zero();
+            av[0].zero();
+            state_product<T, D>(ak, Vs + nb * BS * LDR, Rb, 1.f, c, g);
+            state_product<T, D>(av, Ks + nb * BS * LDR, Ra, b, c, g);
+            if constexpr (CAUSAL) {
+                weight_product<T, D>(ak[0], CmT, PSZ, nb * BS, QTt, w * BS, (nb * BS) / KT, C / KT,
+                                     c, g);
+                // both operands are intermediates: (hi + lo) * hi, then hi * lo
+                weight_product<T, D>(av[0], WT, PSZ, nb * BS, OHt, w * BS, (nb * BS) / KT, C / KT,
+                                     c, g);
+                if constexpr (PP == 2)
+                    weight_product_hi<T, D>(av[0], WT, nb * BS, OHt + TSZ, w * BS, (nb * BS) / KT,
+                                            C / KT, c, g);
+            }
 #pragma unroll
             for (int i = 0; i < NREG; ++i) {
                 const int r_loc = nb * BS + acc_row<BS>(i, g);
                 if (c0 + r_loc < row1) {
                     const size_t o = (size_t)(c0 + r_loc) * D + w * BS + c;
-                    dKp[o] = from_float<T>(b * (ak[nb].get(i) - u_reg));
-                    dVp[o] = from_float<T>(av[nb].get(i) + w_reg);
+                    dKp[o] = from_float<T>(b * (ak[0].get(i) - u_reg));
+                    dVp[o] = from_float<T>(av[0].get(i) + w_reg);
                 }
             }
         }
