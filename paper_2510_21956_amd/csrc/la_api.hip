@@ -9,19 +9,19 @@ static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
 static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128; }
 
-// Segment length.  The apply kernels keep one (bf16, or D = 128) or two (fp32, D <= 64)
-// workgroups resident per compute unit, and a workgroup walks its segment serially, so
-// the launch is balanced when slices x segments is about 256 x that residency: every
-// compute unit then gets the same number of equally long segments in a single round.
+// Segment length.  The masked apply kernels keep one (D = 128) or two (fp32, D = 64)
+// workgroups resident per compute unit (the unmasked ones, which hold no tiles of K and
+// V, four), and a workgroup walks its segment serially, so the launch is balanced when
+// slices x segments is about 256 x that residency: every compute unit then gets the
+// same number of equally long segments in a single round.
 // Segments are also kept long enough that the D x D state a segment hands over stays
 // small next to the rows it covers.  LA_SEG_LEN (rows, rounded up to 64) overrides.
 Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
 {
-    (void)causal;
     Plan p;
     const long BH = (long)B * H;
     const int min_len = (D >= 128) ? 512 : 256;
-    const long resident = (dt == LA_F32 && D <= 64) ? 2 : 1;
+    const long resident = !causal ? 4 : (dt == LA_F32 && D <= 64) ? 2 : 1;
     const long target = 256 * resident;
     long want = (target + BH / 2) / BH;  // nearest number of segments per slice
     long max_by_len = N / min_len;

@@ -2,77 +2,78 @@
 //
 // Same chunk algebra and the same three phases as the generic kernels (per-
 // segment sums, scan over segments, apply), with every dense contraction on
-// MFMA.  A workgroup is four waves and handles one (slice, segment) in chunks
-// of C rows (32 for fp32, 64 for bf16).  Wave w owns columns [w*BS, (w+1)*BS), BS = D/4, of the D x D
-// running state, which stays in its accumulator registers for the whole segment
-// and is fed back as an MFMA operand directly (see la_mma.h).
+// MFMA.  A workgroup handles one (slice, segment) in chunks of C rows (32 for
+// fp32, 64 for bf16).  It has D/16 waves; wave w owns columns [16w, 16w+16) of
+// the D x D running state, which stays in its accumulator registers for the
+// whole segment and is fed back as an MFMA operand directly (see la_mma.h).
 //
 // LDS tiles hold the inputs exactly as given; the coefficients a, b and the
 // row factors 1/g_i are applied in fp32 to accumulators and intermediates, never
 // to a bf16 tile of inputs, so that bf16 I/O loses nothing beyond its own
 // storage rounding.  Intermediates that become bf16 operands are split hi + lo.
+//
+// Output blocks are computed transposed (accumulator rows = output columns), so
+// that a lane ends up with four consecutive columns of one output row and
+// stores them as one vector.
 #include "la_common.h"
 #include "la_mma.h"
 
 namespace la {
 namespace {
 
-#ifndef LA_CHUNK_F32_OVERRIDE
-#define LA_CHUNK_F32_OVERRIDE(x) (x)
-#endif
-constexpr int NT = 256;  // threads per workgroup (4 waves)
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+typedef unsigned int u2v __attribute__((ext_vector_type(2)));
 
 template <typename T, int D>
 struct FC {
     // Chunk rows.  fp32 runs at the fp32 MFMA rate, where the work spent on the
-    // chunk's own C x C blocks counts, and its tiles are twice as large per row
-    // block, so it takes the smaller chunk; bf16 takes the larger.
-    static constexpr int C = LA_CHUNK_F32_OVERRIDE(sizeof(T) == 4 ? 32 : 64);
-    static constexpr int BS = D / 4;
-    static constexpr int NG = 64 / BS;
-    static constexpr int NB = C / BS;   // row blocks per chunk
-    static constexpr int NRB = D / BS;  // row blocks of a state column (= 4)
+    // chunk's own C x C blocks counts, and its tiles are twice as large per row,
+    // so it takes the smaller chunk; bf16 takes the larger.
+    static constexpr int C = sizeof(T) == 4 ? 32 : 64;
+    static constexpr int BS = 16;        // MFMA tile edge = columns owned by a wave
+    static constexpr int NW = D / BS;    // waves per workgroup
+    static constexpr int NT = 64 * NW;   // threads per workgroup
+    static constexpr int NB = C / BS;    // row blocks per chunk
+    static constexpr int NRB = D / BS;   // row blocks of a state column
     static constexpr int KT = Mma<T, BS>::KT;
     static constexpr int LDR = D + 4;  // row-major tile  [C][LDR]
     static constexpr int LDT = C + 4;  // transposed tile [D][LDT]
     static constexpr int EPV = 16 / sizeof(T);  // elements per 16-byte unit
     static constexpr int GPR = D / EPV;         // 16-byte units per row
-    static constexpr int RQP = NT / GPR;        // row quads covered per pass
-    static constexpr int PASSES = ((C / 4) + RQP - 1) / RQP;
-    static_assert(KT <= BS, "k-tile must not span accumulator blocks");
+    static constexpr int HT = NT / 2;           // threads per staging half
+    static_assert(HT / GPR == C / 4, "each half of the workgroup stages one C x D tile");
     static_assert(D % KT == 0 && C % KT == 0, "tile sizes");
+    static_assert(NT >= 2 * D, "vector sums use threads [0, 2D)");
 };
 
 // ---------------------------------------------------------------------------
-// Staging: C rows x D of one tensor, global -> registers -> LDS.
-// Thread t handles 16-byte column unit dg = t % GPR of rows 4*rq .. 4*rq+3,
-// rq = t / GPR + pass * RQP, so that it can write the transposed tile with
+// Staging: C rows x D of one tensor, global -> registers -> LDS, by one half of
+// the workgroup (the other half stages another tensor at the same time).
+// Thread th of the half handles 16-byte column unit dg = th % GPR of rows
+// 4*rq .. 4*rq+3, rq = th / GPR, so that it can write the transposed tile with
 // 4-element vectors along the row index.
 // ---------------------------------------------------------------------------
 template <typename T, int D>
 struct Stager {
     typedef FC<T, D> F;
     static constexpr int C = F::C;
-    u4v raw[F::PASSES][4];
+    u4v raw[4];
 
-    __device__ __forceinline__ void load(const T *X, long c0, long row_end)
+    // `mine`: this thread's half stages this tensor (wave-uniform).
+    __device__ __forceinline__ void load(bool mine, const T *X, long c0, long row_end)
     {
-        const int dg = threadIdx.x % F::GPR;
+        if (!mine) return;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
 #pragma unroll
-        for (int ps = 0; ps < F::PASSES; ++ps) {
-            const int rq = threadIdx.x / F::GPR + ps * F::RQP;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const long r = c0 + 4 * rq + i;
-                const bool ok = rq < C / 4 && r < row_end;
-                // one 16-byte load per unit; rows past the end read row 0 and are zeroed
-                const u4v *src =
-                    reinterpret_cast<const u4v *>(X + (size_t)(ok ? r : 0) * D + dg * F::EPV);
-                u4v v = *src;
-                if (!ok) v = u4v{0u, 0u, 0u, 0u};
-                raw[ps][i] = v;
-            }
+        for (int i = 0; i < 4; ++i) {
+            const long r = c0 + 4 * rq + i;
+            const bool ok = r < row_end;
+            // one 16-byte load per unit; rows past the end read row 0 and are zeroed
+            const u4v *src =
+                reinterpret_cast<const u4v *>(X + (size_t)(ok ? r : 0) * D + dg * F::EPV);
+            u4v v = *src;
+            if (!ok) v = u4v{0u, 0u, 0u, 0u};
+            raw[i] = v;
         }
     }
 
@@ -87,62 +88,62 @@ struct Stager {
         }
     }
 
-    // Write the row-major tile [C][LDR] and/or the transposed tile [D][LDT], each
-    // element multiplied by row_scale_lds[row] (nullptr: by `uniform`).  With
-    // NPL = 2 the transposed tile gets a second plane at tr + tr_plane holding the
-    // part of the scaled value that the first plane's rounding lost.
-    template <bool ROWMAJOR, bool TRANSPOSED, int NPL = 1>
-    __device__ __forceinline__ void store(T *rm, T *tr, float uniform, const float *row_scale_lds,
-                                          int tr_plane = 0) const
+    // Row-major tile [C][LDR]: the units are copied as they are.
+    __device__ __forceinline__ void store_rows(T *rm) const
     {
-        const int dg = threadIdx.x % F::GPR;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            T *dst = rm + (4 * rq + i) * F::LDR + dg * F::EPV;
+            if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<u4v *>(dst) = raw[i];
+            } else {  // rows of a bf16 tile are 8-byte aligned only
+                *reinterpret_cast<u2v *>(dst) = u2v{raw[i][0], raw[i][1]};
+                *reinterpret_cast<u2v *>(dst + 4) = u2v{raw[i][2], raw[i][3]};
+            }
+        }
+    }
+
+    // Transposed tile [D][LDT], unscaled: pure data movement.
+    __device__ __forceinline__ void store_cols(T *tr) const
+    {
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                *reinterpret_cast<u4v *>(tr + (dg * 4 + e) * F::LDT + 4 * rq) =
+                    u4v{raw[0][e], raw[1][e], raw[2][e], raw[3][e]};
+        } else {
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                // word wd of each row holds elements 2wd (low half) and 2wd+1 (high half)
+                const uint32_t r0 = raw[0][wd], r1 = raw[1][wd], r2 = raw[2][wd], r3 = raw[3][wd];
+                const u2v lo = {(r0 & 0xffffu) | (r1 << 16), (r2 & 0xffffu) | (r3 << 16)};
+                const u2v hi = {(r0 >> 16) | (r1 & 0xffff0000u), (r2 >> 16) | (r3 & 0xffff0000u)};
+                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd) * F::LDT + 4 * rq) = lo;
+                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd + 1) * F::LDT + 4 * rq) = hi;
+            }
+        }
+    }
+
+    // Transposed tile with every element multiplied by row_scale[row] in fp32; with
+    // bf16 a second plane at tr + plane holds what the first plane's rounding lost.
+    __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, const float *row_scale) const
+    {
         typedef typename Vec4<T>::type V4;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        const f4v s = *reinterpret_cast<const f4v *>(row_scale + 4 * rq);
 #pragma unroll
-        for (int ps = 0; ps < F::PASSES; ++ps) {
-            const int rq = threadIdx.x / F::GPR + ps * F::RQP;
-            if (rq < C / 4) {
-                float s0 = uniform, s1 = uniform, s2 = uniform, s3 = uniform;
-                if (row_scale_lds) {
-                    s0 = row_scale_lds[4 * rq];
-                    s1 = row_scale_lds[4 * rq + 1];
-                    s2 = row_scale_lds[4 * rq + 2];
-                    s3 = row_scale_lds[4 * rq + 3];
-                }
-                const u4v u0 = raw[ps][0], u1 = raw[ps][1], u2 = raw[ps][2], u3 = raw[ps][3];
-                if constexpr (ROWMAJOR) {
-#pragma unroll
-                    for (int h = 0; h < F::EPV / 4; ++h) {
-                        T *dst = rm + (4 * rq) * F::LDR + dg * F::EPV + 4 * h;
-                        V4 v0 = {from_float<T>(s0 * elem(u0, 4 * h)), from_float<T>(s0 * elem(u0, 4 * h + 1)),
-                                 from_float<T>(s0 * elem(u0, 4 * h + 2)), from_float<T>(s0 * elem(u0, 4 * h + 3))};
-                        V4 v1 = {from_float<T>(s1 * elem(u1, 4 * h)), from_float<T>(s1 * elem(u1, 4 * h + 1)),
-                                 from_float<T>(s1 * elem(u1, 4 * h + 2)), from_float<T>(s1 * elem(u1, 4 * h + 3))};
-                        V4 v2 = {from_float<T>(s2 * elem(u2, 4 * h)), from_float<T>(s2 * elem(u2, 4 * h + 1)),
-                                 from_float<T>(s2 * elem(u2, 4 * h + 2)), from_float<T>(s2 * elem(u2, 4 * h + 3))};
-                        V4 v3 = {from_float<T>(s3 * elem(u3, 4 * h)), from_float<T>(s3 * elem(u3, 4 * h + 1)),
-                                 from_float<T>(s3 * elem(u3, 4 * h + 2)), from_float<T>(s3 * elem(u3, 4 * h + 3))};
-                        *reinterpret_cast<V4 *>(dst) = v0;
-                        *reinterpret_cast<V4 *>(dst + F::LDR) = v1;
-                        *reinterpret_cast<V4 *>(dst + 2 * F::LDR) = v2;
-                        *reinterpret_cast<V4 *>(dst + 3 * F::LDR) = v3;
-                    }
-                }
-                if constexpr (TRANSPOSED) {
-#pragma unroll
-                    for (int e = 0; e < F::EPV; ++e) {
-                        const float x0 = s0 * elem(u0, e), x1 = s1 * elem(u1, e),
-                                    x2 = s2 * elem(u2, e), x3 = s3 * elem(u3, e);
-                        V4 v = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2),
-                                from_float<T>(x3)};
-                        T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * rq;
-                        *reinterpret_cast<V4 *>(dst) = v;
-                        if constexpr (NPL == 2) {
-                            V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
-                                     from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
-                            *reinterpret_cast<V4 *>(dst + tr_plane) = vl;
-                        }
-                    }
-                }
+        for (int e = 0; e < F::EPV; ++e) {
+            const float x0 = s[0] * elem(raw[0], e), x1 = s[1] * elem(raw[1], e),
+                        x2 = s[2] * elem(raw[2], e), x3 = s[3] * elem(raw[3], e);
+            V4 v = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2), from_float<T>(x3)};
+            T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * rq;
+            *reinterpret_cast<V4 *>(dst) = v;
+            if constexpr (Mma<T, F::BS>::PLANES == 2) {
+                V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
+                         from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
+                *reinterpret_cast<V4 *>(dst + plane) = vl;
             }
         }
     }
@@ -153,22 +154,38 @@ template <typename T, int D>
 __device__ __forceinline__ float tile_row_sum(const T *tr, int r)
 {
     typedef FC<T, D> F;
-    constexpr int C = F::C;
     typedef typename Vec4<T>::type V4;
     float s = 0.f;
 #pragma unroll
-    for (int n = 0; n < C; n += 4) {
+    for (int n = 0; n < F::C; n += 4) {
         V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
-        s += to_float(v[0]) + to_float(v[1]) + to_float(v[2]) + to_float(v[3]);
+        s += (to_float(v[0]) + to_float(v[1])) + (to_float(v[2]) + to_float(v[3]));
     }
     return s;
 }
 
-template <int BS>
+// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.
+template <typename T, int D>
+__device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *wgt)
+{
+    typedef FC<T, D> F;
+    typedef typename Vec4<T>::type V4;
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < F::C; n += 4) {
+        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
+        f4v x = *reinterpret_cast<const f4v *>(wgt + n);
+        s += (to_float(v[0]) * x[0] + to_float(v[1]) * x[1]) +
+             (to_float(v[2]) * x[2] + to_float(v[3]) * x[3]);
+    }
+    return s;
+}
+
+// Sum over the four lane groups of a wave (lanes l, l^16, l^32, l^48).
 __device__ __forceinline__ float reduce_lane_groups(float x)
 {
     x += __shfl_xor(x, 32);
-    if constexpr (BS == 16) x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 16);
     return x;
 }
 
@@ -178,71 +195,81 @@ struct XsY {
     typename M::Frag x[NX];
     typename M::Frag y;
 };
-template <typename M, int NX>
-struct Xs {
-    typename M::Frag x[NX];
+template <typename M, int NY>
+struct Ys {
+    typename M::Frag y[NY];
+};
+template <typename M, int NX, int NY>
+struct XsYs {
+    typename M::Frag x[NX], y[NY];
 };
 
+typedef Acc<16> Blk;  // 16 x 16 accumulator block: lane (c, g) holds rows 4g..4g+3 of column c
+
 // st[rb] += A_rb B^T over the C chunk rows: A = transposed tile `at` (row block rb),
-// B = transposed tile `bt` (rows w*BS + c), both [D][LDT] with the chunk row contiguous.
-// This is the rank-C update of a D x BS column of a running state.
-template <typename T, int D, int BS, int NRB>
-__device__ __forceinline__ void outer_update(Acc<BS> (&st)[NRB], const T *at, const T *bt, int w,
+// B = transposed tile `bt` (rows 16w + c), both [D][LDT] with the chunk row contiguous.
+// This is the rank-C update of the 16 columns of a running state that wave w owns.
+template <typename T, int D>
+__device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, const T *bt, int w,
                                              int c, int g)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, BS> M;
-    static_assert(BS == F::BS && NRB == F::NRB, "state column shape");
-    constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
-    typedef XsY<M, NRB> B;
-    pipeline<C / KT>(
-        C / KT,
-        [&](int kt) {
-            B b;
-            b.y = M::load(bt + (w * BS + c) * LDT + kt * KT, g);
+    typedef Mma<T, 16> M;
+    constexpr int NRB = F::NRB, KT = F::KT, LDT = F::LDT, C = F::C;
+    constexpr int GRP = 4;  // row blocks per pass: bounds the fragments held in flight
+    typedef XsY<M, GRP> B;
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) b.x[rb] = M::load(at + (rb * BS + c) * LDT + kt * KT, g);
-            return b;
-        },
-        [&](int, const B &b) {
+    for (int r0 = 0; r0 < NRB; r0 += GRP) {
+        pipeline<C / KT>(
+            C / KT,
+            [&](int kt) {
+                B b;
+                b.y = M::load(bt + (w * 16 + c) * LDT + kt * KT, g);
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) M::mma(st[rb], b.x[rb], b.y);
-        });
+                for (int rb = 0; rb < GRP; ++rb)
+                    b.x[rb] = M::load(at + ((r0 + rb) * 16 + c) * LDT + kt * KT, g);
+                return b;
+            },
+            [&](int, const B &b) {
+#pragma unroll
+                for (int rb = 0; rb < GRP; ++rb) M::mma(st[r0 + rb], b.x[rb], b.y);
+            });
+    }
 }
 
-// acc[m] += X_m col^T-contraction: X = row-major tile `xs` (row block m), the other
-// operand the accumulator-resident state column `col` (scaled), contraction over D.
-template <typename T, int D, int NM, int BS, int NRB>
-__device__ __forceinline__ void state_product(Acc<BS> (&acc)[NM], const T *xs,
-                                              const Acc<BS> (&col)[NRB], float scale, int c, int g)
+// acc[m][j][i] += scale * sum_k col[k][j] * ys[m*16 + i][k]:  rows j = the wave's state
+// columns, columns i = rows of block m of the row-major tile `ys`, contraction over D.
+// col = the accumulator-resident state column.
+template <typename T, int D, int NM>
+__device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D / 16],
+                                              float scale, const T *ys, int c, int g)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, BS> M;
-    static_assert(BS == F::BS && NRB == F::NRB, "state column shape");
-    constexpr int KT = F::KT, LDR = F::LDR;
-    typedef Xs<M, NM> B;
+    typedef Mma<T, 16> M;
+    constexpr int NRB = F::NRB, KT = F::KT, LDR = F::LDR;
+    typedef Ys<M, NM> B;
     pipeline<D / KT>(
         D / KT,
         [&](int kt) {
             B b;
 #pragma unroll
-            for (int m = 0; m < NM; ++m) b.x[m] = M::load(xs + (m * BS + c) * LDR + kt * KT, g);
+            for (int m = 0; m < NM; ++m) b.y[m] = M::load(ys + (m * 16 + c) * LDR + kt * KT, g);
             return b;
         },
         [&](int kt, const B &b) {
-            const typename M::Frag2 fb = column_frag<T, BS, NRB>(col, kt, scale);
+            const typename M::Frag2 fx = column_frag<T, 16, NRB>(col, kt, scale);
 #pragma unroll
-            for (int m = 0; m < NM; ++m) M::mma2(acc[m], b.x[m], fb);
+            for (int m = 0; m < NM; ++m) M::mma2x(acc[m], fx, b.y[m]);
         });
 }
 
-// One BS x BS block  X_rows(xr) . Y_rows(yr)^T  of two row-major tiles, contraction over D.
+// One 16 x 16 block  X_rows(xr) . Y_rows(yr)^T  of two row-major tiles, contraction over D.
 template <typename T, int D>
-__device__ __forceinline__ void block_product(Acc<D / 4> &acc, const T *xs, int xr,
-                                              const T *ys, int yr, int c, int g)
+__device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, const T *ys, int yr,
+                                              int c, int g)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
+    typedef Mma<T, 16> M;
     constexpr int KT = F::KT, LDR = F::LDR;
     typedef XsY<M, 1> B;
     pipeline<D / KT>(
@@ -256,52 +283,81 @@ __device__ __forceinline__ void block_product(Acc<D / 4> &acc, const T *xs, int 
         [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
 }
 
-// acc += W_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T : W = weight-block tile with PP planes
-// ([C][LDT] each, plane stride psz), Y = transposed tile [D][LDT]; contraction over chunk rows.
-template <typename T, int D>
-__device__ __forceinline__ void weight_product(Acc<D / 4> &acc, const T *wt, int psz,
-                                               int xr, const T *yt, int yr, int kt0, int kt1,
-                                               int c, int g)
+// acc += X_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T over chunk rows, where X is a tile with
+// NXP planes (plane stride xps) and Y a tile with NYP planes (plane stride yps), all with
+// leading dimension LDT.  Products of two second planes are dropped.
+template <typename T, int D, int NXP, int NYP>
+__device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, int xr, const T *yt,
+                                              int yps, int yr, int kt0, int kt1, int c, int g)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int KT = F::KT, LDT = F::LDT, C = F::C, PP = M::PLANES;
-    typedef XsY<M, PP> B;
+    typedef Mma<T, 16> M;
+    constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
+    typedef XsYs<M, NXP, NYP> B;
     pipeline<C / KT>(
         kt1 - kt0,
         [&](int s) {
             B b;
-            b.y = M::load(yt + (yr + c) * LDT + (kt0 + s) * KT, g);
 #pragma unroll
-            for (int pl = 0; pl < PP; ++pl)
-                b.x[pl] = M::load(wt + pl * psz + (xr + c) * LDT + (kt0 + s) * KT, g);
+            for (int p = 0; p < NXP; ++p)
+                b.x[p] = M::load(xt + p * xps + (xr + c) * LDT + (kt0 + s) * KT, g);
+#pragma unroll
+            for (int p = 0; p < NYP; ++p)
+                b.y[p] = M::load(yt + p * yps + (yr + c) * LDT + (kt0 + s) * KT, g);
             return b;
         },
         [&](int, const B &b) {
 #pragma unroll
-            for (int pl = 0; pl < PP; ++pl) M::mma(acc, b.x[pl], b.y);
+            for (int p = 0; p < NXP; ++p)
+#pragma unroll
+                for (int q = 0; q < NYP; ++q)
+                    if (p + q < 2) M::mma(acc, b.x[p], b.y[q]);
         });
 }
 
-// As weight_product, but only the first (hi) plane of W.
+// Write a 16 x 16 accumulator block, after the caller's element-wise map, into a weight
+// tile ([C][LDT], PLANES planes) with the block's ROW index contiguous: the value of
+// (row r, column c) goes to tile[(col0 + c) * LDT + row0 + r].  A lane's four registers
+// are four consecutive rows, i.e. one 4-element vector store per plane.
 template <typename T, int D>
-__device__ __forceinline__ void weight_product_hi(Acc<D / 4> &acc, const T *wt, int xr,
-                                                  const T *yt, int yr, int kt0, int kt1, int c,
-                                                  int g)
+__device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0, int row0, int c,
+                                                   int g, const float (&vals)[4])
 {
-    typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
-    typedef XsY<M, 1> B;
-    pipeline<C / KT>(
-        kt1 - kt0,
-        [&](int s) {
-            B b;
-            b.y = M::load(yt + (yr + c) * LDT + (kt0 + s) * KT, g);
-            b.x[0] = M::load(wt + (xr + c) * LDT + (kt0 + s) * KT, g);
-            return b;
-        },
-        [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
+    typedef Mma<T, 16> M;
+    typedef typename Vec4<T>::type V4;
+    float hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) M::split(vals[e], hi[e], lo[e]);
+    T *dst = tile + (col0 + c) * FC<T, D>::LDT + row0 + 4 * g;
+    V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]), from_float<T>(hi[3])};
+    *reinterpret_cast<V4 *>(dst) = vh;
+    if constexpr (M::PLANES == 2) {
+        V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
+                 from_float<T>(lo[3])};
+        *reinterpret_cast<V4 *>(dst + plane) = vl;
+    }
+}
+
+// Store the wave's 16 x 16 output block.  On entry lane (c, g) holds columns col0 + 4g..4g+3
+// of block row c.  Neighbouring lanes would write to different rows, which the memory
+// pipeline cannot merge, so the values are first exchanged between lanes (no memory
+// involved): afterwards lane l holds row l / 4, column quad l % 4, and four neighbouring
+// lanes write one contiguous run of a row.  Rows at or beyond `rows_valid` are skipped.
+template <typename T>
+__device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_valid, int l,
+                                            float x0, float x1, float x2, float x3)
+{
+    const int src = 16 * (l % 4) + l / 4;  // lane that holds (row l/4, column quad l%4)
+    const int row = l / 4, cq = l % 4;
+    if constexpr (sizeof(T) == 4) {
+        f4v v = {__shfl(x0, src), __shfl(x1, src), __shfl(x2, src), __shfl(x3, src)};
+        if (row < rows_valid) *reinterpret_cast<f4v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
+    } else {
+        bf4v p = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2), from_float<T>(x3)};
+        u2v u = *reinterpret_cast<u2v *>(&p);
+        u2v v = {(unsigned)__shfl((int)u[0], src), (unsigned)__shfl((int)u[1], src)};
+        if (row < rows_valid) *reinterpret_cast<u2v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -309,59 +365,42 @@ __device__ __forceinline__ void weight_product_hi(Acc<D / 4> &acc, const T *wt, 
 // without the factors), written to state slot `seg + slot_shift`.
 // ---------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, const T *__restrict__ V,
-                                                   float *__restrict__ ws, int N, int nseg,
-                                                   int nseg_run, int seg_len, size_t slot_floats,
-                                                   int slot_shift)
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_state(
+    const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
+    int nseg_run, int seg_len, size_t slot_floats, int slot_shift)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int C = F::C;
-    __shared__ __align__(16) T KTt[D * F::LDT];
-    __shared__ __align__(16) T VTt[D * F::LDT];
+    constexpr int C = F::C, NRB = F::NRB, LDT = F::LDT;
+    __shared__ __align__(16) T KTt[D * LDT];
+    __shared__ __align__(16) T VTt[D * LDT];
     const int bh = blockIdx.x / nseg_run, seg = blockIdx.x % nseg_run;
     const T *Kp = K + (size_t)bh * N * D, *Vp = V + (size_t)bh * N * D;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % F::BS, g = l / F::BS;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
+    const bool h0 = t < F::HT;
 
-    Acc<F::BS> st[F::NRB];
+    Blk st[NRB];
 #pragma unroll
-    for (int rb = 0; rb < F::NRB; ++rb) st[rb].zero();
+    for (int rb = 0; rb < NRB; ++rb) st[rb].zero();
     float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
 
-    // PF chunks are kept in flight.  (Two were measured no faster than one, and cost
-    // registers, so one it is.)
-    constexpr int PF = 1;
-    Stager<T, D> sk[PF], sv[PF];
-#pragma unroll
-    for (int p = 0; p < PF; ++p) {
-        sk[p].load(Kp, row0 + p * C, row1);
-        sv[p].load(Vp, row0 + p * C, row1);
-    }
-    for (long cb = row0; cb < row1; cb += PF * C) {
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const long c0 = cb + p * C;
-            if (c0 < row1) {
-                __syncthreads();
-                sk[p].template store<false, true>(nullptr, KTt, 1.f, nullptr);
-                sv[p].template store<false, true>(nullptr, VTt, 1.f, nullptr);
-                __syncthreads();
-                sk[p].load(Kp, c0 + PF * C, row1);
-                sv[p].load(Vp, c0 + PF * C, row1);
-                outer_update<T, D>(st, KTt, VTt, w, c, g);
-                if (t < D) vec += tile_row_sum<T, D>(VTt, t);
-                else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
-            }
-        }
+    Stager<T, D> s1;  // half 0: K, half 1: V
+    s1.load(true, h0 ? Kp : Vp, row0, row1);
+    for (long c0 = row0; c0 < row1; c0 += C) {
+        __syncthreads();
+        s1.store_cols(h0 ? KTt : VTt);
+        __syncthreads();
+        s1.load(true, h0 ? Kp : Vp, c0 + C, row1);  // next chunk, in flight during the products
+        outer_update<T, D>(st, KTt, VTt, w, c, g);
+        if (t < D) vec += tile_row_sum<T, D>(VTt, t);
+        else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
     }
     float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats;
 #pragma unroll
-    for (int rb = 0; rb < F::NRB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int i = 0; i < F::BS * F::BS / 64; ++i)
-            slot[(rb * F::BS + acc_row<F::BS>(i, g)) * D + w * F::BS + c] = st[rb].get(i);
+        for (int i = 0; i < 4; ++i) slot[(rb * 16 + 4 * g + i) * D + w * 16 + c] = st[rb].get(i);
     if (t < D) slot[D * D + D + t] = vec;             // p
     else if (t < 2 * D) slot[D * D + (t - D)] = vec;  // z
 }
@@ -372,26 +411,22 @@ __global__ __launch_bounds__(NT) void kf_fwd_state(const T *__restrict__ K, cons
 //   then S += K_c^T V_c, z += sum k, p += sum v
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, const T *__restrict__ K,
-                                                   const T *__restrict__ V, T *__restrict__ O,
-                                                   float *__restrict__ G,
-                                                   const float *__restrict__ ws, int N, int nseg,
-                                                   int seg_len, size_t slot_floats, float a, float b)
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
+    float *__restrict__ G, const float *__restrict__ ws, int N, int nseg, int seg_len,
+    size_t slot_floats, float a, float b)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int C = F::C;
-    typedef typename Vec4<T>::type V4;
-    constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
-    constexpr int NREG = BS * BS / 64;
+    typedef Mma<T, 16> M;
+    constexpr int C = F::C, NW = F::NW, NT = F::NT, NB = F::NB, NRB = F::NRB, KT = F::KT;
+    constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;  // tiles only the masked path needs shrink to nothing
     __shared__ __align__(16) T Qs[C * LDR];
     __shared__ __align__(16) T Ks[TS * C * LDR + 4];
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
     __shared__ __align__(16) T VTt[TS * D * LDT + 4];
-    constexpr int PP = M::PLANES, PSZ = C * LDT;  // weight block tile: hi plane (+ lo plane)
-    __shared__ __align__(16) T Ps[TS * PP * PSZ + 4];
-    __shared__ float psum[NB][C], qzs[C], ginv[4][C], zs[D], csv[D], csk[D];
+    __shared__ __align__(16) T Ps[TS * PP * PSZ + 4];  // weight blocks: hi plane (+ lo plane)
+    __shared__ __align__(16) float psum[NB][C], qzs[C], ginv[NW][C], zs[D], csv[D], csk[D];
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -400,159 +435,120 @@ __global__ __launch_bounds__(NT) void kf_fwd_apply(const T *__restrict__ Q, cons
     float *Gp = G + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
+    const bool h0 = t < F::HT;
 
-    // initial state from the scanned slot
+    // initial state from the scanned slot: S[r][j], j = 16w + c
     const bool zero_init = CAUSAL && seg == 0;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
-    Acc<BS> st[NRB];
+    Blk st[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int i = 0; i < NREG; ++i)
-            st[rb].set(i, zero_init ? 0.f : slot[(rb * BS + acc_row<BS>(i, g)) * D + w * BS + c]);
-    float p_reg = zero_init ? 0.f : a * slot[D * D + D + w * BS + c];  // a * p
+        for (int i = 0; i < 4; ++i)
+            st[rb].set(i, zero_init ? 0.f : slot[(rb * 16 + 4 * g + i) * D + w * 16 + c]);
+    f4v p4 = {0.f, 0.f, 0.f, 0.f};  // a * p[16w + 4g + 0..3]
+    if (!zero_init) p4 = a * *reinterpret_cast<const f4v *>(slot + D * D + D + w * 16 + 4 * g);
     if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
 
-    Stager<T, D> sq, sk, sv;
-    sq.load(Qp, row0, row1);
-    if constexpr (CAUSAL) {
-        sk.load(Kp, row0, row1);
-        sv.load(Vp, row0, row1);
-    }
+    // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
+    Stager<T, D> s1, s2;
+    s1.load(CAUSAL || h0, h0 ? Qp : Kp, row0, row1);
+    if constexpr (CAUSAL) s2.load(h0, Vp, row0, row1);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
-        sq.template store<true, false>(Qs, nullptr, 1.f, nullptr);
-        if constexpr (CAUSAL) {
-            sk.template store<true, true>(Ks, KTt, 1.f, nullptr);
-            sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
+        if (h0) {
+            s1.store_rows(Qs);
+            if constexpr (CAUSAL) s2.store_cols(VTt);
+        } else if constexpr (CAUSAL) {
+            s1.store_rows(Ks);
+            s1.store_cols(KTt);
         }
         __syncthreads();
-        sq.load(Qp, c0 + C, row1);  // next chunk, in flight during this chunk's work
-        if constexpr (CAUSAL) {
-            sk.load(Kp, c0 + C, row1);
-            sv.load(Vp, c0 + C, row1);
-        }
+        s1.load(CAUSAL || h0, h0 ? Qp : Kp, c0 + C, row1);  // next chunk, in flight meanwhile
+        if constexpr (CAUSAL) s2.load(h0, Vp, c0 + C, row1);
 
-        // ---- phase A: P = tril(a + b K Q^T)^T blocks, q.z, column sums, b Q S ----
+        // ---- phase A: weight blocks P = tril(a + b Q K^T), q.z, column sums ----
         if constexpr (CAUSAL) {
             int pidx = 0;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) {
 #pragma unroll
                 for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if ((pidx & 3) != w) continue;
-                    Acc<BS> pa;
+                    if (pidx % NW != w) continue;
+                    Blk pa;  // rows n (block nb), columns i (block ib)
                     pa.zero();
-                    block_product<T, D>(pa, Ks, nb * BS, Qs, ib * BS, c, g);
-                    float rs = 0.f;
+                    block_product<T, D>(pa, Ks, nb * 16, Qs, ib * 16, c, g);
+                    float vals[4], rs = 0.f;
 #pragma unroll
-                    for (int q = 0; q < NREG / 4; ++q) {
-                        float hi[4], lo[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int n_loc = acc_row<BS>(4 * q + e, g);
-                            float x = a + b * pa.get(4 * q + e);
-                            if (nb == ib && n_loc > c) x = 0.f;
-                            rs += x;
-                            M::split(x, hi[e], lo[e]);
-                        }
-                        T *dst = Ps + (ib * BS + c) * LDT + nb * BS + acc_row<BS>(4 * q, g);
-                        V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]),
-                                 from_float<T>(hi[3])};
-                        *reinterpret_cast<V4 *>(dst) = vh;
-                        if constexpr (PP == 2) {
-                            V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]),
-                                     from_float<T>(lo[2]), from_float<T>(lo[3])};
-                            *reinterpret_cast<V4 *>(dst + PSZ) = vl;
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        float x = a + b * pa.get(e);
+                        if (nb == ib && 4 * g + e > c) x = 0.f;
+                        vals[e] = x;
+                        rs += x;
                     }
-                    rs = reduce_lane_groups<BS>(rs);
-                    if (g == 0) psum[nb][ib * BS + c] = rs;
+                    store_weight_block<T, D>(Ps, PSZ, ib * 16, nb * 16, c, g, vals);
+                    if (KT > 16 && nb == ib && ib % 2 == 0) {
+                        // the k-tile of the products below also covers the next block: zeros
+                        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+                        store_weight_block<T, D>(Ps, PSZ, ib * 16, (nb + 1) * 16, c, g, zero);
+                    }
+                    rs = reduce_lane_groups(rs);
+                    if (g == 0) psum[nb][ib * 16 + c] = rs;
                 }
             }
             if (t < D) csv[t] = tile_row_sum<T, D>(VTt, t);
             else if (t < 2 * D) csk[t - D] = tile_row_sum<T, D>(KTt, t - D);
         }
         {
-            constexpr int PARTS = NT / C;  // threads per row
+            typedef typename Vec4<T>::type V4;
+            constexpr int PARTS = NT / C, PER = D / PARTS;  // threads per row, elements per thread
             const int i = t / PARTS, part = t % PARTS;
             float s = 0.f;
-#pragma unroll 8
-            for (int d = part * (D / PARTS); d < (part + 1) * (D / PARTS); ++d)
-                s += to_float(Qs[i * LDR + d]) * zs[d];
+#pragma unroll
+            for (int d = 0; d < PER; d += 4) {
+                V4 qv = *reinterpret_cast<const V4 *>(Qs + i * LDR + part * PER + d);
+                f4v zv = *reinterpret_cast<const f4v *>(zs + part * PER + d);
+                s += (to_float(qv[0]) * zv[0] + to_float(qv[1]) * zv[1]) +
+                     (to_float(qv[2]) * zv[2] + to_float(qv[3]) * zv[3]);
+            }
 #pragma unroll
             for (int m = 1; m < PARTS; m <<= 1) s += __shfl_xor(s, m);
             if (part == 0) qzs[i] = s;
         }
-        Acc<BS> facc[NB];
-#pragma unroll
-        for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
-        state_product<T, D>(facc, Qs, st, b, c, g);
         __syncthreads();
 
-        // ---- phase B: denominators, P V, normalise and store, state update ----
-        {
-            if (l < C) {
-                float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
-                if constexpr (CAUSAL) {
-                    for (int nb = 0; nb <= l / BS; ++nb) gv += psum[nb][l];
-                }
-                ginv[w][l] = 1.f / gv;
-                if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
+        // ---- phase B: denominators; per row block b S^T Q^T + V^T P^T, normalise, store ----
+        if (l < C) {
+            float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
+            if constexpr (CAUSAL) {
+                for (int nb = 0; nb <= l / 16; ++nb) gv += psum[nb][l];
             }
-            __builtin_amdgcn_wave_barrier();
+            ginv[w][l] = 1.f / gv;
+            if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
         }
-        if constexpr (CAUSAL) {
+        __builtin_amdgcn_wave_barrier();
+        {
+            Blk facc[NB];  // rows j = 16w + 4g + e, columns i
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib)
-                weight_product<T, D>(facc[ib], Ps, PSZ, ib * BS, VTt, w * BS, 0,
-                                     ((ib + 1) * BS) / KT, c, g);
-        }
+            for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
+            state_product<T, D, NB>(facc, st, b, Qs, c, g);
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r_loc = ib * BS + acc_row<BS>(i, g);
-                const float val = (facc[ib].get(i) + p_reg) * ginv[w][r_loc];
-                if (c0 + r_loc < row1)
-                    Op[(size_t)(c0 + r_loc) * D + w * BS + c] = from_float<T>(val);
+            for (int ib = 0; ib < NB; ++ib) {
+                if constexpr (CAUSAL)
+                    chunk_product<T, D, 1, PP>(facc[ib], VTt, 0, w * 16, Ps, PSZ, ib * 16, 0,
+                                               ((ib + 1) * 16 + KT - 1) / KT, c, g);
+                const float gi = ginv[w][ib * 16 + c];
+                store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
+                               (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi,
+                               (facc[ib].get(1) + p4[1]) * gi, (facc[ib].get(2) + p4[2]) * gi,
+                               (facc[ib].get(3) + p4[3]) * gi);
             }
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, KTt, VTt, w, c, g);
-            p_reg += a * csv[w * BS + c];
+            p4 += a * *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
             if (t >= D && t < 2 * D) zs[t - D] += csk[t - D];
-        }
-    }
-}
-
-// Write a BS x BS accumulator block, after the caller's element-wise map, into an
-// LDS tile with the block's ROW index contiguous: value of (row r, column c) goes
-// to tile[(col0 + c) * ld + row0 + r].  A lane's four registers of a group are
-// four consecutive rows, so each group is one 4-element vector store.  Values
-// that will be bf16 MFMA operands are split into a hi and a lo plane.
-template <typename T, int BS>
-__device__ __forceinline__ void store_block_rows_contiguous(T *tile, int plane_stride, int ld,
-                                                            int col0, int row0, int c, int g,
-                                                            const float *vals)
-{
-    typedef Mma<T, BS> M;
-    typedef typename Vec4<T>::type V4;
-    constexpr int NREG = BS * BS / 64;
-#pragma unroll
-    for (int q = 0; q < NREG / 4; ++q) {
-        float hi[4], lo[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) M::split(vals[4 * q + e], hi[e], lo[e]);
-        T *dst = tile + (col0 + c) * ld + row0 + acc_row<BS>(4 * q, g);
-        V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]),
-                 from_float<T>(hi[3])};
-        *reinterpret_cast<V4 *>(dst) = vh;
-        if constexpr (M::PLANES == 2) {
-            V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
-                     from_float<T>(lo[3])};
-            *reinterpret_cast<V4 *>(dst + plane_stride) = vl;
         }
     }
 }
@@ -566,34 +562,23 @@ struct BwdSlot {
                          RT = 2 * D * D + 3 * D, END = 3 * D * D + 3 * D;
 };
 
-// Row sum over the planes of a transposed tile.
-template <typename T, int D, int NPL>
-__device__ __forceinline__ float tile_row_sum_planes(const T *tr, int plane, int r)
-{
-    float s = tile_row_sum<T, D>(tr, r);
-    if constexpr (NPL == 2) s += tile_row_sum<T, D>(tr + plane, r);
-    return s;
-}
-
 // ---------------------------------------------------------------------------
 // Phase 1 (backward): per-segment sums of both directions, and
 // dprime_i = o_i . dO_i  (= g_i delta_i), written to the workspace.
 // ---------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(NT) void kf_bwd_state(
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_state(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     float *__restrict__ ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
     size_t slot_floats, int causal)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int C = F::C;
+    typedef Mma<T, 16> M;
     typedef BwdSlot<D> SL;
-    constexpr int BS = F::BS, NRB = F::NRB, KT = F::KT, LDT = F::LDT, NREG = BS * BS / 64;
-    constexpr int PP = M::PLANES, TSZ = D * LDT;
+    constexpr int C = F::C, NRB = F::NRB, LDT = F::LDT, PP = M::PLANES, TSZ = D * LDT;
     __shared__ __align__(16) T QTt[TSZ], OHt[PP * TSZ], KTt[TSZ], VTt[TSZ];
-    __shared__ float rs[C], dl[C];  // 1/g_i and delta_i = dprime_i / g_i
+    __shared__ __align__(16) float rs[C], dl[C];  // 1/g_i and delta_i = dprime_i / g_i
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
@@ -601,11 +586,12 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
     float *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
+    const bool h0 = t < F::HT;
     const bool need_S = causal ? (seg + 1 < nseg) : true;
     const bool need_R = causal ? (seg > 0) : true;
 
-    Acc<BS> accST[NRB], accR[NRB];
+    Blk accST[NRB], accR[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         accST[rb].zero();
@@ -613,64 +599,53 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
     }
     float vecW = 0.f, vecZ = 0.f, vecU = 0.f;  // t < D: w[t], z[t];  D <= t < 2D: u[t-D]
 
-    Stager<T, D> sq, sk, sv, sdo, so;
-    sq.load(Qp, row0, row1);
-    sdo.load(dOp, row0, row1);
-    so.load(Op, row0, row1);
-    if (need_S) {
-        sk.load(Kp, row0, row1);
-        sv.load(Vp, row0, row1);
-    }
+    // staging: half 0: dO, O (for dprime), Q; half 1: K, V
+    Stager<T, D> s1, s2, s3;
+    s1.load(h0 || need_S, h0 ? dOp : Kp, row0, row1);
+    s2.load(h0 || need_S, h0 ? Op : Vp, row0, row1);
+    s3.load(h0, Qp, row0, row1);
     float g_next = (t < C && row0 + t < row1) ? Gp[row0 + t] : 0.f;
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         if (t < C) rs[t] = (c0 + t < row1) ? 1.f / g_next : 0.f;
         __syncthreads();
-        // o_i . dO_i : partial over this thread's columns, then over the F::GPR
-        // consecutive lanes that share the row
-#pragma unroll
-        for (int ps = 0; ps < F::PASSES; ++ps) {
-            const int rq = t / F::GPR + ps * F::RQP;
+        if (h0) {
+            // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
+            // lanes that share the row
+            const int th = t % F::HT, rq = th / F::GPR;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float s = 0.f;
 #pragma unroll
                 for (int e = 0; e < F::EPV; ++e)
-                    s += Stager<T, D>::elem(so.raw[ps][i], e) * Stager<T, D>::elem(sdo.raw[ps][i], e);
+                    s += Stager<T, D>::elem(s2.raw[i], e) * Stager<T, D>::elem(s1.raw[i], e);
 #pragma unroll
                 for (int m = 1; m < F::GPR; m <<= 1) s += __shfl_xor(s, m);
-                if (t % F::GPR == 0 && rq < C / 4) {
+                if (th % F::GPR == 0) {
                     const int r = 4 * rq + i;
                     dl[r] = s * rs[r];
                     if (c0 + r < row1) dp[c0 + r] = s;
                 }
             }
-        }
-        sq.template store<false, true>(nullptr, QTt, 1.f, nullptr);
-        sdo.template store<false, true, PP>(nullptr, OHt, 1.f, rs, TSZ);
-        if (need_S) {
-            sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
-            sv.template store<false, true>(nullptr, VTt, 1.f, nullptr);
+            s1.store_cols_scaled(OHt, TSZ, rs);
+            s3.store_cols(QTt);
+        } else if (need_S) {
+            s1.store_cols(KTt);
+            s2.store_cols(VTt);
         }
         __syncthreads();
-        sq.load(Qp, c0 + C, row1);  // next chunk, in flight during the products below
-        sdo.load(dOp, c0 + C, row1);
-        so.load(Op, c0 + C, row1);
-        if (need_S) {
-            sk.load(Kp, c0 + C, row1);
-            sv.load(Vp, c0 + C, row1);
-        }
+        s1.load(h0 || need_S, h0 ? dOp : Kp, c0 + C, row1);  // next chunk, in flight meanwhile
+        s2.load(h0 || need_S, h0 ? Op : Vp, c0 + C, row1);
+        s3.load(h0, Qp, c0 + C, row1);
         g_next = (t < C && c0 + C + t < row1) ? Gp[c0 + C + t] : 0.f;
         if (need_R) {
 #pragma unroll
             for (int pl = 0; pl < PP; ++pl) outer_update<T, D>(accR, QTt, OHt + pl * TSZ, w, c, g);
             if (t < D) {
-                vecW += tile_row_sum_planes<T, D, PP>(OHt, TSZ, t);
+                vecW += tile_row_sum<T, D>(OHt, t);
+                if constexpr (PP == 2) vecW += tile_row_sum<T, D>(OHt + TSZ, t);
             } else if (t < 2 * D) {
-                float s = 0.f;
-#pragma unroll 8
-                for (int n = 0; n < C; ++n) s += to_float(QTt[(t - D) * LDT + n]) * dl[n];
-                vecU += s;
+                vecU += tile_row_dot<T, D>(QTt, t - D, dl);
             }
         }
         if (need_S) {
@@ -683,8 +658,8 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r = rb * BS + acc_row<BS>(i, g), j = w * BS + c;
+            for (int i = 0; i < 4; ++i) {
+                const int r = rb * 16 + 4 * g + i, j = w * 16 + c;
                 slot[SL::R + r * D + j] = accR[rb].get(i);
                 slot[SL::RT + j * D + r] = accR[rb].get(i);
             }
@@ -696,8 +671,8 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
 #pragma unroll
         for (int jb = 0; jb < NRB; ++jb)
 #pragma unroll
-            for (int i = 0; i < NREG; ++i)
-                slot[SL::ST + (jb * BS + acc_row<BS>(i, g)) * D + w * BS + c] = accST[jb].get(i);
+            for (int i = 0; i < 4; ++i)
+                slot[SL::ST + (jb * 16 + 4 * g + i) * D + w * 16 + c] = accST[jb].get(i);
         if (t < D) slot[SL::Z + t] = vecZ;
     }
 }
@@ -710,23 +685,23 @@ __global__ __launch_bounds__(NT) void kf_bwd_state(
 //   columns r) because this product contracts over j.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void kf_bwd_dq(
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
     const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ G,
     const T *__restrict__ dO, T *__restrict__ dQ, const float *__restrict__ ws,
     const float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int C = F::C;
+    typedef Mma<T, 16> M;
     typedef BwdSlot<D> SL;
-    constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
-    constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
+    constexpr int C = F::C, NW = F::NW, NB = F::NB, NRB = F::NRB, KT = F::KT;
+    constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
+    constexpr int TS = CAUSAL ? 1 : 0;
     __shared__ __align__(16) T dOs[C * LDR];
     __shared__ __align__(16) T Vs[TS * C * LDR + 4];
     __shared__ __align__(16) T VTt[TS * D * LDT + 4];
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
     __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
-    __shared__ float rs[C], dl[C], csk[D];  // b/g_i, dprime_i, column sums of K
+    __shared__ __align__(16) float rs[C], dl[C], csk[D];  // b/g_i, dprime_i, column sums of K
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -735,25 +710,24 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
+    const bool h0 = t < F::HT;
 
     const bool zero_init = CAUSAL && seg == 0;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
-    Acc<BS> st[NRB];  // S^T: rows j, columns r = w*BS + c
+    Blk st[NRB];  // S^T: rows j, columns r = 16w + c
 #pragma unroll
     for (int jb = 0; jb < NRB; ++jb)
 #pragma unroll
-        for (int i = 0; i < NREG; ++i)
-            st[jb].set(i, zero_init ? 0.f
-                                    : slot[SL::ST + (jb * BS + acc_row<BS>(i, g)) * D + w * BS + c]);
-    float z_reg = zero_init ? 0.f : slot[SL::Z + w * BS + c];
+        for (int i = 0; i < 4; ++i)
+            st[jb].set(i, zero_init ? 0.f : slot[SL::ST + (jb * 16 + 4 * g + i) * D + w * 16 + c]);
+    f4v z4 = {0.f, 0.f, 0.f, 0.f};  // z[16w + 4g + 0..3]
+    if (!zero_init) z4 = *reinterpret_cast<const f4v *>(slot + SL::Z + w * 16 + 4 * g);
 
-    Stager<T, D> sk, sv, sdo;
-    sdo.load(dOp, row0, row1);
-    if constexpr (CAUSAL) {
-        sk.load(Kp, row0, row1);
-        sv.load(Vp, row0, row1);
-    }
+    // staging: half 0: dO (rows) then K (columns); half 1: V (rows and columns)
+    Stager<T, D> s1, s2;
+    s1.load(CAUSAL || h0, h0 ? dOp : Vp, row0, row1);
+    if constexpr (CAUSAL) s2.load(h0, Kp, row0, row1);
     float g_next = 1.f, d_next = 0.f;
     if (t < C && row0 + t < row1) {
         g_next = Gp[row0 + t];
@@ -761,10 +735,12 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
     }
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
-        sdo.template store<true, false>(dOs, nullptr, 1.f, nullptr);
-        if constexpr (CAUSAL) {
-            sv.template store<true, true>(Vs, VTt, 1.f, nullptr);
-            sk.template store<false, true>(nullptr, KTt, 1.f, nullptr);
+        if (h0) {
+            s1.store_rows(dOs);
+            if constexpr (CAUSAL) s2.store_cols(KTt);
+        } else if constexpr (CAUSAL) {
+            s1.store_rows(Vs);
+            s1.store_cols(VTt);
         }
         if (t < C) {
             const bool ok = c0 + t < row1;
@@ -772,66 +748,65 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
             dl[t] = ok ? d_next : 0.f;
         }
         __syncthreads();
-        sdo.load(dOp, c0 + C, row1);  // next chunk, in flight during this chunk's work
-        if constexpr (CAUSAL) {
-            sk.load(Kp, c0 + C, row1);
-            sv.load(Vp, c0 + C, row1);
-        }
+        s1.load(CAUSAL || h0, h0 ? dOp : Vp, c0 + C, row1);  // next chunk, in flight meanwhile
+        if constexpr (CAUSAL) s2.load(h0, Kp, c0 + C, row1);
         if (t < C && c0 + C + t < row1) {
             g_next = Gp[c0 + C + t];
             d_next = dp[c0 + C + t];
         }
 
-        // ---- phase A: Cm' blocks (as Cm'^T: rows n, columns i), column sums, dO S^T ----
+        // ---- phase A: weight blocks Cm' (rows n, columns i), column sums of K ----
         if constexpr (CAUSAL) {
             int pidx = 0;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) {
 #pragma unroll
                 for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if ((pidx & 3) != w) continue;
-                    Acc<BS> pa;
+                    if (pidx % NW != w) continue;
+                    Blk pa;
                     pa.zero();
-                    block_product<T, D>(pa, Vs, nb * BS, dOs, ib * BS, c, g);
-                    const float di = dl[ib * BS + c];
-                    float vals[NREG];
+                    block_product<T, D>(pa, Vs, nb * 16, dOs, ib * 16, c, g);
+                    const float di = dl[ib * 16 + c];
+                    float vals[4];
 #pragma unroll
-                    for (int i = 0; i < NREG; ++i) {
-                        float x = pa.get(i) - di;
-                        if (nb == ib && acc_row<BS>(i, g) > c) x = 0.f;
-                        vals[i] = x;
+                    for (int e = 0; e < 4; ++e) {
+                        float x = pa.get(e) - di;
+                        if (nb == ib && 4 * g + e > c) x = 0.f;
+                        vals[e] = x;
                     }
-                    store_block_rows_contiguous<T, BS>(Cms, PSZ, LDT, ib * BS, nb * BS, c, g, vals);
+                    store_weight_block<T, D>(Cms, PSZ, ib * 16, nb * 16, c, g, vals);
+                    if (KT > 16 && nb == ib && ib % 2 == 0) {
+                        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+                        store_weight_block<T, D>(Cms, PSZ, ib * 16, (nb + 1) * 16, c, g, zero);
+                    }
                 }
             }
             if (t < D) csk[t] = tile_row_sum<T, D>(KTt, t);
+            __syncthreads();
         }
-        Acc<BS> acc[NB];
-#pragma unroll
-        for (int ib = 0; ib < NB; ++ib) acc[ib].zero();
-        state_product<T, D>(acc, dOs, st, 1.f, c, g);
-        __syncthreads();
 
-        // ---- phase B: Cm' K, scale and store, state update ----
-        if constexpr (CAUSAL) {
+        // ---- phase B: per row block S dO^T + K^T Cm'^T (rows r, columns i), scale, store ----
+        {
+            Blk acc[NB];
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib)
-                weight_product<T, D>(acc[ib], Cms, PSZ, ib * BS, KTt, w * BS, 0,
-                                     ((ib + 1) * BS) / KT, c, g);
-        }
+            for (int ib = 0; ib < NB; ++ib) acc[ib].zero();
+            state_product<T, D, NB>(acc, st, 1.f, dOs, c, g);
 #pragma unroll
-        for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r_loc = ib * BS + acc_row<BS>(i, g);
-                const float val = rs[r_loc] * (acc[ib].get(i) - dl[r_loc] * z_reg);
-                if (c0 + r_loc < row1)
-                    dQp[(size_t)(c0 + r_loc) * D + w * BS + c] = from_float<T>(val);
+            for (int ib = 0; ib < NB; ++ib) {
+                if constexpr (CAUSAL)
+                    chunk_product<T, D, 1, PP>(acc[ib], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
+                                               ((ib + 1) * 16 + KT - 1) / KT, c, g);
+                const int r_loc = ib * 16 + c;
+                const float sc = rs[r_loc], di = dl[r_loc];
+                store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
+                               (int)(row1 - c0) - ib * 16, l, sc * (acc[ib].get(0) - di * z4[0]),
+                               sc * (acc[ib].get(1) - di * z4[1]), sc * (acc[ib].get(2) - di * z4[2]),
+                               sc * (acc[ib].get(3) - di * z4[3]));
             }
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, VTt, KTt, w, c, g);
-            z_reg += csk[w * BS + c];
+            z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
     }
 }
@@ -845,24 +820,23 @@ __global__ __launch_bounds__(NT) void kf_bwd_dq(
 // columns r for dK (contraction over j).
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void kf_bwd_dkv(
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
     size_t slot_floats, float a, float b)
 {
     typedef FC<T, D> F;
-    typedef Mma<T, F::BS> M;
-    constexpr int C = F::C;
+    typedef Mma<T, 16> M;
     typedef BwdSlot<D> SL;
-    constexpr int BS = F::BS, NB = F::NB, NRB = F::NRB, KT = F::KT, LDR = F::LDR, LDT = F::LDT;
-    constexpr int NREG = BS * BS / 64, TS = CAUSAL ? 1 : 0, PP = M::PLANES, PSZ = C * LDT;
-    constexpr int TSZ = D * LDT;
+    constexpr int C = F::C, NW = F::NW, NB = F::NB, NRB = F::NRB, KT = F::KT;
+    constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT, TSZ = D * LDT;
+    constexpr int TS = CAUSAL ? 1 : 0;
     __shared__ __align__(16) T Ks[C * LDR], Vs[C * LDR];
     __shared__ __align__(16) T Qs[TS * C * LDR + 4], dOs[TS * C * LDR + 4];
     __shared__ __align__(16) T QTt[TS * TSZ + 4], OHt[TS * PP * TSZ + 4];
     __shared__ __align__(16) T CmT[TS * PP * PSZ + 4], WT[TS * PP * PSZ + 4];
-    __shared__ float rs[C], dl[C], csu[D], csw[D];  // 1/g_i, dprime_i
+    __shared__ __align__(16) float rs[C], dl[C], dls[C], csu[D], csw[D];  // 1/g, dprime, delta
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -871,37 +845,38 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % BS, g = l / BS;
+    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
+    const bool h0 = t < F::HT;
 
     const bool zero_init = CAUSAL && seg == nseg - 1;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
-    Acc<BS> Ra[NRB];  // R  : rows r, columns j = w*BS + c
-    Acc<BS> Rb[NRB];  // R^T: rows j, columns r = w*BS + c
+    Blk Ra[NRB];  // R  : rows r, columns j = 16w + c
+    Blk Rb[NRB];  // R^T: rows j, columns r = 16w + c
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int i = 0; i < NREG; ++i) {
-            const int row = rb * BS + acc_row<BS>(i, g), col = w * BS + c;
+        for (int i = 0; i < 4; ++i) {
+            const int row = rb * 16 + 4 * g + i, col = w * 16 + c;
             Ra[rb].set(i, zero_init ? 0.f : slot[SL::R + row * D + col]);
             Rb[rb].set(i, zero_init ? 0.f : slot[SL::RT + row * D + col]);
         }
-    float u_reg = zero_init ? 0.f : slot[SL::U + w * BS + c];
-    float w_reg = zero_init ? 0.f : a * slot[SL::W + w * BS + c];  // a * w
+    f4v u4 = {0.f, 0.f, 0.f, 0.f}, w4 = {0.f, 0.f, 0.f, 0.f};  // u[16w+4g+e], a * w[16w+4g+e]
+    if (!zero_init) {
+        u4 = *reinterpret_cast<const f4v *>(slot + SL::U + w * 16 + 4 * g);
+        w4 = a * *reinterpret_cast<const f4v *>(slot + SL::W + w * 16 + 4 * g);
+    }
 
+    // staging: half 0: K (rows), V (rows); half 1: Q (rows, columns), dO (rows, scaled columns)
     const long nchunks = (row1 - row0 + C - 1) / C;
-    Stager<T, D> sq, sk, sv, sdo;
+    Stager<T, D> s1, s2;
     float g_next = 1.f, d_next = 0.f;
     {
         const long cl = row0 + (nchunks - 1) * C;  // the sweep starts at the last chunk
-        sk.load(Kp, cl, row1);
-        sv.load(Vp, cl, row1);
-        if constexpr (CAUSAL) {
-            sq.load(Qp, cl, row1);
-            sdo.load(dOp, cl, row1);
-            if (t < C && cl + t < row1) {
-                g_next = Gp[cl + t];
-                d_next = dp[cl + t];
-            }
+        s1.load(CAUSAL || h0, h0 ? Kp : Qp, cl, row1);
+        s2.load(CAUSAL || h0, h0 ? Vp : dOp, cl, row1);
+        if (CAUSAL && t < C && cl + t < row1) {
+            g_next = Gp[cl + t];
+            d_next = dp[cl + t];
         }
     }
     for (long ci = nchunks - 1; ci >= 0; --ci) {
@@ -910,98 +885,99 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
         if constexpr (CAUSAL) {
             if (t < C) {
                 const bool ok = c0 + t < row1;
-                rs[t] = ok ? 1.f / g_next : 0.f;
-                dl[t] = ok ? d_next : 0.f;
+                const float r = ok ? 1.f / g_next : 0.f, d = ok ? d_next : 0.f;
+                rs[t] = r;
+                dl[t] = d;
+                dls[t] = d * r;
             }
             __syncthreads();
         }
-        sk.template store<true, false>(Ks, nullptr, 1.f, nullptr);
-        sv.template store<true, false>(Vs, nullptr, 1.f, nullptr);
-        if constexpr (CAUSAL) {
-            sq.template store<true, true>(Qs, QTt, 1.f, nullptr);
-            sdo.template store<true, false>(dOs, nullptr, 1.f, nullptr);
-            sdo.template store<false, true, PP>(nullptr, OHt, 1.f, rs, TSZ);
+        if (h0) {
+            s1.store_rows(Ks);
+            s2.store_rows(Vs);
+        } else if constexpr (CAUSAL) {
+            s1.store_rows(Qs);
+            s1.store_cols(QTt);
+            s2.store_rows(dOs);
+            s2.store_cols_scaled(OHt, TSZ, rs);
         }
         __syncthreads();
         {
             // next chunk of the descending sweep (none after the first chunk of the segment)
             const long cn = c0 - C;
             const long end_n = ci > 0 ? row1 : cn;  // end <= start: nothing is loaded
-            sk.load(Kp, cn, end_n);
-            sv.load(Vp, cn, end_n);
-            if constexpr (CAUSAL) {
-                sq.load(Qp, cn, end_n);
-                sdo.load(dOp, cn, end_n);
-                if (t < C && ci > 0) {
-                    g_next = Gp[cn + t];
-                    d_next = dp[cn + t];
-                }
+            s1.load(CAUSAL || h0, h0 ? Kp : Qp, cn, end_n);
+            s2.load(CAUSAL || h0, h0 ? Vp : dOp, cn, end_n);
+            if (CAUSAL && t < C && ci > 0) {
+                g_next = Gp[cn + t];
+                d_next = dp[cn + t];
             }
         }
 
-        // ---- phase A: Cm and W blocks (rows i, columns n), column sums ----
+        // ---- phase A: weight blocks Cm and W (rows i, columns n), column sums ----
         if constexpr (CAUSAL) {
             int pidx = 0;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) {
 #pragma unroll
                 for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if ((pidx & 3) != w) continue;
-                    Acc<BS> pc, pw;
+                    if (pidx % NW != w) continue;
+                    Blk pc, pw;
                     pc.zero();
                     pw.zero();
-                    block_product<T, D>(pc, dOs, ib * BS, Vs, nb * BS, c, g);
-                    block_product<T, D>(pw, Qs, ib * BS, Ks, nb * BS, c, g);
-                    float vc[NREG], vw[NREG];
+                    block_product<T, D>(pc, dOs, ib * 16, Vs, nb * 16, c, g);
+                    block_product<T, D>(pw, Qs, ib * 16, Ks, nb * 16, c, g);
+                    const f4v r4 = *reinterpret_cast<const f4v *>(rs + ib * 16 + 4 * g);
+                    const f4v d4 = *reinterpret_cast<const f4v *>(dl + ib * 16 + 4 * g);
+                    float vc[4], vw[4];
 #pragma unroll
-                    for (int i = 0; i < NREG; ++i) {
-                        const int i_loc = acc_row<BS>(i, g);  // row i of the block, column n = c
-                        const bool off = (nb == ib && c > i_loc);
-                        vc[i] = off ? 0.f : rs[ib * BS + i_loc] * (pc.get(i) - dl[ib * BS + i_loc]);
-                        vw[i] = off ? 0.f : a + b * pw.get(i);
+                    for (int e = 0; e < 4; ++e) {
+                        const bool off = (nb == ib && c > 4 * g + e);  // column n beyond row i
+                        vc[e] = off ? 0.f : r4[e] * (pc.get(e) - d4[e]);
+                        vw[e] = off ? 0.f : a + b * pw.get(e);
                     }
-                    store_block_rows_contiguous<T, BS>(CmT, PSZ, LDT, nb * BS, ib * BS, c, g, vc);
-                    store_block_rows_contiguous<T, BS>(WT, PSZ, LDT, nb * BS, ib * BS, c, g, vw);
+                    store_weight_block<T, D>(CmT, PSZ, nb * 16, ib * 16, c, g, vc);
+                    store_weight_block<T, D>(WT, PSZ, nb * 16, ib * 16, c, g, vw);
+                    if (KT > 16 && nb == ib && nb % 2 == 1) {
+                        // the first k-tile of the products below starts one block earlier: zeros
+                        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+                        store_weight_block<T, D>(CmT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero);
+                        store_weight_block<T, D>(WT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero);
+                    }
                 }
             }
             if (t < D) {
-                csw[t] = tile_row_sum_planes<T, D, PP>(OHt, TSZ, t);
+                float s = tile_row_sum<T, D>(OHt, t);
+                if constexpr (PP == 2) s += tile_row_sum<T, D>(OHt + TSZ, t);
+                csw[t] = s;
             } else if (t < 2 * D) {
-                float s = 0.f;
-#pragma unroll 8
-                for (int n = 0; n < C; ++n) s += to_float(QTt[(t - D) * LDT + n]) * (dl[n] * rs[n]);
-                csu[t - D] = s;
+                csu[t - D] = tile_row_dot<T, D>(QTt, t - D, dls);
             }
+            __syncthreads();
         }
-        __syncthreads();
 
-        // ---- phase B: per row block: V R^T, b K R, Cm^T Q, W^T OmegaHat; store; state update ----
+        // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
+        //      OmegaHat^T W; store ----
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            Acc<BS> ak[1], av[1];
+            Blk ak[1], av[1];
             ak[0].zero();
             av[0].zero();
-            state_product<T, D>(ak, Vs + nb * BS * LDR, Rb, 1.f, c, g);
-            state_product<T, D>(av, Ks + nb * BS * LDR, Ra, b, c, g);
+            state_product<T, D, 1>(ak, Rb, 1.f, Vs + nb * 16 * LDR, c, g);
+            state_product<T, D, 1>(av, Ra, b, Ks + nb * 16 * LDR, c, g);
             if constexpr (CAUSAL) {
-                weight_product<T, D>(ak[0], CmT, PSZ, nb * BS, QTt, w * BS, (nb * BS) / KT, C / KT,
-                                     c, g);
-                // both operands are intermediates: (hi + lo) * hi, then hi * lo
-                weight_product<T, D>(av[0], WT, PSZ, nb * BS, OHt, w * BS, (nb * BS) / KT, C / KT,
-                                     c, g);
-                if constexpr (PP == 2)
-                    weight_product_hi<T, D>(av[0], WT, nb * BS, OHt + TSZ, w * BS, (nb * BS) / KT,
-                                            C / KT, c, g);
+                chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
+                                           (nb * 16) / KT, C / KT, c, g);
+                chunk_product<T, D, PP, PP>(av[0], OHt, TSZ, w * 16, WT, PSZ, nb * 16,
+                                            (nb * 16) / KT, C / KT, c, g);
             }
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r_loc = nb * BS + acc_row<BS>(i, g);
-                if (c0 + r_loc < row1) {
-                    const size_t o = (size_t)(c0 + r_loc) * D + w * BS + c;
-                    dKp[o] = from_float<T>(b * (ak[0].get(i) - u_reg));
-                    dVp[o] = from_float<T>(av[0].get(i) + w_reg);
-                }
-            }
+            const size_t o = (size_t)(c0 + nb * 16) * D;
+            const int valid = (int)(row1 - c0) - nb * 16;
+            store_block<T>(dKp + o, D, w * 16, valid, l, b * (ak[0].get(0) - u4[0]),
+                           b * (ak[0].get(1) - u4[1]), b * (ak[0].get(2) - u4[2]),
+                           b * (ak[0].get(3) - u4[3]));
+            store_block<T>(dVp + o, D, w * 16, valid, l, av[0].get(0) + w4[0],
+                           av[0].get(1) + w4[1], av[0].get(2) + w4[2], av[0].get(3) + w4[3]);
         }
         if constexpr (CAUSAL) {
 #pragma unroll
@@ -1009,8 +985,8 @@ __global__ __launch_bounds__(NT) void kf_bwd_dkv(
                 outer_update<T, D>(Ra, QTt, OHt + pl * TSZ, w, c, g);
                 outer_update<T, D>(Rb, OHt + pl * TSZ, QTt, w, c, g);
             }
-            u_reg += csu[w * BS + c];
-            w_reg += a * csw[w * BS + c];
+            u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
+            w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
         }
     }
 }
@@ -1024,6 +1000,7 @@ template <typename T, int D>
 la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, void *Ov, float *G, float *ws, hipStream_t st, Tracer &tc)
 {
+    constexpr int NT = FC<T, D>::NT;
     const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv;
     T *O = (T *)Ov;
     const int nseg = pl.nseg;
@@ -1052,13 +1029,14 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
                    void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
 {
     typedef BwdSlot<D> SL;
+    constexpr int NT = FC<T, D>::NT;
     const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv, *O = (const T *)Ov,
             *dO = (const T *)dOv;
     T *dQ = (T *)dQv, *dK = (T *)dKv, *dV = (T *)dVv;
     const int nseg = pl.nseg;
-    float *delta = ws + pl.delta_offset_floats;
+    float *dprime = ws + pl.delta_offset_floats;
     const dim3 grid(pr.BH * nseg), block(NT);
-    kf_bwd_state<T, D><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, ws, delta, pr.N, nseg,
+    kf_bwd_state<T, D><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, ws, dprime, pr.N, nseg,
                                                pl.seg_len, pl.slot_floats, pr.causal);
     tc.mark("bwd_state");
     if (pr.causal) {
@@ -1071,18 +1049,18 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     }
     tc.mark("scan_slots");
     if (pr.causal) {
-        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, delta, pr.N, nseg,
+        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, dprime, pr.N, nseg,
                                                       pl.seg_len, pl.slot_floats, pr.b);
         tc.mark("bwd_dq");
-        kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, delta, pr.N,
+        kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                        nseg, pl.seg_len, pl.slot_floats, pr.a,
                                                        pr.b);
         tc.mark("bwd_dkv");
     } else {
-        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, delta, pr.N, nseg,
+        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, dprime, pr.N, nseg,
                                                        pl.seg_len, pl.slot_floats, pr.b);
         tc.mark("bwd_dq");
-        kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, delta, pr.N,
+        kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                         nseg, pl.seg_len, pl.slot_floats, pr.a,
                                                         pr.b);
         tc.mark("bwd_dkv");
@@ -1094,7 +1072,8 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
 
 bool fast_supported(const Problem &pr, int is_backward)
 {
-    if (pr.dt == LA_F32) return pr.D == 64 || (pr.D == 128 && !is_backward);
+    (void)is_backward;
+    if (pr.dt == LA_F32) return pr.D == 64 || pr.D == 128;
     return pr.D == 128;
 }
 
@@ -1104,6 +1083,8 @@ la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const 
 {
     if (pr.dt == LA_F32 && pr.D == 64)
         return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+    if (pr.dt == LA_F32 && pr.D == 128)
+        return fast_bwd<float, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
     if (pr.dt == LA_BF16 && pr.D == 128)
         return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
     return LA_ERR_UNSUPPORTED;

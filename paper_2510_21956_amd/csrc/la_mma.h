@@ -104,6 +104,11 @@ struct Mma<float, BS> {
     {
         mma(c, a, b.hi);
     }
+    // The intermediate (possibly split) is the X operand: c += a * b.
+    static __device__ __forceinline__ void mma2x(Acc<BS> &c, const Frag2 &a, Frag b)
+    {
+        mma(c, a.hi, b);
+    }
     // Split a float intermediate for storage in an LDS tile: plane 0 (and 1).
     static __device__ __forceinline__ void split(float x, float &hi, float &lo)
     {
@@ -156,6 +161,11 @@ struct Mma<__bf16, BS> {
     {
         mma(c, a, b.hi);
         mma(c, a, b.lo);
+    }
+    static __device__ __forceinline__ void mma2x(Acc<BS> &c, const Frag2 &a, Frag b)
+    {
+        mma(c, a.hi, b);
+        mma(c, a.lo, b);
     }
     static __device__ __forceinline__ void split(float x, float &hi, float &lo)
     {
