@@ -41,6 +41,12 @@ struct FC {
     static constexpr int EPV = 16 / sizeof(T);  // elements per 16-byte unit
     static constexpr int GPR = D / EPV;         // 16-byte units per row
     static constexpr int HT = NT / 2;           // threads per staging half
+    // Transposed tiles are written by lanes whose rows are 2*EPV... apart: EPV rows per
+    // 16-byte unit of a lane, neighbouring lanes EPV rows on.  With any row padding that
+    // keeps vector alignment those rows collide in the LDS banks, so the 4-element column
+    // groups of row d are stored XOR-swizzled by swz(d); readers apply the same swizzle.
+    static constexpr int SWM = C / 8;  // swizzle values: 0 .. SWM-1 (= k-tile width in groups)
+    static __device__ __forceinline__ int swz(int d) { return (d / (2 * EPV)) % SWM; }
     static_assert(HT / GPR == C / 4, "each half of the workgroup stages one C x D tile");
     static_assert(D % KT == 0 && C % KT == 0, "tile sizes");
     static_assert(NT >= 2 * D, "vector sums use threads [0, 2D)");
@@ -111,7 +117,8 @@ struct Stager {
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                *reinterpret_cast<u4v *>(tr + (dg * 4 + e) * F::LDT + 4 * rq) =
+                *reinterpret_cast<u4v *>(tr + (dg * 4 + e) * F::LDT +
+                                         4 * (rq ^ F::swz(dg * 4 + e))) =
                     u4v{raw[0][e], raw[1][e], raw[2][e], raw[3][e]};
         } else {
 #pragma unroll
@@ -120,8 +127,9 @@ struct Stager {
                 const uint32_t r0 = raw[0][wd], r1 = raw[1][wd], r2 = raw[2][wd], r3 = raw[3][wd];
                 const u2v lo = {(r0 & 0xffffu) | (r1 << 16), (r2 & 0xffffu) | (r3 << 16)};
                 const u2v hi = {(r0 >> 16) | (r1 & 0xffff0000u), (r2 >> 16) | (r3 & 0xffff0000u)};
-                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd) * F::LDT + 4 * rq) = lo;
-                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd + 1) * F::LDT + 4 * rq) = hi;
+                const int cg = 4 * (rq ^ F::swz(dg * 8));  // the same for all 8 rows of the unit
+                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd) * F::LDT + cg) = lo;
+                *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd + 1) * F::LDT + cg) = hi;
             }
         }
     }
@@ -138,7 +146,7 @@ struct Stager {
             const float x0 = s[0] * elem(raw[0], e), x1 = s[1] * elem(raw[1], e),
                         x2 = s[2] * elem(raw[2], e), x3 = s[3] * elem(raw[3], e);
             V4 v = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2), from_float<T>(x3)};
-            T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * rq;
+            T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * (rq ^ F::swz(dg * F::EPV + e));
             *reinterpret_cast<V4 *>(dst) = v;
             if constexpr (Mma<T, F::BS>::PLANES == 2) {
                 V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
@@ -171,10 +179,11 @@ __device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *w
     typedef FC<T, D> F;
     typedef typename Vec4<T>::type V4;
     float s = 0.f;
+    const int sw = F::swz(r);
 #pragma unroll
     for (int n = 0; n < F::C; n += 4) {
         V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
-        f4v x = *reinterpret_cast<const f4v *>(wgt + n);
+        f4v x = *reinterpret_cast<const f4v *>(wgt + 4 * ((n / 4) ^ sw));
         s += (to_float(v[0]) * x[0] + to_float(v[1]) * x[1]) +
              (to_float(v[2]) * x[2] + to_float(v[3]) * x[3]);
     }
@@ -209,14 +218,13 @@ typedef Acc<16> Blk;  // 16 x 16 accumulator block: lane (c, g) holds rows 4g..4
 // st[rb] += A_rb B^T over the C chunk rows: A = transposed tile `at` (row block rb),
 // B = transposed tile `bt` (rows 16w + c), both [D][LDT] with the chunk row contiguous.
 // This is the rank-C update of the 16 columns of a running state that wave w owns.
-template <typename T, int D>
+template <typename T, int D, int GRP = 4>  // GRP row blocks per pass bounds the fragments in flight
 __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, const T *bt, int w,
                                              int c, int g)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDT = F::LDT, C = F::C;
-    constexpr int GRP = 4;  // row blocks per pass: bounds the fragments held in flight
     typedef XsY<M, GRP> B;
 #pragma unroll
     for (int r0 = 0; r0 < NRB; r0 += GRP) {
@@ -224,10 +232,11 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, con
             C / KT,
             [&](int kt) {
                 B b;
-                b.y = M::load(bt + (w * 16 + c) * LDT + kt * KT, g);
+                b.y = M::load_swz(bt + (w * 16 + c) * LDT + kt * KT, g, F::swz(w * 16 + c));
 #pragma unroll
                 for (int rb = 0; rb < GRP; ++rb)
-                    b.x[rb] = M::load(at + ((r0 + rb) * 16 + c) * LDT + kt * KT, g);
+                    b.x[rb] = M::load_swz(at + ((r0 + rb) * 16 + c) * LDT + kt * KT, g,
+                                          F::swz((r0 + rb) * 16 + c));
                 return b;
             },
             [&](int, const B &b) {
@@ -283,9 +292,10 @@ __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, con
         [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
 }
 
-// acc += X_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T over chunk rows, where X is a tile with
-// NXP planes (plane stride xps) and Y a tile with NYP planes (plane stride yps), all with
-// leading dimension LDT.  Products of two second planes are dropped.
+// acc += X_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T over chunk rows, where X is a
+// (swizzled) transposed tile with NXP planes (plane stride xps) and Y a weight tile with
+// NYP planes (plane stride yps), both with leading dimension LDT.  Products of two second
+// planes are dropped.
 template <typename T, int D, int NXP, int NYP>
 __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, int xr, const T *yt,
                                               int yps, int yr, int kt0, int kt1, int c, int g)
@@ -300,7 +310,8 @@ __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, in
             B b;
 #pragma unroll
             for (int p = 0; p < NXP; ++p)
-                b.x[p] = M::load(xt + p * xps + (xr + c) * LDT + (kt0 + s) * KT, g);
+                b.x[p] = M::load_swz(xt + p * xps + (xr + c) * LDT + (kt0 + s) * KT, g,
+                                     F::swz(xr + c));
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
                 b.y[p] = M::load(yt + p * yps + (yr + c) * LDT + (kt0 + s) * KT, g);
@@ -470,12 +481,12 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
 
         // ---- phase A: weight blocks P = tril(a + b Q K^T), q.z, column sums ----
         if constexpr (CAUSAL) {
-            int pidx = 0;
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-                for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if (pidx % NW != w) continue;
+            // the NB(NB+1)/2 blocks on or below the diagonal, dealt round-robin to the waves
+#pragma unroll 1
+            for (int pidx = w; pidx < NB * (NB + 1) / 2; pidx += NW) {
+                int ib = 0, nb = pidx;
+                while (nb > ib) nb -= ++ib;
+                {
                     Blk pa;  // rows n (block nb), columns i (block ib)
                     pa.zero();
                     block_product<T, D>(pa, Ks, nb * 16, Qs, ib * 16, c, g);
@@ -757,12 +768,12 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
 
         // ---- phase A: weight blocks Cm' (rows n, columns i), column sums of K ----
         if constexpr (CAUSAL) {
-            int pidx = 0;
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-                for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if (pidx % NW != w) continue;
+            // the NB(NB+1)/2 blocks on or below the diagonal, dealt round-robin to the waves
+#pragma unroll 1
+            for (int pidx = w; pidx < NB * (NB + 1) / 2; pidx += NW) {
+                int ib = 0, nb = pidx;
+                while (nb > ib) nb -= ++ib;
+                {
                     Blk pa;
                     pa.zero();
                     block_product<T, D>(pa, Vs, nb * 16, dOs, ib * 16, c, g);
@@ -916,12 +927,12 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
 
         // ---- phase A: weight blocks Cm and W (rows i, columns n), column sums ----
         if constexpr (CAUSAL) {
-            int pidx = 0;
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-#pragma unroll
-                for (int nb = 0; nb <= ib; ++nb, ++pidx) {
-                    if (pidx % NW != w) continue;
+            // the NB(NB+1)/2 blocks on or below the diagonal, dealt round-robin to the waves
+#pragma unroll 1
+            for (int pidx = w; pidx < NB * (NB + 1) / 2; pidx += NW) {
+                int ib = 0, nb = pidx;
+                while (nb > ib) nb -= ++ib;
+                {
                     Blk pc, pw;
                     pc.zero();
                     pw.zero();
@@ -958,7 +969,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
 
         // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
         //      OmegaHat^T W; store ----
-#pragma unroll
+#pragma unroll 1
         for (int nb = 0; nb < NB; ++nb) {
             Blk ak[1], av[1];
             ak[0].zero();
@@ -968,8 +979,12 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
             if constexpr (CAUSAL) {
                 chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
                                            (nb * 16) / KT, C / KT, c, g);
-                chunk_product<T, D, PP, PP>(av[0], OHt, TSZ, w * 16, WT, PSZ, nb * 16,
-                                            (nb * 16) / KT, C / KT, c, g);
+                // both operands are intermediates: hi (hi + lo), then lo hi
+                chunk_product<T, D, 1, PP>(av[0], OHt, 0, w * 16, WT, PSZ, nb * 16,
+                                           (nb * 16) / KT, C / KT, c, g);
+                if constexpr (PP == 2)
+                    chunk_product<T, D, 1, 1>(av[0], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
+                                              (nb * 16) / KT, C / KT, c, g);
             }
             const size_t o = (size_t)(c0 + nb * 16) * D;
             const int valid = (int)(row1 - c0) - nb * 16;
@@ -982,8 +997,8 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
         if constexpr (CAUSAL) {
 #pragma unroll
             for (int pl = 0; pl < PP; ++pl) {
-                outer_update<T, D>(Ra, QTt, OHt + pl * TSZ, w, c, g);
-                outer_update<T, D>(Rb, OHt + pl * TSZ, QTt, w, c, g);
+                outer_update<T, D, 2>(Ra, QTt, OHt + pl * TSZ, w, c, g);
+                outer_update<T, D, 2>(Rb, OHt + pl * TSZ, QTt, w, c, g);
             }
             u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
             w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);

@@ -88,6 +88,12 @@ struct Mma<float, BS> {
     {
         return *reinterpret_cast<const f4v *>(p + 4 * g);
     }
+    // The same from a tile whose 4-element column groups are XOR-swizzled by `sw`
+    // (sw < NG, so the swizzle stays inside the k-tile).
+    static __device__ __forceinline__ Frag load_swz(const float *p, int g, int sw)
+    {
+        return *reinterpret_cast<const f4v *>(p + 4 * (g ^ sw));
+    }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v) { return Frag2{g0}; }
     static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
     {
@@ -135,6 +141,15 @@ struct Mma<__bf16, BS> {
     {
         bf4v lo = *reinterpret_cast<const bf4v *>(p + 4 * g);
         bf4v hi = *reinterpret_cast<const bf4v *>(p + KT / 2 + 4 * g);
+        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return r;
+    }
+    // The same from a tile whose 4-element column groups are XOR-swizzled by `sw`
+    // (sw < 2 * NG, so the swizzle stays inside the k-tile).
+    static __device__ __forceinline__ Frag load_swz(const __bf16 *p, int g, int sw)
+    {
+        bf4v lo = *reinterpret_cast<const bf4v *>(p + 4 * (g ^ sw));
+        bf4v hi = *reinterpret_cast<const bf4v *>(p + 4 * ((g + NG) ^ sw));
         Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return r;
     }
