@@ -203,14 +203,18 @@ def main():
     # G, delta' are one float per token-head):
     #   fwd_state: K, V in                                   2 D e
     #   fwd_apply: Q, K, V in; O, G out                      4 D e + 4
-    #   bwd_state: Q, K, V, O, dO, G in; delta' out          5 D e + 8
-    #   bwd_dq   : K, V, dO, G, delta' in; dQ out            4 D e + 8
+    #   bwd_state: K, V in                                   2 D e
+    #   bwd_dq   : Q, K, V, O, dO, G in; dQ, delta' out      6 D e + 8
     #   bwd_dkv  : Q, K, V, dO, G, delta' in; dK, dV out     6 D e + 8
-    #   (generic path) bwd_apply: Q, K, V, dO, G, delta in; dQ, dK, dV out   7 D e + 8
-    alg_bytes = {"fwd_state": 2 * D * e, "fwd_apply": 4 * D * e + 4, "bwd_state": 5 * D * e + 8,
-                 "bwd_dq": 4 * D * e + 8, "bwd_dkv": 6 * D * e + 8, "bwd_apply": 7 * D * e + 8}
+    #   plain-ALU path: generic_bwd_state reads Q, K, V, O, dO, G and writes delta
+    #   (5 D e + 8); generic_bwd_apply reads Q, K, V, dO, G, delta and writes dQ, dK, dV
+    #   (7 D e + 8)
+    alg_bytes = {"fwd_state": 2 * D * e, "fwd_apply": 4 * D * e + 4, "bwd_state": 2 * D * e,
+                 "bwd_dq": 6 * D * e + 8, "bwd_dkv": 6 * D * e + 8,
+                 "generic_fwd_state": 2 * D * e, "generic_fwd_apply": 4 * D * e + 4,
+                 "generic_bwd_state": 5 * D * e + 8, "generic_bwd_apply": 7 * D * e + 8}
     dom = max(kernels_ms, key=kernels_ms.get)
-    dom_key = next((k for k in alg_bytes if dom.endswith(k)), None)
+    dom_key = dom.split(":")[1] if dom.split(":")[1] in alg_bytes else None
     dom_ms = kernels_ms[dom]
     roofline = None
     if dom_key:

@@ -134,13 +134,12 @@ struct Stager {
         }
     }
 
-    // Transposed tile with every element multiplied by row_scale[row] in fp32; with
-    // bf16 a second plane at tr + plane holds what the first plane's rounding lost.
-    __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, const float *row_scale) const
+    // Transposed tile with the elements of this thread's row i multiplied by s[i] in fp32;
+    // with bf16 a second plane at tr + plane holds what the first plane's rounding lost.
+    __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, f4v s) const
     {
         typedef typename Vec4<T>::type V4;
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
-        const f4v s = *reinterpret_cast<const f4v *>(row_scale + 4 * rq);
 #pragma unroll
         for (int e = 0; e < F::EPV; ++e) {
             const float x0 = s[0] * elem(raw[0], e), x1 = s[1] * elem(raw[1], e),
@@ -372,11 +371,12 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 }
 
 // ---------------------------------------------------------------------------
-// Phase 1 (forward): per-segment S = sum k v^T, z = sum k, p = sum v (Eq. xy
-// without the factors), written to state slot `seg + slot_shift`.
+// Phase 1: per-segment S = sum k v^T, z = sum k, p = sum v (Eq. xy without the
+// factors), written to state slot `seg + slot_shift` as [S | z | p].  The
+// backward pass takes the TRANSPOSED variant, [S^T | z], for its ascending sweep.
 // ---------------------------------------------------------------------------
-template <typename T, int D>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_state(
+template <typename T, int D, bool TRANSPOSED>
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_kv_state(
     const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
     int nseg_run, int seg_len, size_t slot_floats, int slot_shift)
 {
@@ -403,17 +403,24 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_state(
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
         s1.load(true, h0 ? Kp : Vp, c0 + C, row1);  // next chunk, in flight during the products
-        outer_update<T, D>(st, KTt, VTt, w, c, g);
-        if (t < D) vec += tile_row_sum<T, D>(VTt, t);
-        else if (t < 2 * D) vec += tile_row_sum<T, D>(KTt, t - D);
+        if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, KTt, w, c, g);
+        else outer_update<T, D>(st, KTt, VTt, w, c, g);
+        if (t < D) {
+            if constexpr (!TRANSPOSED) vec += tile_row_sum<T, D>(VTt, t);
+        } else if (t < 2 * D) {
+            vec += tile_row_sum<T, D>(KTt, t - D);
+        }
     }
     float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) slot[(rb * 16 + 4 * g + i) * D + w * 16 + c] = st[rb].get(i);
-    if (t < D) slot[D * D + D + t] = vec;             // p
-    else if (t < 2 * D) slot[D * D + (t - D)] = vec;  // z
+    if (t < D) {
+        if constexpr (!TRANSPOSED) slot[D * D + D + t] = vec;  // p
+    } else if (t < 2 * D) {
+        slot[D * D + (t - D)] = vec;  // z
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -574,155 +581,51 @@ struct BwdSlot {
 };
 
 // ---------------------------------------------------------------------------
-// Phase 1 (backward): per-segment sums of both directions, and
-// dprime_i = o_i . dO_i  (= g_i delta_i), written to the workspace.
+// Backward, ascending sweep: dQ (Eq. back1), and on the way everything the
+// descending sweep needs from this direction.  With dprime_i = o_i . dO_i
+// (= g_i delta_i) and Cm'_in = dO_i . v_n - dprime_i (= g_i times the c_in of
+// Eq. bound / b):
+//   dQ_c = diag(b / g) (tril(Cm') K_c + dO_c S^T - dprime z^T)
+//   then S += K_c^T V_c, z += sum k.   The state is held transposed (rows j,
+//   columns r) because this product contracts over j.
+// The kernel also writes dprime to the workspace and accumulates the segment's
+// reverse-running sums R = sum q OmegaHat^T, u = sum delta q, w = sum OmegaHat
+// (Eq. endd without the factors), which it leaves in the slot of the segment
+// that will start from them.
 // ---------------------------------------------------------------------------
-template <typename T, int D>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_state(
+template <typename T, int D, bool CAUSAL>
+__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
-    float *__restrict__ ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
-    size_t slot_floats, int causal)
+    T *__restrict__ dQ, float *ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
+    size_t slot_floats, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     typedef BwdSlot<D> SL;
-    constexpr int C = F::C, NRB = F::NRB, LDT = F::LDT, PP = M::PLANES, TSZ = D * LDT;
-    __shared__ __align__(16) T QTt[TSZ], OHt[PP * TSZ], KTt[TSZ], VTt[TSZ];
-    __shared__ __align__(16) float rs[C], dl[C];  // 1/g_i and delta_i = dprime_i / g_i
+    constexpr int C = F::C, NW = F::NW, NB = F::NB, NRB = F::NRB, KT = F::KT;
+    constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT, TSZ = D * LDT;
+    constexpr int TS = CAUSAL ? 1 : 0;
+    __shared__ __align__(16) T dOs[C * LDR];
+    __shared__ __align__(16) T QTt[TSZ], OHt[PP * TSZ];
+    __shared__ __align__(16) T Vs[TS * C * LDR + 4];
+    __shared__ __align__(16) T VTt[TS * TSZ + 4];
+    __shared__ __align__(16) T KTt[TS * TSZ + 4];
+    __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
+    __shared__ __align__(16) float rs[C], dl[C], dls[C], csk[D];  // 1/g, dprime, delta, sum k
+
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
+    T *dQp = dQ + base;
     const float *Gp = G + (size_t)bh * N;
     float *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
     const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
     const bool h0 = t < F::HT;
-    const bool need_S = causal ? (seg + 1 < nseg) : true;
-    const bool need_R = causal ? (seg > 0) : true;
-
-    Blk accST[NRB], accR[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        accST[rb].zero();
-        accR[rb].zero();
-    }
-    float vecW = 0.f, vecZ = 0.f, vecU = 0.f;  // t < D: w[t], z[t];  D <= t < 2D: u[t-D]
-
-    // staging: half 0: dO, O (for dprime), Q; half 1: K, V
-    Stager<T, D> s1, s2, s3;
-    s1.load(h0 || need_S, h0 ? dOp : Kp, row0, row1);
-    s2.load(h0 || need_S, h0 ? Op : Vp, row0, row1);
-    s3.load(h0, Qp, row0, row1);
-    float g_next = (t < C && row0 + t < row1) ? Gp[row0 + t] : 0.f;
-    for (long c0 = row0; c0 < row1; c0 += C) {
-        __syncthreads();
-        if (t < C) rs[t] = (c0 + t < row1) ? 1.f / g_next : 0.f;
-        __syncthreads();
-        if (h0) {
-            // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
-            // lanes that share the row
-            const int th = t % F::HT, rq = th / F::GPR;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float s = 0.f;
-#pragma unroll
-                for (int e = 0; e < F::EPV; ++e)
-                    s += Stager<T, D>::elem(s2.raw[i], e) * Stager<T, D>::elem(s1.raw[i], e);
-#pragma unroll
-                for (int m = 1; m < F::GPR; m <<= 1) s += __shfl_xor(s, m);
-                if (th % F::GPR == 0) {
-                    const int r = 4 * rq + i;
-                    dl[r] = s * rs[r];
-                    if (c0 + r < row1) dp[c0 + r] = s;
-                }
-            }
-            s1.store_cols_scaled(OHt, TSZ, rs);
-            s3.store_cols(QTt);
-        } else if (need_S) {
-            s1.store_cols(KTt);
-            s2.store_cols(VTt);
-        }
-        __syncthreads();
-        s1.load(h0 || need_S, h0 ? dOp : Kp, c0 + C, row1);  // next chunk, in flight meanwhile
-        s2.load(h0 || need_S, h0 ? Op : Vp, c0 + C, row1);
-        s3.load(h0, Qp, c0 + C, row1);
-        g_next = (t < C && c0 + C + t < row1) ? Gp[c0 + C + t] : 0.f;
-        if (need_R) {
-#pragma unroll
-            for (int pl = 0; pl < PP; ++pl) outer_update<T, D>(accR, QTt, OHt + pl * TSZ, w, c, g);
-            if (t < D) {
-                vecW += tile_row_sum<T, D>(OHt, t);
-                if constexpr (PP == 2) vecW += tile_row_sum<T, D>(OHt + TSZ, t);
-            } else if (t < 2 * D) {
-                vecU += tile_row_dot<T, D>(QTt, t - D, dl);
-            }
-        }
-        if (need_S) {
-            outer_update<T, D>(accST, VTt, KTt, w, c, g);
-            if (t < D) vecZ += tile_row_sum<T, D>(KTt, t);
-        }
-    }
-    if (need_R) {
-        float *slot = ws + ((size_t)bh * nseg + seg - (causal ? 1 : 0)) * slot_floats;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = rb * 16 + 4 * g + i, j = w * 16 + c;
-                slot[SL::R + r * D + j] = accR[rb].get(i);
-                slot[SL::RT + j * D + r] = accR[rb].get(i);
-            }
-        if (t < D) slot[SL::W + t] = vecW;
-        else if (t < 2 * D) slot[SL::U + (t - D)] = vecU;
-    }
-    if (need_S) {
-        float *slot = ws + ((size_t)bh * nseg + seg + (causal ? 1 : 0)) * slot_floats;
-#pragma unroll
-        for (int jb = 0; jb < NRB; ++jb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                slot[SL::ST + (jb * 16 + 4 * g + i) * D + w * 16 + c] = accST[jb].get(i);
-        if (t < D) slot[SL::Z + t] = vecZ;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Phase 3 (backward), ascending sweep: dQ (Eq. back1).  With dprime_i = o_i . dO_i
-// and Cm'_in = dO_i . v_n - dprime_i (= g_i times the c_in of Eq. bound / b):
-//   dQ_c = diag(b / g) (tril(Cm') K_c + dO_c S^T - dprime z^T)
-//   then S += K_c^T V_c, z += sum k.   The state is held transposed (rows j,
-//   columns r) because this product contracts over j.
-// ---------------------------------------------------------------------------
-template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
-    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ G,
-    const T *__restrict__ dO, T *__restrict__ dQ, const float *__restrict__ ws,
-    const float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b)
-{
-    typedef FC<T, D> F;
-    typedef Mma<T, 16> M;
-    typedef BwdSlot<D> SL;
-    constexpr int C = F::C, NW = F::NW, NB = F::NB, NRB = F::NRB, KT = F::KT;
-    constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
-    constexpr int TS = CAUSAL ? 1 : 0;
-    __shared__ __align__(16) T dOs[C * LDR];
-    __shared__ __align__(16) T Vs[TS * C * LDR + 4];
-    __shared__ __align__(16) T VTt[TS * D * LDT + 4];
-    __shared__ __align__(16) T KTt[TS * D * LDT + 4];
-    __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
-    __shared__ __align__(16) float rs[C], dl[C], csk[D];  // b/g_i, dprime_i, column sums of K
-
-    const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
-    const size_t base = (size_t)bh * N * D;
-    const T *Kp = K + base, *Vp = V + base, *dOp = dO + base;
-    T *dQp = dQ + base;
-    const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
-    const long row0 = (long)seg * seg_len;
-    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
-    const bool h0 = t < F::HT;
+    const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
+    const bool need_R = CAUSAL ? (seg > 0) : true;  // segment 0's sums start no one
 
     const bool zero_init = CAUSAL && seg == 0;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
@@ -734,37 +637,67 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
             st[jb].set(i, zero_init ? 0.f : slot[SL::ST + (jb * 16 + 4 * g + i) * D + w * 16 + c]);
     f4v z4 = {0.f, 0.f, 0.f, 0.f};  // z[16w + 4g + 0..3]
     if (!zero_init) z4 = *reinterpret_cast<const f4v *>(slot + SL::Z + w * 16 + 4 * g);
+    Blk accR[NRB];  // this segment's R: rows r, columns j = 16w + c
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) accR[rb].zero();
+    float vecR = 0.f;  // t < D: w[t];  D <= t < 2D: u[t-D]
 
-    // staging: half 0: dO (rows) then K (columns); half 1: V (rows and columns)
-    Stager<T, D> s1, s2;
-    s1.load(CAUSAL || h0, h0 ? dOp : Vp, row0, row1);
-    if constexpr (CAUSAL) s2.load(h0, Kp, row0, row1);
-    float g_next = 1.f, d_next = 0.f;
-    if (t < C && row0 + t < row1) {
-        g_next = Gp[row0 + t];
-        d_next = dp[row0 + t];
-    }
+    // staging: half 0: dO (rows, scaled columns), O (for dprime), Q (columns);
+    //          half 1: V (rows and columns), K (columns); unmasked: Q instead, no K
+    Stager<T, D> s1, s2, s3;
+    f4v g4 = {1.f, 1.f, 1.f, 1.f};  // half 0: g of this thread's four rows
+    const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = h0 ? Op : Kp;
+    auto fetch = [&](long c0) {
+        s1.load(h0 || CAUSAL || need_R, p1, c0, row1);
+        s2.load(h0 || CAUSAL, p2, c0, row1);
+        if constexpr (CAUSAL) s3.load(h0 && need_R, Qp, c0, row1);
+        if (h0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const long r = c0 + 4 * rq + i;
+                g4[i] = r < row1 ? Gp[r] : 1.f;
+            }
+        }
+    };
+    fetch(row0);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         if (h0) {
+            f4v r4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r4[i] = (c0 + 4 * rq + i < row1) ? 1.f / g4[i] : 0.f;
+            // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
+            // lanes that share the row
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < F::EPV; ++e)
+                    s += Stager<T, D>::elem(s2.raw[i], e) * Stager<T, D>::elem(s1.raw[i], e);
+#pragma unroll
+                for (int m = 1; m < F::GPR; m <<= 1) s += __shfl_xor(s, m);
+                if (dg == 0) {
+                    const int r = 4 * rq + i;
+                    rs[r] = r4[i];
+                    dl[r] = s;
+                    dls[r] = s * r4[i];
+                    if (c0 + r < row1) dp[c0 + r] = s;
+                }
+            }
             s1.store_rows(dOs);
-            if constexpr (CAUSAL) s2.store_cols(KTt);
+            if (need_R) {
+                s1.store_cols_scaled(OHt, TSZ, r4);
+                if constexpr (CAUSAL) s3.store_cols(QTt);
+            }
         } else if constexpr (CAUSAL) {
             s1.store_rows(Vs);
             s1.store_cols(VTt);
-        }
-        if (t < C) {
-            const bool ok = c0 + t < row1;
-            rs[t] = ok ? b / g_next : 0.f;
-            dl[t] = ok ? d_next : 0.f;
+            s2.store_cols(KTt);
+        } else {
+            s1.store_cols(QTt);
         }
         __syncthreads();
-        s1.load(CAUSAL || h0, h0 ? dOp : Vp, c0 + C, row1);  // next chunk, in flight meanwhile
-        if constexpr (CAUSAL) s2.load(h0, Kp, c0 + C, row1);
-        if (t < C && c0 + C + t < row1) {
-            g_next = Gp[c0 + C + t];
-            d_next = dp[c0 + C + t];
-        }
+        fetch(c0 + C);  // next chunk, in flight meanwhile
 
         // ---- phase A: weight blocks Cm' (rows n, columns i), column sums of K ----
         if constexpr (CAUSAL) {
@@ -808,7 +741,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
                     chunk_product<T, D, 1, PP>(acc[ib], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
                                                ((ib + 1) * 16 + KT - 1) / KT, c, g);
                 const int r_loc = ib * 16 + c;
-                const float sc = rs[r_loc], di = dl[r_loc];
+                const float sc = b * rs[r_loc], di = dl[r_loc];
                 store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
                                (int)(row1 - c0) - ib * 16, l, sc * (acc[ib].get(0) - di * z4[0]),
                                sc * (acc[ib].get(1) - di * z4[1]), sc * (acc[ib].get(2) - di * z4[2]),
@@ -819,6 +752,30 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
             outer_update<T, D>(st, VTt, KTt, w, c, g);
             z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
+        if (need_R) {
+#pragma unroll
+            for (int pl = 0; pl < PP; ++pl)
+                outer_update<T, D, 2>(accR, QTt, OHt + pl * TSZ, w, c, g);
+            if (t < D) {
+                vecR += tile_row_sum<T, D>(OHt, t);
+                if constexpr (PP == 2) vecR += tile_row_sum<T, D>(OHt + TSZ, t);
+            } else if (t < 2 * D) {
+                vecR += tile_row_dot<T, D>(QTt, t - D, dls);
+            }
+        }
+    }
+    if (need_R) {
+        float *out = ws + ((size_t)bh * nseg + seg - (CAUSAL ? 1 : 0)) * slot_floats;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = rb * 16 + 4 * g + i, j = w * 16 + c;
+                out[SL::R + r * D + j] = accR[rb].get(i);
+                out[SL::RT + j * D + r] = accR[rb].get(i);
+            }
+        if (t < D) out[SL::W + t] = vecR;
+        else if (t < 2 * D) out[SL::U + (t - D)] = vecR;
     }
 }
 
@@ -910,7 +867,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
             s1.store_rows(Qs);
             s1.store_cols(QTt);
             s2.store_rows(dOs);
-            s2.store_cols_scaled(OHt, TSZ, rs);
+            s2.store_cols_scaled(OHt, TSZ, *reinterpret_cast<const f4v *>(rs + 4 * ((t % F::HT) / F::GPR)));
         }
         __syncthreads();
         {
@@ -1021,7 +978,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nseg = pl.nseg;
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
-        kf_fwd_state<T, D><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
+        kf_kv_state<T, D, false><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
         tc.mark("fwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, D * D + 2 * D, pr.causal ? 0 : 2,
@@ -1051,35 +1008,42 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nseg = pl.nseg;
     float *dprime = ws + pl.delta_offset_floats;
     const dim3 grid(pr.BH * nseg), block(NT);
-    kf_bwd_state<T, D><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, ws, dprime, pr.N, nseg,
-                                               pl.seg_len, pl.slot_floats, pr.causal);
-    tc.mark("bwd_state");
-    if (pr.causal) {
-        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST, 0, 1, nseg - 1,
-                          st);
-        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 1, 0, nseg - 2,
-                          st);
-    } else {
-        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, SL::END, 2, 0, nseg - 1, st);
+    // forward-running sums per segment (none needed from a masked pass's last segment)
+    const int nrun = pr.causal ? nseg - 1 : nseg;
+    if (nrun > 0) {
+        kf_kv_state<T, D, true><<<dim3(pr.BH * nrun), block, 0, st>>>(
+            K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
+        tc.mark("bwd_state");
+        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST,
+                          pr.causal ? 0 : 2, pr.causal ? 1 : 0, nseg - 1, st);
+        tc.mark("scan_slots");
     }
-    tc.mark("scan_slots");
+    if (pr.causal)
+        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, dprime, pr.N,
+                                                      nseg, pl.seg_len, pl.slot_floats, pr.b);
+    else
+        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, dprime, pr.N,
+                                                       nseg, pl.seg_len, pl.slot_floats, pr.b);
+    tc.mark("bwd_dq");
+    // reverse-running sums left by the ascending sweep
     if (pr.causal) {
-        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, dprime, pr.N, nseg,
-                                                      pl.seg_len, pl.slot_floats, pr.b);
-        tc.mark("bwd_dq");
+        if (nseg > 1) {
+            launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 1, 0,
+                              nseg - 2, st);
+            tc.mark("scan_slots_rev");
+        }
         kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                        nseg, pl.seg_len, pl.slot_floats, pr.a,
                                                        pr.b);
-        tc.mark("bwd_dkv");
     } else {
-        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(K, V, G, dO, dQ, ws, dprime, pr.N, nseg,
-                                                       pl.seg_len, pl.slot_floats, pr.b);
-        tc.mark("bwd_dq");
+        launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
+                          st);
+        tc.mark("scan_slots_rev");
         kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                         nseg, pl.seg_len, pl.slot_floats, pr.a,
                                                         pr.b);
-        tc.mark("bwd_dkv");
     }
+    tc.mark("bwd_dkv");
     return launch_status();
 }
 
