@@ -65,22 +65,39 @@ struct Stager {
     static constexpr int C = F::C;
     u4v raw[4];
 
-    // `mine`: this thread's half stages this tensor (wave-uniform).
-    __device__ __forceinline__ void load(bool mine, const T *X, long c0, long row_end)
+    // `mine`: this thread's half stages this tensor (wave-uniform).  X is the slice's base
+    // and has N rows; chunk rows at or beyond row_end are not wanted (clip() zeroes them
+    // later) and whatever valid row is cheapest to address is read for them.  Nothing here
+    // looks at the loaded values, so the loads stay in flight until the tile is written.
+    __device__ __forceinline__ void load(bool mine, const T *X, long c0, long row_end, int N)
     {
-        if (!mine) return;
+        if (!mine || c0 >= row_end) return;
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        if (c0 + C <= N) {
+            // uniform chunk base + one per-thread offset + constant row strides
+            const T *base = X + (size_t)c0 * D;
+            const unsigned off = (unsigned)(4 * rq * D + dg * F::EPV);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const long r = c0 + 4 * rq + i;
-            const bool ok = r < row_end;
-            // one 16-byte load per unit; rows past the end read row 0 and are zeroed
-            const u4v *src =
-                reinterpret_cast<const u4v *>(X + (size_t)(ok ? r : 0) * D + dg * F::EPV);
-            u4v v = *src;
-            if (!ok) v = u4v{0u, 0u, 0u, 0u};
-            raw[i] = v;
+            for (int i = 0; i < 4; ++i)
+                raw[i] = *reinterpret_cast<const u4v *>(base + off + i * D);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                long r = c0 + 4 * rq + i;
+                r = r < N ? r : N - 1;
+                raw[i] = *reinterpret_cast<const u4v *>(X + (size_t)r * D + dg * F::EPV);
+            }
         }
+    }
+
+    // Zero the rows at or beyond row_end; only the last chunk of a segment has any.
+    __device__ __forceinline__ void clip(long c0, long row_end)
+    {
+        if (c0 + C <= row_end) return;
+        const int rq = (threadIdx.x % F::HT) / F::GPR;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (c0 + 4 * rq + i >= row_end) raw[i] = u4v{0u, 0u, 0u, 0u};
     }
 
     // Element e of unit u as a float.
@@ -376,7 +393,7 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 // backward pass takes the TRANSPOSED variant, [S^T | z], for its ascending sweep.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool TRANSPOSED>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_kv_state(
+__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
     int nseg_run, int seg_len, size_t slot_floats, int slot_shift)
 {
@@ -388,8 +405,9 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_kv_state(
     const T *Kp = K + (size_t)bh * N * D, *Vp = V + (size_t)bh * N * D;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
-    const bool h0 = t < F::HT;
+    const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
+    const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
+    const bool h0 = w < F::NW / 2;  // first or second staging half
 
     Blk st[NRB];
 #pragma unroll
@@ -397,12 +415,13 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_kv_state(
     float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
 
     Stager<T, D> s1;  // half 0: K, half 1: V
-    s1.load(true, h0 ? Kp : Vp, row0, row1);
+    s1.load(true, h0 ? Kp : Vp, row0, row1, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
+        s1.clip(c0, row1);
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
-        s1.load(true, h0 ? Kp : Vp, c0 + C, row1);  // next chunk, in flight during the products
+        s1.load(true, h0 ? Kp : Vp, c0 + C, row1, N);  // next chunk, in flight during the products
         if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, KTt, w, c, g);
         else outer_update<T, D>(st, KTt, VTt, w, c, g);
         if (t < D) {
@@ -429,7 +448,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_kv_state(
 //   then S += K_c^T V_c, z += sum k, p += sum v
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
+__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, int N, int nseg, int seg_len,
     size_t slot_floats, float a, float b)
@@ -453,8 +472,9 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
     float *Gp = G + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
-    const bool h0 = t < F::HT;
+    const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
+    const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
+    const bool h0 = w < F::NW / 2;  // first or second staging half
 
     // initial state from the scanned slot: S[r][j], j = 16w + c
     const bool zero_init = CAUSAL && seg == 0;
@@ -471,10 +491,12 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
 
     // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
     Stager<T, D> s1, s2;
-    s1.load(CAUSAL || h0, h0 ? Qp : Kp, row0, row1);
-    if constexpr (CAUSAL) s2.load(h0, Vp, row0, row1);
+    s1.load(CAUSAL || h0, h0 ? Qp : Kp, row0, row1, N);
+    if constexpr (CAUSAL) s2.load(h0, Vp, row0, row1, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
+        s1.clip(c0, row1);
+        if constexpr (CAUSAL) s2.clip(c0, row1);
         if (h0) {
             s1.store_rows(Qs);
             if constexpr (CAUSAL) s2.store_cols(VTt);
@@ -483,8 +505,8 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_fwd_apply(
             s1.store_cols(KTt);
         }
         __syncthreads();
-        s1.load(CAUSAL || h0, h0 ? Qp : Kp, c0 + C, row1);  // next chunk, in flight meanwhile
-        if constexpr (CAUSAL) s2.load(h0, Vp, c0 + C, row1);
+        s1.load(CAUSAL || h0, h0 ? Qp : Kp, c0 + C, row1, N);  // next chunk, in flight meanwhile
+        if constexpr (CAUSAL) s2.load(h0, Vp, c0 + C, row1, N);
 
         // ---- phase A: weight blocks P = tril(a + b Q K^T), q.z, column sums ----
         if constexpr (CAUSAL) {
@@ -594,7 +616,7 @@ struct BwdSlot {
 // that will start from them.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
+__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
@@ -622,8 +644,9 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
     float *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
-    const bool h0 = t < F::HT;
+    const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
+    const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
+    const bool h0 = w < F::NW / 2;  // first or second staging half
     const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
     const bool need_R = CAUSAL ? (seg > 0) : true;  // segment 0's sums start no one
 
@@ -648,20 +671,29 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
     f4v g4 = {1.f, 1.f, 1.f, 1.f};  // half 0: g of this thread's four rows
     const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = h0 ? Op : Kp;
     auto fetch = [&](long c0) {
-        s1.load(h0 || CAUSAL || need_R, p1, c0, row1);
-        s2.load(h0 || CAUSAL, p2, c0, row1);
-        if constexpr (CAUSAL) s3.load(h0 && need_R, Qp, c0, row1);
-        if (h0) {
+        s1.load(h0 || CAUSAL || need_R, p1, c0, row1, N);
+        s2.load(h0 || CAUSAL, p2, c0, row1, N);
+        if constexpr (CAUSAL) s3.load(h0 && need_R, Qp, c0, row1, N);
+        if (h0 && c0 < row1) {
+            if (c0 + C <= N) {
+                const float *gb = Gp + c0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const long r = c0 + 4 * rq + i;
-                g4[i] = r < row1 ? Gp[r] : 1.f;
+                for (int i = 0; i < 4; ++i) g4[i] = gb[4 * rq + i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const long r = c0 + 4 * rq + i;
+                    g4[i] = Gp[r < N ? r : N - 1];
+                }
             }
         }
     };
     fetch(row0);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
+        s1.clip(c0, row1);
+        s2.clip(c0, row1);
+        if constexpr (CAUSAL) s3.clip(c0, row1);
         if (h0) {
             f4v r4;
 #pragma unroll
@@ -730,22 +762,25 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
         }
 
         // ---- phase B: per row block S dO^T + K^T Cm'^T (rows r, columns i), scale, store ----
-        {
-            Blk acc[NB];
+        // (two row blocks at a time: bounds the accumulators and fragments alive at once)
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) acc[ib].zero();
-            state_product<T, D, NB>(acc, st, 1.f, dOs, c, g);
+        for (int i0 = 0; i0 < NB; i0 += 2) {
+            Blk acc[2];
+            acc[0].zero();
+            acc[1].zero();
+            state_product<T, D, 2>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
+            for (int ii = 0; ii < 2; ++ii) {
+                const int ib = i0 + ii;
                 if constexpr (CAUSAL)
-                    chunk_product<T, D, 1, PP>(acc[ib], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
+                    chunk_product<T, D, 1, PP>(acc[ii], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
                                                ((ib + 1) * 16 + KT - 1) / KT, c, g);
                 const int r_loc = ib * 16 + c;
                 const float sc = b * rs[r_loc], di = dl[r_loc];
                 store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
-                               (int)(row1 - c0) - ib * 16, l, sc * (acc[ib].get(0) - di * z4[0]),
-                               sc * (acc[ib].get(1) - di * z4[1]), sc * (acc[ib].get(2) - di * z4[2]),
-                               sc * (acc[ib].get(3) - di * z4[3]));
+                               (int)(row1 - c0) - ib * 16, l, sc * (acc[ii].get(0) - di * z4[0]),
+                               sc * (acc[ii].get(1) - di * z4[1]), sc * (acc[ii].get(2) - di * z4[2]),
+                               sc * (acc[ii].get(3) - di * z4[3]));
             }
         }
         if constexpr (CAUSAL) {
@@ -755,7 +790,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
         if (need_R) {
 #pragma unroll
             for (int pl = 0; pl < PP; ++pl)
-                outer_update<T, D, 2>(accR, QTt, OHt + pl * TSZ, w, c, g);
+                outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2>(accR, QTt, OHt + pl * TSZ, w, c, g);
             if (t < D) {
                 vecR += tile_row_sum<T, D>(OHt, t);
                 if constexpr (PP == 2) vecR += tile_row_sum<T, D>(OHt + TSZ, t);
@@ -788,7 +823,7 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dq(
 // columns r for dK (contraction over j).
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
+__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
@@ -813,8 +848,9 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
-    const int t = threadIdx.x, w = t / 64, l = t % 64, c = l % 16, g = l / 16;
-    const bool h0 = t < F::HT;
+    const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
+    const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
+    const bool h0 = w < F::NW / 2;  // first or second staging half
 
     const bool zero_init = CAUSAL && seg == nseg - 1;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
@@ -840,8 +876,8 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
     float g_next = 1.f, d_next = 0.f;
     {
         const long cl = row0 + (nchunks - 1) * C;  // the sweep starts at the last chunk
-        s1.load(CAUSAL || h0, h0 ? Kp : Qp, cl, row1);
-        s2.load(CAUSAL || h0, h0 ? Vp : dOp, cl, row1);
+        s1.load(CAUSAL || h0, h0 ? Kp : Qp, cl, row1, N);
+        s2.load(CAUSAL || h0, h0 ? Vp : dOp, cl, row1, N);
         if (CAUSAL && t < C && cl + t < row1) {
             g_next = Gp[cl + t];
             d_next = dp[cl + t];
@@ -860,6 +896,8 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
             }
             __syncthreads();
         }
+        s1.clip(c0, row1);
+        s2.clip(c0, row1);
         if (h0) {
             s1.store_rows(Ks);
             s2.store_rows(Vs);
@@ -874,8 +912,8 @@ __global__ __launch_bounds__((FC<T, D>::NT)) void kf_bwd_dkv(
             // next chunk of the descending sweep (none after the first chunk of the segment)
             const long cn = c0 - C;
             const long end_n = ci > 0 ? row1 : cn;  // end <= start: nothing is loaded
-            s1.load(CAUSAL || h0, h0 ? Kp : Qp, cn, end_n);
-            s2.load(CAUSAL || h0, h0 ? Vp : dOp, cn, end_n);
+            s1.load(CAUSAL || h0, h0 ? Kp : Qp, cn, end_n, N);
+            s2.load(CAUSAL || h0, h0 ? Vp : dOp, cn, end_n, N);
             if (CAUSAL && t < C && ci > 0) {
                 g_next = Gp[cn + t];
                 d_next = dp[cn + t];
