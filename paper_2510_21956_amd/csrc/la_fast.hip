@@ -15,6 +15,8 @@
 // Output blocks are computed transposed (accumulator rows = output columns), so
 // that a lane ends up with four consecutive columns of one output row and
 // stores them as one vector.
+#include <type_traits>
+
 #include "la_common.h"
 #include "la_mma.h"
 
@@ -47,6 +49,8 @@ struct FC {
     // groups of row d are stored XOR-swizzled by swz(d); readers apply the same swizzle.
     static constexpr int SWM = C / 8;  // swizzle values: 0 .. SWM-1 (= k-tile width in groups)
     static __device__ __forceinline__ int swz(int d) { return (d / (2 * EPV)) % SWM; }
+    // For row d = r0 + c with r0 a multiple of 16 and c < 16: swz(d) = swz(r0) ^ swz(c).
+    static_assert(16 % (2 * EPV) == 0, "a 16-row block covers whole swizzle steps");
     static_assert(HT / GPR == C / 4, "each half of the workgroup stages one C x D tile");
     static_assert(D % KT == 0 && C % KT == 0, "tile sizes");
     static_assert(NT >= 2 * D, "vector sums use threads [0, 2D)");
@@ -65,28 +69,22 @@ struct Stager {
     static constexpr int C = F::C;
     u4v raw[4];
 
-    // `mine`: this thread's half stages this tensor (wave-uniform).  X is the slice's base
-    // and has N rows; chunk rows at or beyond row_end are not wanted (clip() zeroes them
-    // later) and whatever valid row is cheapest to address is read for them.  Nothing here
-    // looks at the loaded values, so the loads stay in flight until the tile is written.
-    __device__ __forceinline__ void load(bool mine, const T *X, long c0, long row_end, int N)
+    // Request this thread's part of chunk rows [c0, c0 + C) of X, the base of a slice of N
+    // rows (c0 < N); rows beyond the slice read its last row instead.  Deliberately
+    // unconditional and blind to the loaded values: the registers are then written by
+    // nothing but these loads, which stay in flight until the tile is written.  (A load
+    // under a branch, or a value patched after loading, makes the compiler wait for the
+    // data right here.)  A half with no tensor of its own for a stager requests the other
+    // half's: the same lines at the same time, so no extra memory traffic.
+    __device__ __forceinline__ void load(const T *X, long c0, int N)
     {
-        if (!mine || c0 >= row_end) return;
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
-        if (c0 + C <= N) {
-            // uniform chunk base + one per-thread offset + constant row strides
-            const T *base = X + (size_t)c0 * D;
-            const unsigned off = (unsigned)(4 * rq * D + dg * F::EPV);
+        const T *base = X + (size_t)c0 * D;
+        const int last = N - 1 - (int)c0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                raw[i] = *reinterpret_cast<const u4v *>(base + off + i * D);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                long r = c0 + 4 * rq + i;
-                r = r < N ? r : N - 1;
-                raw[i] = *reinterpret_cast<const u4v *>(X + (size_t)r * D + dg * F::EPV);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int rl = min(4 * rq + i, last);
+            raw[i] = *reinterpret_cast<const u4v *>(base + (unsigned)(rl * D + dg * F::EPV));
         }
     }
 
@@ -188,7 +186,9 @@ __device__ __forceinline__ float tile_row_sum(const T *tr, int r)
     return s;
 }
 
-// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.
+// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.  The loop is
+// kept rolled: unrolled, each step's un-swizzled weight address would sit in a register
+// of its own for the whole kernel.
 template <typename T, int D>
 __device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *wgt)
 {
@@ -196,13 +196,34 @@ __device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *w
     typedef typename Vec4<T>::type V4;
     float s = 0.f;
     const int sw = F::swz(r);
-#pragma unroll
-    for (int n = 0; n < F::C; n += 4) {
-        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
-        f4v x = *reinterpret_cast<const f4v *>(wgt + 4 * ((n / 4) ^ sw));
+#pragma unroll 1
+    for (int m = 0; m < F::C / 4; ++m) {
+        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m);
+        f4v x = *reinterpret_cast<const f4v *>(wgt + 4 * (m ^ sw));
         s += (to_float(v[0]) * x[0] + to_float(v[1]) * x[1]) +
              (to_float(v[2]) * x[2] + to_float(v[3]) * x[3]);
     }
+    return s;
+}
+
+// Sum over each aligned group of WIDTH consecutive lanes, result in every lane of the
+// group.  Up to 16 lanes this is data-parallel-primitive moves inside the vector ALU
+// (swap neighbours, swap pairs, mirror the half row, mirror the row: after each step all
+// lanes that already shared a partial sum still do); beyond that, lane shuffles.
+template <int WIDTH>
+__device__ __forceinline__ float reduce_adjacent(float s)
+{
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(
+            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                               0xf, 0xf, true));
+    };
+    if constexpr (WIDTH >= 2) s += dpp(s, std::integral_constant<int, 0xB1>{});   // quad_perm 1,0,3,2
+    if constexpr (WIDTH >= 4) s += dpp(s, std::integral_constant<int, 0x4E>{});   // quad_perm 2,3,0,1
+    if constexpr (WIDTH >= 8) s += dpp(s, std::integral_constant<int, 0x141>{});  // row_half_mirror
+    if constexpr (WIDTH >= 16) s += dpp(s, std::integral_constant<int, 0x140>{}); // row_mirror
+    if constexpr (WIDTH >= 32) s += __shfl_xor(s, 16);
+    if constexpr (WIDTH >= 64) s += __shfl_xor(s, 32);
     return s;
 }
 
@@ -234,30 +255,48 @@ typedef Acc<16> Blk;  // 16 x 16 accumulator block: lane (c, g) holds rows 4g..4
 // st[rb] += A_rb B^T over the C chunk rows: A = transposed tile `at` (row block rb),
 // B = transposed tile `bt` (rows 16w + c), both [D][LDT] with the chunk row contiguous.
 // This is the rank-C update of the 16 columns of a running state that wave w owns.
-template <typename T, int D, int GRP = 4>  // GRP row blocks per pass bounds the fragments in flight
-__device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, const T *bt, int w,
-                                             int c, int g)
+// Either operand may be an intermediate split over NAP resp. NBP planes (plane strides
+// aps, bps); every fragment is read once and used for all the planes of the other side.
+template <typename T, int D, int GRP = 4, int NAP = 1, int NBP = 1>  // GRP row blocks per pass
+__device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int aps, const T *bt,
+                                             int bps, int w, int c, const SwzLane &ql, SwzOff wo)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDT = F::LDT, C = F::C;
-    typedef XsY<M, GRP> B;
+    static_assert(NAP == 1 || NBP == 1, "products of two second planes are never needed");
+    typedef XsYs<M, GRP * NAP, NBP> B;
+    // An offset of zero the compiler cannot see through: the fragment addresses below are
+    // then worked out here, a few integer adds, instead of each being kept in a register of
+    // its own across the whole chunk loop.
+    int lane0 = c * LDT;
+    asm volatile("" : "+v"(lane0));
 #pragma unroll
     for (int r0 = 0; r0 < NRB; r0 += GRP) {
         pipeline<C / KT>(
             C / KT,
             [&](int kt) {
                 B b;
-                b.y = M::load_swz(bt + (w * 16 + c) * LDT + kt * KT, g, F::swz(w * 16 + c));
+#pragma unroll
+                for (int q = 0; q < NBP; ++q)
+                    b.y[q] = M::load_off(bt + q * bps + w * 16 * LDT + lane0 + kt * KT, wo);
 #pragma unroll
                 for (int rb = 0; rb < GRP; ++rb)
-                    b.x[rb] = M::load_swz(at + ((r0 + rb) * 16 + c) * LDT + kt * KT, g,
-                                          F::swz((r0 + rb) * 16 + c));
+#pragma unroll
+                    for (int q = 0; q < NAP; ++q)
+                        b.x[rb * NAP + q] =
+                            M::load_swz(at + q * aps + (r0 + rb) * 16 * LDT + lane0 + kt * KT, ql,
+                                        F::swz((r0 + rb) * 16));
                 return b;
             },
             [&](int, const B &b) {
 #pragma unroll
-                for (int rb = 0; rb < GRP; ++rb) M::mma(st[r0 + rb], b.x[rb], b.y);
+                for (int rb = 0; rb < GRP; ++rb)
+#pragma unroll
+                    for (int qa = 0; qa < NAP; ++qa)
+#pragma unroll
+                        for (int qb = 0; qb < NBP; ++qb)
+                            M::mma(st[r0 + rb], b.x[rb * NAP + qa], b.y[qb]);
             });
     }
 }
@@ -314,20 +353,22 @@ __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, con
 // planes are dropped.
 template <typename T, int D, int NXP, int NYP>
 __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, int xr, const T *yt,
-                                              int yps, int yr, int kt0, int kt1, int c, int g)
+                                              int yps, int yr, int kt0, int kt1, int c, int g,
+                                              SwzOff xo)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int KT = F::KT, LDT = F::LDT, C = F::C;
     typedef XsYs<M, NXP, NYP> B;
+    int lane0 = c * LDT;  // opaque to the compiler, see outer_update
+    asm volatile("" : "+v"(lane0));
     pipeline<C / KT>(
         kt1 - kt0,
         [&](int s) {
             B b;
 #pragma unroll
             for (int p = 0; p < NXP; ++p)
-                b.x[p] = M::load_swz(xt + p * xps + (xr + c) * LDT + (kt0 + s) * KT, g,
-                                     F::swz(xr + c));
+                b.x[p] = M::load_off(xt + p * xps + xr * LDT + lane0 + (kt0 + s) * KT, xo);
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
                 b.y[p] = M::load(yt + p * yps + (yr + c) * LDT + (kt0 + s) * KT, g);
@@ -408,6 +449,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
+    // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
+    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     Blk st[NRB];
 #pragma unroll
@@ -415,15 +459,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
 
     Stager<T, D> s1;  // half 0: K, half 1: V
-    s1.load(true, h0 ? Kp : Vp, row0, row1, N);
+    const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
+    s1.load(h0 ? Kp : Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         s1.clip(c0, row1);
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
-        s1.load(true, h0 ? Kp : Vp, c0 + C, row1, N);  // next chunk, in flight during the products
-        if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, KTt, w, c, g);
-        else outer_update<T, D>(st, KTt, VTt, w, c, g);
+        // next chunk, in flight during the products (after the last one: that one again)
+        s1.load(h0 ? Kp : Vp, min(c0 + C, c_last), N);
+        if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
+        else outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, ql, wo);
         if (t < D) {
             if constexpr (!TRANSPOSED) vec += tile_row_sum<T, D>(VTt, t);
         } else if (t < 2 * D) {
@@ -475,6 +521,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
+    // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
+    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     // initial state from the scanned slot: S[r][j], j = 16w + c
     const bool zero_init = CAUSAL && seg == 0;
@@ -491,8 +540,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
 
     // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
     Stager<T, D> s1, s2;
-    s1.load(CAUSAL || h0, h0 ? Qp : Kp, row0, row1, N);
-    if constexpr (CAUSAL) s2.load(h0, Vp, row0, row1, N);
+    const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
+    const T *p1 = (h0 || !CAUSAL) ? Qp : Kp;
+    s1.load(p1, row0, N);
+    if constexpr (CAUSAL) s2.load(Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
         s1.clip(c0, row1);
@@ -505,8 +556,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             s1.store_cols(KTt);
         }
         __syncthreads();
-        s1.load(CAUSAL || h0, h0 ? Qp : Kp, c0 + C, row1, N);  // next chunk, in flight meanwhile
-        if constexpr (CAUSAL) s2.load(h0, Vp, c0 + C, row1, N);
+        // next chunk, in flight meanwhile (after the last one: that one again)
+        s1.load(p1, min(c0 + C, c_last), N);
+        if constexpr (CAUSAL) s2.load(Vp, min(c0 + C, c_last), N);
 
         // ---- phase A: weight blocks P = tril(a + b Q K^T), q.z, column sums ----
         if constexpr (CAUSAL) {
@@ -577,7 +629,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             for (int ib = 0; ib < NB; ++ib) {
                 if constexpr (CAUSAL)
                     chunk_product<T, D, 1, PP>(facc[ib], VTt, 0, w * 16, Ps, PSZ, ib * 16, 0,
-                                               ((ib + 1) * 16 + KT - 1) / KT, c, g);
+                                               ((ib + 1) * 16 + KT - 1) / KT, c, g, wo);
                 const float gi = ginv[w][ib * 16 + c];
                 store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
                                (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi,
@@ -586,7 +638,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             }
         }
         if constexpr (CAUSAL) {
-            outer_update<T, D>(st, KTt, VTt, w, c, g);
+            outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, ql, wo);
             p4 += a * *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
             if (t >= D && t < 2 * D) zs[t - D] += csk[t - D];
         }
@@ -647,6 +699,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
+    // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
+    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
     const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
     const bool need_R = CAUSAL ? (seg > 0) : true;  // segment 0's sums start no one
 
@@ -665,28 +720,20 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     for (int rb = 0; rb < NRB; ++rb) accR[rb].zero();
     float vecR = 0.f;  // t < D: w[t];  D <= t < 2D: u[t-D]
 
-    // staging: half 0: dO (rows, scaled columns), O (for dprime), Q (columns);
-    //          half 1: V (rows and columns), K (columns); unmasked: Q instead, no K
+    // staging: half 0: dO (rows, scaled columns) and O (for dprime);
+    //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
     Stager<T, D> s1, s2, s3;
-    f4v g4 = {1.f, 1.f, 1.f, 1.f};  // half 0: g of this thread's four rows
-    const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = h0 ? Op : Kp;
+    f4v g4 = {1.f, 1.f, 1.f, 1.f};  // g of this thread's four rows
+    const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
+    const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     auto fetch = [&](long c0) {
-        s1.load(h0 || CAUSAL || need_R, p1, c0, row1, N);
-        s2.load(h0 || CAUSAL, p2, c0, row1, N);
-        if constexpr (CAUSAL) s3.load(h0 && need_R, Qp, c0, row1, N);
-        if (h0 && c0 < row1) {
-            if (c0 + C <= N) {
-                const float *gb = Gp + c0;
+        s1.load(p1, c0, N);
+        s2.load(p2, c0, N);
+        if constexpr (CAUSAL) s3.load(Qp, c0, N);
+        const float *gb = Gp + c0;
+        const int last = N - 1 - (int)c0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) g4[i] = gb[4 * rq + i];
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const long r = c0 + 4 * rq + i;
-                    g4[i] = Gp[r < N ? r : N - 1];
-                }
-            }
-        }
+        for (int i = 0; i < 4; ++i) g4[i] = gb[(unsigned)min(4 * rq + i, last)];
     };
     fetch(row0);
     for (long c0 = row0; c0 < row1; c0 += C) {
@@ -697,7 +744,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
         if (h0) {
             f4v r4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r4[i] = (c0 + 4 * rq + i < row1) ? 1.f / g4[i] : 0.f;
+            for (int i = 0; i < 4; ++i)
+                r4[i] = (c0 + 4 * rq + i < row1) ? __builtin_amdgcn_rcpf(g4[i]) : 0.f;
             // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
             // lanes that share the row
 #pragma unroll
@@ -706,8 +754,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
 #pragma unroll
                 for (int e = 0; e < F::EPV; ++e)
                     s += Stager<T, D>::elem(s2.raw[i], e) * Stager<T, D>::elem(s1.raw[i], e);
-#pragma unroll
-                for (int m = 1; m < F::GPR; m <<= 1) s += __shfl_xor(s, m);
+                s = reduce_adjacent<F::GPR>(s);
                 if (dg == 0) {
                     const int r = 4 * rq + i;
                     rs[r] = r4[i];
@@ -717,19 +764,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
                 }
             }
             s1.store_rows(dOs);
-            if (need_R) {
-                s1.store_cols_scaled(OHt, TSZ, r4);
-                if constexpr (CAUSAL) s3.store_cols(QTt);
-            }
+            if (need_R) s1.store_cols_scaled(OHt, TSZ, r4);
         } else if constexpr (CAUSAL) {
             s1.store_rows(Vs);
             s1.store_cols(VTt);
             s2.store_cols(KTt);
+            if (need_R) s3.store_cols(QTt);
         } else {
             s1.store_cols(QTt);
         }
         __syncthreads();
-        fetch(c0 + C);  // next chunk, in flight meanwhile
+        fetch(min(c0 + C, c_last));  // next chunk, in flight meanwhile (at the end: the last again)
 
         // ---- phase A: weight blocks Cm' (rows n, columns i), column sums of K ----
         if constexpr (CAUSAL) {
@@ -774,7 +819,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
                 const int ib = i0 + ii;
                 if constexpr (CAUSAL)
                     chunk_product<T, D, 1, PP>(acc[ii], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
-                                               ((ib + 1) * 16 + KT - 1) / KT, c, g);
+                                               ((ib + 1) * 16 + KT - 1) / KT, c, g, wo);
                 const int r_loc = ib * 16 + c;
                 const float sc = b * rs[r_loc], di = dl[r_loc];
                 store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
@@ -784,13 +829,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
             }
         }
         if constexpr (CAUSAL) {
-            outer_update<T, D>(st, VTt, KTt, w, c, g);
+            outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
             z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
         if (need_R) {
-#pragma unroll
-            for (int pl = 0; pl < PP; ++pl)
-                outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2>(accR, QTt, OHt + pl * TSZ, w, c, g);
+            outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
             if (t < D) {
                 vecR += tile_row_sum<T, D>(OHt, t);
                 if constexpr (PP == 2) vecR += tile_row_sum<T, D>(OHt + TSZ, t);
@@ -835,11 +878,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     constexpr int C = F::C, NW = F::NW, NB = F::NB, NRB = F::NRB, KT = F::KT;
     constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT, TSZ = D * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;
-    __shared__ __align__(16) T Ks[C * LDR], Vs[C * LDR];
-    __shared__ __align__(16) T Qs[TS * C * LDR + 4], dOs[TS * C * LDR + 4];
-    __shared__ __align__(16) T QTt[TS * TSZ + 4], OHt[TS * PP * TSZ + 4];
-    __shared__ __align__(16) T CmT[TS * PP * PSZ + 4], WT[TS * PP * PSZ + 4];
-    __shared__ __align__(16) float rs[C], dl[C], dls[C], csu[D], csw[D];  // 1/g, dprime, delta
+    // One LDS block laid out by hand, small arrays first: addresses are then a lane offset
+    // plus a constant the instruction can carry, instead of one base register per array.
+    constexpr int RM = C * LDR;  // elements of a row-major tile
+    constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ);
+    __shared__ __align__(16) unsigned char lds[(3 * C + 2 * D) * 4 + NELEM * sizeof(T)];
+    float *rs = reinterpret_cast<float *>(lds), *dl = rs + C, *dls = dl + C;  // 1/g, dprime, delta
+    float *csu = dls + C, *csw = csu + D;
+    T *CmT = reinterpret_cast<T *>(csw + D), *WT = CmT + TS * PP * PSZ;
+    T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
+    T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -851,6 +899,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
+    // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
+    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     const bool zero_init = CAUSAL && seg == nseg - 1;
     const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
@@ -870,55 +921,63 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
         w4 = a * *reinterpret_cast<const f4v *>(slot + SL::W + w * 16 + 4 * g);
     }
 
-    // staging: half 0: K (rows), V (rows); half 1: Q (rows, columns), dO (rows, scaled columns)
+    // staging: half 0: K (rows), Q (rows, columns); half 1: V (rows), dO (rows, scaled
+    // columns) and the row factors; unmasked: K and V only
     const long nchunks = (row1 - row0 + C - 1) / C;
+    const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
     Stager<T, D> s1, s2;
-    float g_next = 1.f, d_next = 0.f;
-    {
-        const long cl = row0 + (nchunks - 1) * C;  // the sweep starts at the last chunk
-        s1.load(CAUSAL || h0, h0 ? Kp : Qp, cl, row1, N);
-        s2.load(CAUSAL || h0, h0 ? Vp : dOp, cl, row1, N);
-        if (CAUSAL && t < C && cl + t < row1) {
-            g_next = Gp[cl + t];
-            d_next = dp[cl + t];
+    const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
+    f4v g4 = {1.f, 1.f, 1.f, 1.f}, d4 = {0.f, 0.f, 0.f, 0.f};  // g, dprime of this thread's rows
+    auto fetch = [&](long c0) {
+        s1.load(p1, c0, N);
+        if constexpr (CAUSAL) {
+            s2.load(p2, c0, N);
+            const float *gb = Gp + c0, *db = dp + c0;
+            const int last = N - 1 - (int)c0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned r = (unsigned)min(4 * rq + i, last);
+                g4[i] = gb[r];
+                d4[i] = db[r];
+            }
         }
-    }
+    };
+    fetch(row0 + (nchunks - 1) * C);  // the sweep starts at the last chunk
     for (long ci = nchunks - 1; ci >= 0; --ci) {
         const long c0 = row0 + ci * C;
         __syncthreads();
-        if constexpr (CAUSAL) {
-            if (t < C) {
-                const bool ok = c0 + t < row1;
-                const float r = ok ? 1.f / g_next : 0.f, d = ok ? d_next : 0.f;
-                rs[t] = r;
-                dl[t] = d;
-                dls[t] = d * r;
-            }
-            __syncthreads();
-        }
         s1.clip(c0, row1);
-        s2.clip(c0, row1);
+        if constexpr (CAUSAL) s2.clip(c0, row1);
         if (h0) {
             s1.store_rows(Ks);
-            s2.store_rows(Vs);
-        } else if constexpr (CAUSAL) {
-            s1.store_rows(Qs);
-            s1.store_cols(QTt);
-            s2.store_rows(dOs);
-            s2.store_cols_scaled(OHt, TSZ, *reinterpret_cast<const f4v *>(rs + 4 * ((t % F::HT) / F::GPR)));
-        }
-        __syncthreads();
-        {
-            // next chunk of the descending sweep (none after the first chunk of the segment)
-            const long cn = c0 - C;
-            const long end_n = ci > 0 ? row1 : cn;  // end <= start: nothing is loaded
-            s1.load(CAUSAL || h0, h0 ? Kp : Qp, cn, end_n, N);
-            s2.load(CAUSAL || h0, h0 ? Vp : dOp, cn, end_n, N);
-            if (CAUSAL && t < C && ci > 0) {
-                g_next = Gp[cn + t];
-                d_next = dp[cn + t];
+            if constexpr (CAUSAL) {
+                s2.store_rows(Qs);
+                s2.store_cols(QTt);
+            }
+        } else {
+            s1.store_rows(Vs);
+            if constexpr (CAUSAL) {
+                f4v r4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool ok = c0 + 4 * rq + i < row1;
+                    r4[i] = ok ? __builtin_amdgcn_rcpf(g4[i]) : 0.f;
+                    if (dg == 0) {
+                        const int r = 4 * rq + i;
+                        const float d = ok ? d4[i] : 0.f;
+                        rs[r] = r4[i];
+                        dl[r] = d;
+                        dls[r] = d * r4[i];
+                    }
+                }
+                s2.store_rows(dOs);
+                s2.store_cols_scaled(OHt, TSZ, r4);
             }
         }
+        __syncthreads();
+        // next chunk of the descending sweep, in flight meanwhile (after the first chunk of
+        // the segment: that one again)
+        fetch(ci > 0 ? c0 - C : c0);
 
         // ---- phase A: weight blocks Cm and W (rows i, columns n), column sums ----
         if constexpr (CAUSAL) {
@@ -973,13 +1032,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
             state_product<T, D, 1>(av, Ra, b, Ks + nb * 16 * LDR, c, g);
             if constexpr (CAUSAL) {
                 chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
-                                           (nb * 16) / KT, C / KT, c, g);
+                                           (nb * 16) / KT, C / KT, c, g, wo);
                 // both operands are intermediates: hi (hi + lo), then lo hi
                 chunk_product<T, D, 1, PP>(av[0], OHt, 0, w * 16, WT, PSZ, nb * 16,
-                                           (nb * 16) / KT, C / KT, c, g);
+                                           (nb * 16) / KT, C / KT, c, g, wo);
                 if constexpr (PP == 2)
                     chunk_product<T, D, 1, 1>(av[0], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
-                                              (nb * 16) / KT, C / KT, c, g);
+                                              (nb * 16) / KT, C / KT, c, g, wo);
             }
             const size_t o = (size_t)(c0 + nb * 16) * D;
             const int valid = (int)(row1 - c0) - nb * 16;
@@ -990,11 +1049,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
                            av[0].get(1) + w4[1], av[0].get(2) + w4[2], av[0].get(3) + w4[3]);
         }
         if constexpr (CAUSAL) {
-#pragma unroll
-            for (int pl = 0; pl < PP; ++pl) {
-                outer_update<T, D, 2>(Ra, QTt, OHt + pl * TSZ, w, c, g);
-                outer_update<T, D, 2>(Rb, OHt + pl * TSZ, QTt, w, c, g);
-            }
+            outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
+            outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
             u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
             w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
         }

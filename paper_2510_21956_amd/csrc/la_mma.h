@@ -70,6 +70,24 @@ __device__ __forceinline__ int acc_row(int i, int g)
 }
 
 // ---- operand fragments and the MFMA itself ------------------------------------
+// Swizzled tiles: element offsets inside a k-tile.  SwzLane is the part of them that
+// depends on the lane, for the four possible low swizzle bits of a row block:
+// q[j] = 4 * (g ^ lane_swizzle ^ j).  With it a fragment address is one of four lane
+// registers plus a constant, whatever the row block.  SwzOff is a fully resolved row.
+struct SwzLane {
+    int q[4];
+};
+struct SwzOff {
+    int lo, hi;
+};
+__device__ __forceinline__ SwzLane make_swz_lane(int g, int lane_sw)
+{
+    SwzLane r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r.q[j] = 4 * (g ^ lane_sw ^ j);
+    return r;
+}
+
 template <typename T, int BS>
 struct Mma;
 
@@ -88,11 +106,20 @@ struct Mma<float, BS> {
     {
         return *reinterpret_cast<const f4v *>(p + 4 * g);
     }
-    // The same from a tile whose 4-element column groups are XOR-swizzled by `sw`
-    // (sw < NG, so the swizzle stays inside the k-tile).
-    static __device__ __forceinline__ Frag load_swz(const float *p, int g, int sw)
+    // The same from a tile whose 4-element column groups are XOR-swizzled inside the
+    // k-tile: `lane` holds the lane-dependent part, s0 < NG the row block's constant part.
+    static __device__ __forceinline__ Frag load_swz(const float *p, const SwzLane &lane, int s0)
     {
-        return *reinterpret_cast<const f4v *>(p + 4 * (g ^ sw));
+        return *reinterpret_cast<const f4v *>(p + lane.q[s0 & 3]);
+    }
+    // Offsets of a row whose swizzle is only known at run time, worked out once.
+    static __device__ __forceinline__ SwzOff swz_offsets(int g, int lane_sw, int s0)
+    {
+        return SwzOff{4 * (g ^ lane_sw ^ s0), 0};
+    }
+    static __device__ __forceinline__ Frag load_off(const float *p, SwzOff o)
+    {
+        return *reinterpret_cast<const f4v *>(p + o.lo);
     }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v) { return Frag2{g0}; }
     static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
@@ -144,12 +171,26 @@ struct Mma<__bf16, BS> {
         Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return r;
     }
-    // The same from a tile whose 4-element column groups are XOR-swizzled by `sw`
-    // (sw < 2 * NG, so the swizzle stays inside the k-tile).
-    static __device__ __forceinline__ Frag load_swz(const __bf16 *p, int g, int sw)
+    // The same from a tile whose 4-element column groups are XOR-swizzled inside the
+    // k-tile (s0 < 2 * NG).  The two low bits of the swizzle act on the lane's group
+    // number, the third swaps the two halves of the k-tile, which is a constant offset.
+    static __device__ __forceinline__ Frag load_swz(const __bf16 *p, const SwzLane &lane, int s0)
     {
-        bf4v lo = *reinterpret_cast<const bf4v *>(p + 4 * (g ^ sw));
-        bf4v hi = *reinterpret_cast<const bf4v *>(p + 4 * ((g + NG) ^ sw));
+        const int q = lane.q[s0 & 3], up = (s0 & NG) ? 4 * NG : 0;
+        bf4v lo = *reinterpret_cast<const bf4v *>(p + q + up);
+        bf4v hi = *reinterpret_cast<const bf4v *>(p + q + (4 * NG - up));
+        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return r;
+    }
+    static __device__ __forceinline__ SwzOff swz_offsets(int g, int lane_sw, int s0)
+    {
+        const int sw = lane_sw ^ s0;
+        return SwzOff{4 * (g ^ sw), 4 * ((g + NG) ^ sw)};
+    }
+    static __device__ __forceinline__ Frag load_off(const __bf16 *p, SwzOff o)
+    {
+        bf4v lo = *reinterpret_cast<const bf4v *>(p + o.lo);
+        bf4v hi = *reinterpret_cast<const bf4v *>(p + o.hi);
         Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return r;
     }
