@@ -235,6 +235,19 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
     return x;
 }
 
+// The per-chunk vector sums (column sums of tiles and the like) are cut into jobs of 64
+// rows, one wave each, and dealt out from the last wave downwards: the weight blocks of
+// phase A go to the first waves, so these fill the waves that would otherwise idle there.
+// Job (kind, part) covers rows [64 part, 64 part + 64) of vector number `kind`.
+template <int NW, int D>
+struct VecJobs {
+    static constexpr int PER = D / 64;
+    static __device__ __forceinline__ bool mine(int kind, int part, int w)
+    {
+        return w == NW - 1 - (kind * PER + part) % NW;
+    }
+};
+
 // Fragment bundles of one pipeline step.
 template <typename M, int NX>
 struct XsY {
@@ -312,12 +325,14 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDR = F::LDR;
     typedef Ys<M, NM> B;
+    int lane0 = c * LDR;  // opaque to the compiler, see outer_update
+    asm volatile("" : "+v"(lane0));
     pipeline<D / KT>(
         D / KT,
         [&](int kt) {
             B b;
 #pragma unroll
-            for (int m = 0; m < NM; ++m) b.y[m] = M::load(ys + (m * 16 + c) * LDR + kt * KT, g);
+            for (int m = 0; m < NM; ++m) b.y[m] = M::load(ys + m * 16 * LDR + lane0 + kt * KT, g);
             return b;
         },
         [&](int kt, const B &b) {
@@ -336,12 +351,14 @@ __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, con
     typedef Mma<T, 16> M;
     constexpr int KT = F::KT, LDR = F::LDR;
     typedef XsY<M, 1> B;
+    int lane0 = c * LDR;  // opaque to the compiler, see outer_update
+    asm volatile("" : "+v"(lane0));
     pipeline<D / KT>(
         D / KT,
         [&](int kt) {
             B b;
-            b.x[0] = M::load(xs + (xr + c) * LDR + kt * KT, g);
-            b.y = M::load(ys + (yr + c) * LDR + kt * KT, g);
+            b.x[0] = M::load(xs + xr * LDR + lane0 + kt * KT, g);
+            b.y = M::load(ys + yr * LDR + lane0 + kt * KT, g);
             return b;
         },
         [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
@@ -504,6 +521,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     constexpr int C = F::C, NW = F::NW, NT = F::NT, NB = F::NB, NRB = F::NRB, KT = F::KT;
     constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;  // tiles only the masked path needs shrink to nothing
+    typedef VecJobs<NW, D> VJ;
     __shared__ __align__(16) T Qs[C * LDR];
     __shared__ __align__(16) T Ks[TS * C * LDR + 4];
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
@@ -589,8 +607,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                     if (g == 0) psum[nb][ib * 16 + c] = rs;
                 }
             }
-            if (t < D) csv[t] = tile_row_sum<T, D>(VTt, t);
-            else if (t < 2 * D) csk[t - D] = tile_row_sum<T, D>(KTt, t - D);
+#pragma unroll
+            for (int part = 0; part < VJ::PER; ++part) {
+                if (VJ::mine(0, part, w)) csv[64 * part + l] = tile_row_sum<T, D>(VTt, 64 * part + l);
+                if (VJ::mine(1, part, w)) csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
+            }
         }
         {
             typedef typename Vec4<T>::type V4;
@@ -686,7 +707,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     __shared__ __align__(16) T VTt[TS * TSZ + 4];
     __shared__ __align__(16) T KTt[TS * TSZ + 4];
     __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
-    __shared__ __align__(16) float rs[C], dl[C], dls[C], csk[D];  // 1/g, dprime, delta, sum k
+    // 1/g of the chunk's rows (two buffers: the next chunk's are written while this one's
+    // are still read), dprime, delta, sum k
+    __shared__ __align__(16) float rsb[2][C], dl[C], dls[C], csk[D];
+    typedef VecJobs<NW, D> VJ;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -718,34 +742,35 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     Blk accR[NRB];  // this segment's R: rows r, columns j = 16w + c
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) accR[rb].zero();
-    float vecR = 0.f;  // t < D: w[t];  D <= t < 2D: u[t-D]
+    float vw = 0.f, vu = 0.f;  // on the waves that own those jobs: w[r], u[r]
 
     // staging: half 0: dO (rows, scaled columns) and O (for dprime);
     //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
     Stager<T, D> s1, s2, s3;
-    f4v g4 = {1.f, 1.f, 1.f, 1.f};  // g of this thread's four rows
+    float g_next;  // g of row t % C of the chunk being fetched
     const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     auto fetch = [&](long c0) {
         s1.load(p1, c0, N);
         s2.load(p2, c0, N);
         if constexpr (CAUSAL) s3.load(Qp, c0, N);
-        const float *gb = Gp + c0;
-        const int last = N - 1 - (int)c0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) g4[i] = gb[(unsigned)min(4 * rq + i, last)];
+        g_next = (Gp + c0)[(unsigned)min(t % C, N - 1 - (int)c0)];
+    };
+    // 1/g of the chunk starting at c0 (whose g values have been fetched) into buffer `par`
+    auto post_factors = [&](long c0, int par) {
+        if (t < C) rsb[par][t] = (c0 + t < row1) ? __builtin_amdgcn_rcpf(g_next) : 0.f;
     };
     fetch(row0);
+    post_factors(row0, 0);
+    int par = 0;
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         s1.clip(c0, row1);
         s2.clip(c0, row1);
         if constexpr (CAUSAL) s3.clip(c0, row1);
+        const float *rs = rsb[par];
         if (h0) {
-            f4v r4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                r4[i] = (c0 + 4 * rq + i < row1) ? __builtin_amdgcn_rcpf(g4[i]) : 0.f;
+            const f4v r4 = *reinterpret_cast<const f4v *>(rs + 4 * rq);
             // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
             // lanes that share the row
 #pragma unroll
@@ -757,7 +782,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
                 s = reduce_adjacent<F::GPR>(s);
                 if (dg == 0) {
                     const int r = 4 * rq + i;
-                    rs[r] = r4[i];
                     dl[r] = s;
                     dls[r] = s * r4[i];
                     if (c0 + r < row1) dp[c0 + r] = s;
@@ -802,9 +826,23 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
                     }
                 }
             }
-            if (t < D) csk[t] = tile_row_sum<T, D>(KTt, t);
-            __syncthreads();
+#pragma unroll
+            for (int part = 0; part < VJ::PER; ++part)
+                if (VJ::mine(0, part, w)) csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
         }
+        if (need_R) {
+            // this chunk's share of w = sum OmegaHat and u = sum delta q
+#pragma unroll
+            for (int part = 0; part < VJ::PER; ++part) {
+                const int r = 64 * part + l;
+                if (VJ::mine(1, part, w)) {
+                    vw += tile_row_sum<T, D>(OHt, r);
+                    if constexpr (PP == 2) vw += tile_row_sum<T, D>(OHt + TSZ, r);
+                }
+                if (VJ::mine(2, part, w)) vu += tile_row_dot<T, D>(QTt, r, dls);
+            }
+        }
+        if constexpr (CAUSAL) __syncthreads();
 
         // ---- phase B: per row block S dO^T + K^T Cm'^T (rows r, columns i), scale, store ----
         // (two row blocks at a time: bounds the accumulators and fragments alive at once)
@@ -832,15 +870,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
             outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
             z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
-        if (need_R) {
-            outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
-            if (t < D) {
-                vecR += tile_row_sum<T, D>(OHt, t);
-                if constexpr (PP == 2) vecR += tile_row_sum<T, D>(OHt + TSZ, t);
-            } else if (t < 2 * D) {
-                vecR += tile_row_dot<T, D>(QTt, t - D, dls);
-            }
-        }
+        if (need_R)
+            outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2, 1, PP>(accR, QTt, 0, OHt, TSZ, w,
+                                                                           c, ql, wo);
+        par ^= 1;
+        post_factors(c0 + C, par);
     }
     if (need_R) {
         float *out = ws + ((size_t)bh * nseg + seg - (CAUSAL ? 1 : 0)) * slot_floats;
@@ -852,8 +886,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
                 out[SL::R + r * D + j] = accR[rb].get(i);
                 out[SL::RT + j * D + r] = accR[rb].get(i);
             }
-        if (t < D) out[SL::W + t] = vecR;
-        else if (t < 2 * D) out[SL::U + (t - D)] = vecR;
+#pragma unroll
+        for (int part = 0; part < VJ::PER; ++part) {
+            if (VJ::mine(1, part, w)) out[SL::W + 64 * part + l] = vw;
+            if (VJ::mine(2, part, w)) out[SL::U + 64 * part + l] = vu;
+        }
     }
 }
 
@@ -882,9 +919,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     // plus a constant the instruction can carry, instead of one base register per array.
     constexpr int RM = C * LDR;  // elements of a row-major tile
     constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ);
-    __shared__ __align__(16) unsigned char lds[(3 * C + 2 * D) * 4 + NELEM * sizeof(T)];
-    float *rs = reinterpret_cast<float *>(lds), *dl = rs + C, *dls = dl + C;  // 1/g, dprime, delta
-    float *csu = dls + C, *csw = csu + D;
+    __shared__ __align__(16) unsigned char lds[(6 * C + 2 * D) * 4 + NELEM * sizeof(T)];
+    // 1/g, dprime, delta of the chunk's rows: two buffers of [3][C], the next chunk's being
+    // written while this one's are still read
+    float *fac = reinterpret_cast<float *>(lds);
+    float *csu = fac + 6 * C, *csw = csu + D;
+    typedef VecJobs<NW, D> VJ;
     T *CmT = reinterpret_cast<T *>(csw + D), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
@@ -927,24 +967,33 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
     Stager<T, D> s1, s2;
     const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
-    f4v g4 = {1.f, 1.f, 1.f, 1.f}, d4 = {0.f, 0.f, 0.f, 0.f};  // g, dprime of this thread's rows
+    float g_next = 1.f, d_next = 0.f;  // g, dprime of row t % C of the chunk being fetched
     auto fetch = [&](long c0) {
         s1.load(p1, c0, N);
         if constexpr (CAUSAL) {
             s2.load(p2, c0, N);
-            const float *gb = Gp + c0, *db = dp + c0;
-            const int last = N - 1 - (int)c0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const unsigned r = (unsigned)min(4 * rq + i, last);
-                g4[i] = gb[r];
-                d4[i] = db[r];
-            }
+            const unsigned r = (unsigned)min(t % C, N - 1 - (int)c0);
+            g_next = (Gp + c0)[r];
+            d_next = (dp + c0)[r];
+        }
+    };
+    // row factors of the chunk starting at c0 (already fetched) into buffer `par`
+    auto post_factors = [&](long c0, int par) {
+        if (CAUSAL && t < C) {
+            const bool ok = c0 + t < row1;
+            const float r = ok ? __builtin_amdgcn_rcpf(g_next) : 0.f, d = ok ? d_next : 0.f;
+            float *f = fac + par * 3 * C;
+            f[t] = r;
+            f[C + t] = d;
+            f[2 * C + t] = d * r;
         }
     };
     fetch(row0 + (nchunks - 1) * C);  // the sweep starts at the last chunk
+    post_factors(row0 + (nchunks - 1) * C, 0);
+    int par = 0;
     for (long ci = nchunks - 1; ci >= 0; --ci) {
         const long c0 = row0 + ci * C;
+        const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
         __syncthreads();
         s1.clip(c0, row1);
         if constexpr (CAUSAL) s2.clip(c0, row1);
@@ -957,21 +1006,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
         } else {
             s1.store_rows(Vs);
             if constexpr (CAUSAL) {
-                f4v r4;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const bool ok = c0 + 4 * rq + i < row1;
-                    r4[i] = ok ? __builtin_amdgcn_rcpf(g4[i]) : 0.f;
-                    if (dg == 0) {
-                        const int r = 4 * rq + i;
-                        const float d = ok ? d4[i] : 0.f;
-                        rs[r] = r4[i];
-                        dl[r] = d;
-                        dls[r] = d * r4[i];
-                    }
-                }
                 s2.store_rows(dOs);
-                s2.store_cols_scaled(OHt, TSZ, r4);
+                s2.store_cols_scaled(OHt, TSZ, *reinterpret_cast<const f4v *>(rs + 4 * rq));
             }
         }
         __syncthreads();
@@ -1011,12 +1047,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
                     }
                 }
             }
-            if (t < D) {
-                float s = tile_row_sum<T, D>(OHt, t);
-                if constexpr (PP == 2) s += tile_row_sum<T, D>(OHt + TSZ, t);
-                csw[t] = s;
-            } else if (t < 2 * D) {
-                csu[t - D] = tile_row_dot<T, D>(QTt, t - D, dls);
+#pragma unroll
+            for (int part = 0; part < VJ::PER; ++part) {
+                const int r = 64 * part + l;
+                if (VJ::mine(0, part, w)) {
+                    float s = tile_row_sum<T, D>(OHt, r);
+                    if constexpr (PP == 2) s += tile_row_sum<T, D>(OHt + TSZ, r);
+                    csw[r] = s;
+                }
+                if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
             }
             __syncthreads();
         }
@@ -1025,28 +1064,34 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
         //      OmegaHat^T W; store ----
 #pragma unroll 1
         for (int nb = 0; nb < NB; ++nb) {
-            Blk ak[1], av[1];
-            ak[0].zero();
-            av[0].zero();
-            state_product<T, D, 1>(ak, Rb, 1.f, Vs + nb * 16 * LDR, c, g);
-            state_product<T, D, 1>(av, Ra, b, Ks + nb * 16 * LDR, c, g);
-            if constexpr (CAUSAL) {
-                chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
-                                           (nb * 16) / KT, C / KT, c, g, wo);
-                // both operands are intermediates: hi (hi + lo), then lo hi
-                chunk_product<T, D, 1, PP>(av[0], OHt, 0, w * 16, WT, PSZ, nb * 16,
-                                           (nb * 16) / KT, C / KT, c, g, wo);
-                if constexpr (PP == 2)
-                    chunk_product<T, D, 1, 1>(av[0], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
-                                              (nb * 16) / KT, C / KT, c, g, wo);
-            }
             const size_t o = (size_t)(c0 + nb * 16) * D;
             const int valid = (int)(row1 - c0) - nb * 16;
-            store_block<T>(dKp + o, D, w * 16, valid, l, b * (ak[0].get(0) - u4[0]),
-                           b * (ak[0].get(1) - u4[1]), b * (ak[0].get(2) - u4[2]),
-                           b * (ak[0].get(3) - u4[3]));
-            store_block<T>(dVp + o, D, w * 16, valid, l, av[0].get(0) + w4[0],
-                           av[0].get(1) + w4[1], av[0].get(2) + w4[2], av[0].get(3) + w4[3]);
+            {
+                Blk ak[1];
+                ak[0].zero();
+                state_product<T, D, 1>(ak, Rb, 1.f, Vs + nb * 16 * LDR, c, g);
+                if constexpr (CAUSAL)
+                    chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
+                                               (nb * 16) / KT, C / KT, c, g, wo);
+                store_block<T>(dKp + o, D, w * 16, valid, l, b * (ak[0].get(0) - u4[0]),
+                               b * (ak[0].get(1) - u4[1]), b * (ak[0].get(2) - u4[2]),
+                               b * (ak[0].get(3) - u4[3]));
+            }
+            {
+                Blk av[1];
+                av[0].zero();
+                state_product<T, D, 1>(av, Ra, b, Ks + nb * 16 * LDR, c, g);
+                if constexpr (CAUSAL) {
+                    // both operands are intermediates: hi (hi + lo), then lo hi
+                    chunk_product<T, D, 1, PP>(av[0], OHt, 0, w * 16, WT, PSZ, nb * 16,
+                                               (nb * 16) / KT, C / KT, c, g, wo);
+                    if constexpr (PP == 2)
+                        chunk_product<T, D, 1, 1>(av[0], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
+                                                  (nb * 16) / KT, C / KT, c, g, wo);
+                }
+                store_block<T>(dVp + o, D, w * 16, valid, l, av[0].get(0) + w4[0],
+                               av[0].get(1) + w4[1], av[0].get(2) + w4[2], av[0].get(3) + w4[3]);
+            }
         }
         if constexpr (CAUSAL) {
             outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
@@ -1054,6 +1099,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
             u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
             w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
         }
+        par ^= 1;
+        post_factors(ci > 0 ? c0 - C : c0, par);
     }
 }
 
