@@ -108,6 +108,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into la_workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--independent", action="store_true",
+                    help="time la_forward + la_backward (no hand-over of running sums)")
     ap.add_argument("--cpu-slices", type=int, default=64)
     ap.add_argument("--buffer-sets", type=int, default=0,
                     help="independent input/output sets rotated through (0: enough to exceed "
@@ -159,11 +161,25 @@ def main():
                       dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
 
+    # A step is the pair a training step runs: the forward pass, which also hands its
+    # running sums at the segment boundaries to the backward pass (la_forward_save), and
+    # the backward pass that starts from them (la_backward_saved).  --independent times
+    # la_forward + la_backward instead, where the backward pass recomputes those sums.
+    nsv = la.la_saved_state_bytes(B, H, N, D, dt, cfg.causal)
+    saved = torch.empty(nsv, dtype=torch.uint8, device="cuda") if nsv else None
+
     def step(t, trf=None, trb=None):
-        la.la_forward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b, cfg.causal,
-                             wsf, None, trf)
-        la.la_backward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
-                              t["dV"], cfg.a, cfg.b, cfg.causal, wsb, None, trb)
+        if args.independent:
+            la.la_forward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b,
+                                 cfg.causal, wsf, None, trf)
+            la.la_backward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
+                                  t["dK"], t["dV"], cfg.a, cfg.b, cfg.causal, wsb, None, trb)
+        else:
+            la.la_forward_save(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b, cfg.causal,
+                               wsf, saved, None, trf)
+            la.la_backward_saved(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
+                                 t["dK"], t["dV"], cfg.a, cfg.b, cfg.causal, wsb, saved, None,
+                                 trb)
 
     for i in range(args.warmup):
         step(sets[i % n_sets])
@@ -247,13 +263,15 @@ def main():
         "dtype": "f32" if cfg.dtype == "f32" else "bf16 I/O, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "H": H, "N": N, "D": D, "causal": cfg.causal,
-                   "a": cfg.a, "b": cfg.b, "buffer_sets": n_sets},
+                   "a": cfg.a, "b": cfg.b, "buffer_sets": n_sets,
+                   "entry_points": "la_forward + la_backward" if args.independent
+                   else "la_forward_save + la_backward_saved"},
         "token_heads_per_s": T / (ms_per_step * 1e-3),
         "whole_pass": {"compulsory_bytes": pass_bytes, "achieved_GBs": pass_gbs,
                        "frac_of_hbm_peak": pass_gbs / HBM_PEAK_GBS},
         "kernels_ms": kernels_ms,
         "peak_device_bytes": int(peak_bytes),
-        "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel()},
+        "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel(), "saved": nsv},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -111,6 +111,51 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Optional hand-over of the forward pass's running sums to the backward pass.
+ *
+ * The ascending sweep of the backward pass (dQ, Eq. back1) starts every segment
+ * from the same sums S = sum k v^T, z = sum k (Eq. xy) that the forward pass
+ * carries through the sequence.  la_backward recomputes them from K and V;
+ * a caller that runs the two passes as a pair (a training step) can let
+ * la_forward_save write them out at the segment boundaries and hand them to
+ * la_backward_saved, which then skips that recomputation.  This is an
+ * addition to the set {Q,K,V,O,g} that Sec. 3.2 keeps: O(B*H*(N/segment)*D^2)
+ * floats, small next to the tensors.
+ *
+ *   la_saved_state_bytes: size of the `saved` buffer for this problem (0 for
+ *       invalid arguments, and 0 when the library would not use one -- head
+ *       sizes handled by the plain-ALU kernels; a zero-size buffer may be NULL).
+ *   la_forward_save:   la_forward, and additionally fills `saved` (device
+ *       memory, 256-byte aligned, at least la_saved_state_bytes bytes).
+ *   la_backward_saved: la_backward, reading `saved` as written by
+ *       la_forward_save for the same Q, K, V, B, H, N, D, dt, a, b, causal.
+ *       Results agree with la_backward up to fp32 rounding order.
+ * `saved` is caller-owned like every other buffer; its layout is private to
+ * the library and to this library version.  `trace` is the timing hook
+ * described below and may be NULL.  Error behaviour as for la_forward /
+ * la_backward; a missing, misaligned or short `saved` is LA_ERR_WORKSPACE.
+ */
+struct la_trace;
+LA_API size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal);
+
+LA_API la_status la_forward_save(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt,
+                     void *workspace, size_t workspace_bytes,
+                     void *saved, size_t saved_bytes,
+                     void *hip_stream, struct la_trace *trace);
+
+LA_API la_status la_backward_saved(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes,
+                      const void *saved, size_t saved_bytes,
+                      void *hip_stream, struct la_trace *trace);
+
+/*
  * Per-kernel timing hook for benchmarks and profiles.  The caller creates
  * `capacity` hipEvent_t handles (timing enabled) and passes them in `events`;
  * the traced entry points record events[0] on the stream before their first

@@ -18,7 +18,8 @@ LA_BF16 = 1
 LA_MAX_TRACE = 8
 
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
-           "la_forward_traced", "la_backward_traced")
+           "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
+           "la_backward_saved")
 
 
 class la_trace(ctypes.Structure):
@@ -66,6 +67,12 @@ def load_library():
     lib.la_forward_traced.argtypes = lib.la_forward.argtypes + [tp]
     lib.la_backward_traced.restype = i
     lib.la_backward_traced.argtypes = lib.la_backward.argtypes + [tp]
+    lib.la_saved_state_bytes.restype = sz
+    lib.la_saved_state_bytes.argtypes = [i, i, i, i, i, i]
+    lib.la_forward_save.restype = i
+    lib.la_forward_save.argtypes = lib.la_forward.argtypes[:-1] + [vp, sz, vp, tp]
+    lib.la_backward_saved.restype = i
+    lib.la_backward_saved.argtypes = lib.la_backward.argtypes[:-1] + [vp, sz, vp, tp]
     _lib = lib
     return lib
 
@@ -89,6 +96,10 @@ def _dtype_code(t):
 def la_workspace_bytes(B, H, N, D, dt, causal, is_backward):
     return int(load_library().la_workspace_bytes(B, H, N, D, dt, int(bool(causal)),
                                                  int(bool(is_backward))))
+
+
+def la_saved_state_bytes(B, H, N, D, dt, causal):
+    return int(load_library().la_saved_state_bytes(B, H, N, D, dt, int(bool(causal))))
 
 
 def _check_tensors(ref, *ts):
@@ -118,6 +129,23 @@ def la_forward(Q, K, V, O, G, a, b, causal, workspace, stream=None):
 
 def la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream=None, trace=None):
     """la_forward_traced of include/la.h; ``trace`` is a la_trace structure or None."""
+    _forward(Q, K, V, O, G, a, b, causal, workspace, None, stream, trace, False)
+
+
+def la_forward_save(Q, K, V, O, G, a, b, causal, workspace, saved, stream=None, trace=None):
+    """la_forward_save of include/la.h; ``saved`` is a uint8 device tensor of at least
+    la_saved_state_bytes(...) bytes (None when that is 0)."""
+    _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, True)
+
+
+def _saved_args(saved, ref):
+    if saved is None:
+        return ctypes.c_void_p(None), 0
+    _check_tensors(ref, saved)
+    return _ptr(saved), saved.numel() * saved.element_size()
+
+
+def _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, save):
     if Q.dim() != 4:
         raise ValueError("Q must be [B, H, N, D]")
     B, H, N, D = Q.shape
@@ -126,13 +154,18 @@ def la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream=None, trace
         raise ValueError("shape mismatch")
     if not (K.dtype == V.dtype == O.dtype == Q.dtype) or G.dtype != torch.float32:
         raise TypeError("dtype mismatch")
-    rc = load_library().la_forward_traced(
-        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), B, H, N, D, float(a), float(b),
-        int(bool(causal)), _dtype_code(Q), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream, Q.device),
-        ctypes.byref(trace) if trace is not None else None)
+    lib = load_library()
+    head = (_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), B, H, N, D, float(a), float(b),
+            int(bool(causal)), _dtype_code(Q), _ptr(workspace),
+            workspace.numel() * workspace.element_size())
+    tr = ctypes.byref(trace) if trace is not None else None
+    if save:
+        sp, sb = _saved_args(saved, Q)
+        rc = lib.la_forward_save(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
+    else:
+        rc = lib.la_forward_traced(*head, _stream_ptr(stream, Q.device), tr)
     if rc != 0:
-        raise LaError(rc, "la_forward")
+        raise LaError(rc, "la_forward_save" if save else "la_forward")
 
 
 def la_backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=None):
@@ -143,6 +176,17 @@ def la_backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=N
 def la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=None,
                        trace=None):
     """la_backward_traced of include/la.h; ``trace`` is a la_trace structure or None."""
+    _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, None, stream, trace, False)
+
+
+def la_backward_saved(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, stream=None,
+                      trace=None):
+    """la_backward_saved of include/la.h; ``saved`` as filled by la_forward_save."""
+    _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, stream, trace, True)
+
+
+def _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, stream, trace,
+              use_saved):
     if Q.dim() != 4:
         raise ValueError("Q must be [B, H, N, D]")
     B, H, N, D = Q.shape
@@ -154,10 +198,15 @@ def la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, s
             raise TypeError("dtype mismatch")
     if G.shape != Q.shape[:3] or G.dtype != torch.float32:
         raise ValueError("G must be [B, H, N] float32")
-    rc = load_library().la_backward_traced(
-        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
-        B, H, N, D, float(a), float(b), int(bool(causal)), _dtype_code(Q), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream, Q.device),
-        ctypes.byref(trace) if trace is not None else None)
+    lib = load_library()
+    head = (_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
+            B, H, N, D, float(a), float(b), int(bool(causal)), _dtype_code(Q), _ptr(workspace),
+            workspace.numel() * workspace.element_size())
+    tr = ctypes.byref(trace) if trace is not None else None
+    if use_saved:
+        sp, sb = _saved_args(saved, Q)
+        rc = lib.la_backward_saved(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
+    else:
+        rc = lib.la_backward_traced(*head, _stream_ptr(stream, Q.device), tr)
     if rc != 0:
-        raise LaError(rc, "la_backward")
+        raise LaError(rc, "la_backward_saved" if use_saved else "la_backward")

@@ -43,6 +43,8 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     p.delta_offset_floats = round_up(slots, 64);
     p.total_bytes = is_backward ? (p.delta_offset_floats + round_up((size_t)BH * N, 64)) * 4
                                 : round_up(slots, 64) * 4;
+    p.saved_floats = round_up(DD + D, 64);
+    p.saved_bytes = (size_t)BH * p.nseg * p.saved_floats * 4;
     return p;
 }
 
@@ -93,10 +95,20 @@ size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal, i
     return la::make_plan(B, H, N, D, dt, causal, is_backward).total_bytes;
 }
 
-la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,
-                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
-                            void *workspace, size_t workspace_bytes, void *hip_stream,
-                            la_trace *trace)
+size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal)
+{
+    if (la::check_shape(B, H, N, D, dt) != LA_OK) return 0;
+    la::Problem pr{B * H, N, D, 1.f, 0.f, causal ? 1 : 0, dt};
+    if (!la::use_fast(pr, 0) || !la::use_fast(pr, 1)) return 0;
+    return la::make_plan(B, H, N, D, dt, causal, 0).saved_bytes;
+}
+
+// `saved` == nullptr: the plain entry points.  Otherwise the buffer must be present and
+// large enough whenever the library would use it.
+static la_status forward_impl(const void *Q, const void *K, const void *V, void *O, float *G,
+                              int B, int H, int N, int D, float a, float b, int causal,
+                              la_dtype dt, void *workspace, size_t workspace_bytes, bool save,
+                              void *saved, size_t saved_bytes, void *hip_stream, la_trace *trace)
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
@@ -108,28 +120,28 @@ la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O
     if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
+    const bool fast = la::use_fast(pr, 0);
+    float *sv = nullptr;
+    if (save && fast && la::use_fast(pr, 1)) {
+        if (!saved || saved_bytes < pl.saved_bytes || (((uintptr_t)saved) & 255u))
+            return LA_ERR_WORKSPACE;
+        sv = (float *)saved;
+    }
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
     la::Tracer tc(trace, (hipStream_t)hip_stream);
-    if (la::use_fast(pr, 0))
-        return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
+    if (fast)
+        return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace, sv,
                                 (hipStream_t)hip_stream, tc);
     return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
                                (hipStream_t)hip_stream, tc);
 }
 
-la_status la_forward(const void *Q, const void *K, const void *V, void *O, float *G, int B, int H,
-                     int N, int D, float a, float b, int causal, la_dtype dt, void *workspace,
-                     size_t workspace_bytes, void *hip_stream)
-{
-    return la_forward_traced(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace,
-                             workspace_bytes, hip_stream, nullptr);
-}
-
-la_status la_backward_traced(const void *Q, const void *K, const void *V, const void *O,
-                             const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
-                             int H, int N, int D, float a, float b, int causal, la_dtype dt,
-                             void *workspace, size_t workspace_bytes, void *hip_stream,
-                             la_trace *trace)
+static la_status backward_impl(const void *Q, const void *K, const void *V, const void *O,
+                               const float *G, const void *dO, void *dQ, void *dK, void *dV,
+                               int B, int H, int N, int D, float a, float b, int causal,
+                               la_dtype dt, void *workspace, size_t workspace_bytes, bool use_saved,
+                               const void *saved, size_t saved_bytes, void *hip_stream,
+                               la_trace *trace)
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
@@ -141,13 +153,56 @@ la_status la_backward_traced(const void *Q, const void *K, const void *V, const 
     if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
+    const bool fast = la::use_fast(pr, 1);
+    const float *sv = nullptr;
+    if (use_saved && fast && la::use_fast(pr, 0)) {
+        if (!saved || saved_bytes < pl.saved_bytes || (((uintptr_t)saved) & 255u))
+            return LA_ERR_WORKSPACE;
+        sv = (const float *)saved;
+    }
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
     la::Tracer tc(trace, (hipStream_t)hip_stream);
-    if (la::use_fast(pr, 1))
-        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
+    if (fast)
+        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv,
                                  (hipStream_t)hip_stream, tc);
     return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
                                 (hipStream_t)hip_stream, tc);
+}
+
+la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,
+                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                            void *workspace, size_t workspace_bytes, void *hip_stream,
+                            la_trace *trace)
+{
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace, workspace_bytes,
+                        false, nullptr, 0, hip_stream, trace);
+}
+
+la_status la_forward(const void *Q, const void *K, const void *V, void *O, float *G, int B, int H,
+                     int N, int D, float a, float b, int causal, la_dtype dt, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace, workspace_bytes,
+                        false, nullptr, 0, hip_stream, nullptr);
+}
+
+la_status la_forward_save(const void *Q, const void *K, const void *V, void *O, float *G, int B,
+                          int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                          void *workspace, size_t workspace_bytes, void *saved, size_t saved_bytes,
+                          void *hip_stream, la_trace *trace)
+{
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace, workspace_bytes,
+                        true, saved, saved_bytes, hip_stream, trace);
+}
+
+la_status la_backward_traced(const void *Q, const void *K, const void *V, const void *O,
+                             const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
+                             int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                             void *workspace, size_t workspace_bytes, void *hip_stream,
+                             la_trace *trace)
+{
+    return backward_impl(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt, workspace,
+                         workspace_bytes, false, nullptr, 0, hip_stream, trace);
 }
 
 la_status la_backward(const void *Q, const void *K, const void *V, const void *O, const float *G,
@@ -155,8 +210,18 @@ la_status la_backward(const void *Q, const void *K, const void *V, const void *O
                       float a, float b, int causal, la_dtype dt, void *workspace,
                       size_t workspace_bytes, void *hip_stream)
 {
-    return la_backward_traced(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt,
-                              workspace, workspace_bytes, hip_stream, nullptr);
+    return backward_impl(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt, workspace,
+                         workspace_bytes, false, nullptr, 0, hip_stream, nullptr);
+}
+
+la_status la_backward_saved(const void *Q, const void *K, const void *V, const void *O,
+                            const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
+                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                            void *workspace, size_t workspace_bytes, const void *saved,
+                            size_t saved_bytes, void *hip_stream, la_trace *trace)
+{
+    return backward_impl(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt, workspace,
+                         workspace_bytes, true, saved, saved_bytes, hip_stream, trace);
 }
 
 }  // extern "C"

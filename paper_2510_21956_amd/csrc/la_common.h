@@ -48,6 +48,12 @@ struct Plan {
     size_t slot_floats;
     size_t delta_offset_floats;  // backward only
     size_t total_bytes;
+    // Hand-over buffer from the forward to the backward pass (matrix-core path only):
+    // per (slice, segment) [S^T (D*D) | z (D)] padded to saved_floats; entry s holds the
+    // sums over all rows before segment s (with the mask) or entry 0 the sums over the
+    // whole sequence (without).
+    size_t saved_floats;
+    size_t saved_bytes;
 };
 
 Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward);
@@ -89,11 +95,14 @@ void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off,
 
 // Matrix-core path (la_fast.hip): fp32 D = 64 (and D = 128 forward only), bf16 D = 128.
 bool fast_supported(const Problem &pr, int is_backward);
+// `saved` (may be null) is the forward-to-backward hand-over buffer described in Plan.
 la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                         const void *V, const void *O, const float *G, const void *dO, void *dQ,
-                        void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
+                        void *dK, void *dV, float *ws, const float *saved, hipStream_t st,
+                        Tracer &tc);
 la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
-                       const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
+                       const void *V, void *O, float *G, float *ws, float *saved, hipStream_t st,
+                       Tracer &tc);
 
 // Generic (plain-ALU, any supported D) path.
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,

@@ -513,8 +513,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
-    float *__restrict__ G, const float *__restrict__ ws, int N, int nseg, int seg_len,
-    size_t slot_floats, float a, float b)
+    float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
+    int nseg, int seg_len, size_t slot_floats, size_t saved_floats, float a, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -555,6 +555,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     f4v p4 = {0.f, 0.f, 0.f, 0.f};  // a * p[16w + 4g + 0..3]
     if (!zero_init) p4 = a * *reinterpret_cast<const f4v *>(slot + D * D + D + w * 16 + 4 * g);
     if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
+    // Hand-over to the backward pass (if asked for): entry s = [S^T | z] summed over all
+    // rows before segment s.  Without the mask every segment starts from the sums over the
+    // whole sequence and segment 0 writes them to entry 0.
+    if (!CAUSAL && saved && seg == 0) {
+        float *dst = saved + (size_t)bh * nseg * saved_floats;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+            *reinterpret_cast<f4v *>(dst + (w * 16 + c) * D + rb * 16 + 4 * g) = st[rb].v;
+        if (t < D) dst[D * D + t] = slot[D * D + t];
+    }
 
     // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
     Stager<T, D> s1, s2;
@@ -664,6 +674,14 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             if (t >= D && t < 2 * D) zs[t - D] += csk[t - D];
         }
     }
+    // with the mask, the state this segment ends with is what the next one starts from
+    if (CAUSAL && saved && seg + 1 < nseg) {
+        float *dst = saved + ((size_t)bh * nseg + seg + 1) * saved_floats;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+            *reinterpret_cast<f4v *>(dst + (w * 16 + c) * D + rb * 16 + 4 * g) = st[rb].v;
+        if (t >= D && t < 2 * D) dst[D * D + t - D] = zs[t - D];  // written by this very thread
+    }
 }
 
 // Fast-path backward slot: [S^T (D*D) | z (D) | R (D*D) | u (D) | w (D) | R^T (D*D)], all
@@ -692,8 +710,8 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
-    T *__restrict__ dQ, float *ws, float *__restrict__ dprime, int N, int nseg, int seg_len,
-    size_t slot_floats, float b)
+    T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
+    float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -729,8 +747,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
     const bool need_R = CAUSAL ? (seg > 0) : true;  // segment 0's sums start no one
 
+    // start of the ascending sweep: [S^T | z] over all rows before this segment, from the
+    // scanned workspace slots or from what the forward pass handed over (same layout)
     const bool zero_init = CAUSAL && seg == 0;
-    const float *slot = ws + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * slot_floats;
+    const float *slot = sinit + ((size_t)bh * nseg + (CAUSAL ? seg : 0)) * sinit_floats;
     Blk st[NRB];  // S^T: rows j, columns r = 16w + c
 #pragma unroll
     for (int jb = 0; jb < NRB; ++jb)
@@ -1111,7 +1131,8 @@ inline la_status launch_status()
 
 template <typename T, int D>
 la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
-                   const void *Vv, void *Ov, float *G, float *ws, hipStream_t st, Tracer &tc)
+                   const void *Vv, void *Ov, float *G, float *ws, float *saved, hipStream_t st,
+                   Tracer &tc)
 {
     constexpr int NT = FC<T, D>::NT;
     const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv;
@@ -1128,10 +1149,12 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     }
     if (pr.causal)
         kf_fwd_apply<T, D, true><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-            Q, K, V, O, G, ws, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.a, pr.b);
+            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
+            pr.b);
     else
         kf_fwd_apply<T, D, false><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-            Q, K, V, O, G, ws, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.a, pr.b);
+            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
+            pr.b);
     tc.mark("fwd_apply");
     return launch_status();
 }
@@ -1139,7 +1162,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
 template <typename T, int D>
 la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
-                   void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
+                   void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc)
 {
     typedef BwdSlot<D> SL;
     constexpr int NT = FC<T, D>::NT;
@@ -1149,9 +1172,10 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nseg = pl.nseg;
     float *dprime = ws + pl.delta_offset_floats;
     const dim3 grid(pr.BH * nseg), block(NT);
-    // forward-running sums per segment (none needed from a masked pass's last segment)
+    // forward-running sums before every segment: handed over by the forward pass, or
+    // per-segment sums (none needed from a masked pass's last segment) and a scan here
     const int nrun = pr.causal ? nseg - 1 : nseg;
-    if (nrun > 0) {
+    if (!saved && nrun > 0) {
         kf_kv_state<T, D, true><<<dim3(pr.BH * nrun), block, 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
         tc.mark("bwd_state");
@@ -1159,12 +1183,16 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
                           pr.causal ? 0 : 2, pr.causal ? 1 : 0, nseg - 1, st);
         tc.mark("scan_slots");
     }
+    const float *sinit = saved ? saved : ws;
+    const size_t sinit_floats = saved ? pl.saved_floats : pl.slot_floats;
     if (pr.causal)
-        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, dprime, pr.N,
-                                                      nseg, pl.seg_len, pl.slot_floats, pr.b);
+        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
+                                                      sinit_floats, dprime, pr.N, nseg,
+                                                      pl.seg_len, pl.slot_floats, pr.b);
     else
-        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, dprime, pr.N,
-                                                       nseg, pl.seg_len, pl.slot_floats, pr.b);
+        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
+                                                       sinit_floats, dprime, pr.N, nseg,
+                                                       pl.seg_len, pl.slot_floats, pr.b);
     tc.mark("bwd_dq");
     // reverse-running sums left by the ascending sweep
     if (pr.causal) {
@@ -1199,25 +1227,27 @@ bool fast_supported(const Problem &pr, int is_backward)
 
 la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                         const void *V, const void *O, const float *G, const void *dO, void *dQ,
-                        void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc)
+                        void *dK, void *dV, float *ws, const float *saved, hipStream_t st,
+                        Tracer &tc)
 {
     if (pr.dt == LA_F32 && pr.D == 64)
-        return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+        return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_F32 && pr.D == 128)
-        return fast_bwd<float, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+        return fast_bwd<float, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_BF16 && pr.D == 128)
-        return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+        return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     return LA_ERR_UNSUPPORTED;
 }
 
 la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
-                       const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc)
+                       const void *V, void *O, float *G, float *ws, float *saved, hipStream_t st,
+                       Tracer &tc)
 {
     if (pr.dt == LA_F32) {
-        if (pr.D == 64) return fast_fwd<float, 64>(pr, pl, Q, K, V, O, G, ws, st, tc);
-        if (pr.D == 128) return fast_fwd<float, 128>(pr, pl, Q, K, V, O, G, ws, st, tc);
+        if (pr.D == 64) return fast_fwd<float, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
+        if (pr.D == 128) return fast_fwd<float, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     } else if (pr.D == 128) {
-        return fast_fwd<__bf16, 128>(pr, pl, Q, K, V, O, G, ws, st, tc);
+        return fast_fwd<__bf16, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     }
     return LA_ERR_UNSUPPORTED;
 }

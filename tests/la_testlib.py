@@ -73,6 +73,34 @@ def gpu_backward(la, dev, O, G, a, b, causal):
     return dQ, dK, dV
 
 
+def gpu_forward_save(la, dev, a, b, causal):
+    """la_forward_save: O, G and the hand-over buffer for la_backward_saved (None when the
+    library uses none for this problem).  The buffer is poisoned first."""
+    Q, K, V = dev["Q"], dev["K"], dev["V"]
+    B, H, N, D = Q.shape
+    O = torch.full_like(Q, float("nan"))
+    G = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=Q.device)
+    wf = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 0), 256),
+                     dtype=torch.uint8, device=Q.device)
+    nb = la.la_saved_state_bytes(B, H, N, D, _dt(la, Q), causal)
+    saved = torch.full((nb,), 0xFF, dtype=torch.uint8, device=Q.device) if nb else None
+    la.la_forward_save(Q, K, V, O, G, a, b, causal, wf, saved)
+    torch.cuda.synchronize()
+    return O, G, saved
+
+
+def gpu_backward_saved(la, dev, O, G, saved, a, b, causal):
+    """la_backward_saved with the buffer of gpu_forward_save."""
+    Q, K, V, dO = dev["Q"], dev["K"], dev["V"], dev["dO"]
+    B, H, N, D = Q.shape
+    dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+    wb = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 1), 256),
+                     dtype=torch.uint8, device=Q.device)
+    la.la_backward_saved(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, wb, saved)
+    torch.cuda.synchronize()
+    return dQ, dK, dV
+
+
 def run_gpu(la, dev, a, b, causal):
     """Forward then backward on the forward's own outputs: O, G, dQ, dK, dV."""
     O, G = gpu_forward(la, dev, a, b, causal)

@@ -11,6 +11,7 @@ import pytest
 import torch
 
 import la_workloads as wl
+from la_testlib import gpu_backward_saved, gpu_forward_save
 from la_testlib import (TOL, excess, gpu_backward, gpu_forward, run_gpu, saved_set, to_device,
                         to_f64, upload_case)
 
@@ -41,7 +42,8 @@ def check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, a, b, causal, 
     to the I/O type, g in float32 -- and the oracle's backward consumes exactly the
     same stored values, so that the quantisation of the stored O is an input, not
     an error of the kernel.  The chained run (backward on the GPU forward's own
-    outputs) is compared with the same reference."""
+    outputs) is compared with the same reference, and so is the pair la_forward_save /
+    la_backward_saved, whose forward outputs must equal la_forward's bit for bit."""
     B, H, N, D = dev["Q"].shape
     tol = TOL[dtype]
     slices = list(slices)
@@ -56,11 +58,15 @@ def check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, a, b, causal, 
     O_in.view(B * H, N, D)[slices] = to_device(O_bits, dtype)
     G_in.view(B * H, N)[slices] = torch.from_numpy(G_32).cuda()
     dQ, dK, dV = gpu_backward(la, dev, O_in, G_in, a, b, causal)         # oracle's stored set
+    O2, G2, saved = gpu_forward_save(la, dev, a, b, causal)
+    assert torch.equal(O2, O) and torch.equal(G2, G), "%s la_forward_save outputs differ" % tag
+    dQs, dKs, dVs = gpu_backward_saved(la, dev, O_in, G_in, saved, a, b, causal)
 
     got = {"O": O, "G": G, "dQ": dQ, "dK": dK, "dV": dV, "dQ_chained": dQc, "dK_chained": dKc,
-           "dV_chained": dVc}
+           "dV_chained": dVc, "dQ_saved": dQs, "dK_saved": dKs, "dV_saved": dVs}
     want = {"O": O_ref, "G": G_ref, "dQ": grads_ref[0], "dK": grads_ref[1], "dV": grads_ref[2],
-            "dQ_chained": grads_ref[0], "dK_chained": grads_ref[1], "dV_chained": grads_ref[2]}
+            "dQ_chained": grads_ref[0], "dK_chained": grads_ref[1], "dV_chained": grads_ref[2],
+            "dQ_saved": grads_ref[0], "dK_saved": grads_ref[1], "dV_saved": grads_ref[2]}
     # every output element must have been written
     for name, t in got.items():
         assert bool(torch.isfinite(t.float()).all()), "%s %s has non-finite values" % (tag, name)
@@ -178,3 +184,20 @@ def test_argument_errors(la):
     with pytest.raises(la.LaError) as e:
         la.la_forward(mis, Q.clone(), Q.clone(), Q.clone(), G, 1.0, 0.5, True, ws)
     assert e.value.code == 4
+    # hand-over buffer: none is used for D = 16, one is required for D = 64
+    assert la.la_saved_state_bytes(1, 1, 64, 16, la.LA_F32, 1) == 0
+    la.la_forward_save(Q, Q.clone(), Q.clone(), Q.clone(), G, 1.0, 0.5, True, ws, None)
+    need = la.la_saved_state_bytes(1, 2, 300, 64, la.LA_F32, 1)
+    assert need > 0
+    Q64 = torch.zeros((1, 2, 300, 64), device="cuda")
+    G64 = torch.zeros((1, 2, 300), device="cuda")
+    big = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    for bad in (None, tiny):
+        with pytest.raises(la.LaError) as e:
+            la.la_forward_save(Q64, Q64.clone(), Q64.clone(), Q64.clone(), G64, 1.0, 0.5, True,
+                               big, bad)
+        assert e.value.code == 5
+        with pytest.raises(la.LaError) as e:
+            la.la_backward_saved(Q64, Q64.clone(), Q64.clone(), Q64.clone(), G64, Q64.clone(),
+                                 Q64.clone(), Q64.clone(), Q64.clone(), 1.0, 0.5, True, big, bad)
+        assert e.value.code == 5
