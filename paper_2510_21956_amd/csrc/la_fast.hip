@@ -24,6 +24,9 @@ namespace la {
 namespace {
 
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+// Fourth word of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no
+// swizzle, out-of-range reads return zero.
+constexpr int kBufferFlags = 0x00020000;
 typedef unsigned int u2v __attribute__((ext_vector_type(2)));
 
 template <typename T, int D>
@@ -70,32 +73,25 @@ struct Stager {
     u4v raw[4];
 
     // Request this thread's part of chunk rows [c0, c0 + C) of X, the base of a slice of N
-    // rows (c0 < N); rows beyond the slice read its last row instead.  Deliberately
-    // unconditional and blind to the loaded values: the registers are then written by
-    // nothing but these loads, which stay in flight until the tile is written.  (A load
-    // under a branch, or a value patched after loading, makes the compiler wait for the
-    // data right here.)  A half with no tensor of its own for a stager requests the other
-    // half's: the same lines at the same time, so no extra memory traffic.
+    // rows (c0 < N).  The chunk is addressed through a buffer descriptor that covers exactly
+    // its valid rows: the address is a uniform base, one per-thread offset and a constant
+    // per row, and rows beyond the slice come back as zeros without any code here.
+    // (Segments start at multiples of 64 rows, so a chunk is cut short only by the end of
+    // the slice.)  The loads are unconditional and nothing looks at the loaded values, so
+    // they stay in flight until the tile is written; a load under a branch, or a value
+    // patched after loading, makes the compiler wait for the data on the spot.  A half
+    // with no tensor of its own for a stager requests the other half's: the same lines at
+    // the same time, so no extra memory traffic.
     __device__ __forceinline__ void load(const T *X, long c0, int N)
     {
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
-        const T *base = X + (size_t)c0 * D;
-        const int last = N - 1 - (int)c0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int rl = min(4 * rq + i, last);
-            raw[i] = *reinterpret_cast<const u4v *>(base + (unsigned)(rl * D + dg * F::EPV));
-        }
-    }
-
-    // Zero the rows at or beyond row_end; only the last chunk of a segment has any.
-    __device__ __forceinline__ void clip(long c0, long row_end)
-    {
-        if (c0 + C <= row_end) return;
-        const int rq = (threadIdx.x % F::HT) / F::GPR;
+        const long rows = (N - c0 < C) ? N - c0 : C;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T *>(X + (size_t)c0 * D), 0, (int)(rows * D * sizeof(T)), kBufferFlags);
+        const int off = (4 * rq * D + dg * F::EPV) * (int)sizeof(T);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (c0 + 4 * rq + i >= row_end) raw[i] = u4v{0u, 0u, 0u, 0u};
+            raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + i * D * (int)sizeof(T), 0, 0);
     }
 
     // Element e of unit u as a float.
@@ -170,6 +166,15 @@ struct Stager {
         }
     }
 };
+
+// x[c0 + r] of a per-row float array of N entries (c0 < N, r < 64); 0 beyond the end.
+__device__ __forceinline__ float load_row_float(const float *x, long c0, int N, int r)
+{
+    const long rows = (N - c0 < 64) ? N - c0 : 64;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(x + c0), 0, (int)(rows * sizeof(float)), kBufferFlags);
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, 4 * r, 0, 0));
+}
 
 // Sum of the C entries of row `r` of a transposed tile.
 template <typename T, int D>
@@ -480,7 +485,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     s1.load(h0 ? Kp : Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
-        s1.clip(c0, row1);
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
         // next chunk, in flight during the products (after the last one: that one again)
@@ -574,8 +578,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     if constexpr (CAUSAL) s2.load(Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
-        s1.clip(c0, row1);
-        if constexpr (CAUSAL) s2.clip(c0, row1);
         if (h0) {
             s1.store_rows(Qs);
             if constexpr (CAUSAL) s2.store_cols(VTt);
@@ -707,7 +709,7 @@ struct BwdSlot {
 // that will start from them.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
+__global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64) ? 2 : 3)) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
@@ -774,7 +776,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
         s1.load(p1, c0, N);
         s2.load(p2, c0, N);
         if constexpr (CAUSAL) s3.load(Qp, c0, N);
-        g_next = (Gp + c0)[(unsigned)min(t % C, N - 1 - (int)c0)];
+        g_next = load_row_float(Gp, c0, N, t % C);
     };
     // 1/g of the chunk starting at c0 (whose g values have been fetched) into buffer `par`
     auto post_factors = [&](long c0, int par) {
@@ -785,9 +787,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dq(
     int par = 0;
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
-        s1.clip(c0, row1);
-        s2.clip(c0, row1);
-        if constexpr (CAUSAL) s3.clip(c0, row1);
         const float *rs = rsb[par];
         if (h0) {
             const f4v r4 = *reinterpret_cast<const f4v *>(rs + 4 * rq);
@@ -992,9 +991,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
         s1.load(p1, c0, N);
         if constexpr (CAUSAL) {
             s2.load(p2, c0, N);
-            const unsigned r = (unsigned)min(t % C, N - 1 - (int)c0);
-            g_next = (Gp + c0)[r];
-            d_next = (dp + c0)[r];
+            g_next = load_row_float(Gp, c0, N, t % C);
+            d_next = load_row_float(dp, c0, N, t % C);
         }
     };
     // row factors of the chunk starting at c0 (already fetched) into buffer `par`
@@ -1015,8 +1013,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
         const long c0 = row0 + ci * C;
         const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
         __syncthreads();
-        s1.clip(c0, row1);
-        if constexpr (CAUSAL) s2.clip(c0, row1);
         if (h0) {
             s1.store_rows(Ks);
             if constexpr (CAUSAL) {
