@@ -191,24 +191,29 @@ __device__ __forceinline__ float tile_row_sum(const T *tr, int r)
     return s;
 }
 
-// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.  The loop is
-// kept rolled: unrolled, each step's un-swizzled weight address would sit in a register
-// of its own for the whole kernel.
+// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.  The row's
+// swizzle is made opaque to the compiler first: otherwise each step's un-swizzled weight
+// address sits in a register of its own for the whole kernel.
 template <typename T, int D>
 __device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *wgt)
 {
     typedef FC<T, D> F;
     typedef typename Vec4<T>::type V4;
-    float s = 0.f;
-    const int sw = F::swz(r);
-#pragma unroll 1
-    for (int m = 0; m < F::C / 4; ++m) {
-        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m);
-        f4v x = *reinterpret_cast<const f4v *>(wgt + 4 * (m ^ sw));
-        s += (to_float(v[0]) * x[0] + to_float(v[1]) * x[1]) +
-             (to_float(v[2]) * x[2] + to_float(v[3]) * x[3]);
+    float s0 = 0.f, s1 = 0.f;
+    int sw = F::swz(r);
+    asm volatile("" : "+v"(sw));
+#pragma unroll
+    for (int m = 0; m < F::C / 4; m += 2) {
+        V4 v0 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m);
+        V4 v1 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m + 4);
+        f4v x0 = *reinterpret_cast<const f4v *>(wgt + 4 * (m ^ sw));
+        f4v x1 = *reinterpret_cast<const f4v *>(wgt + 4 * ((m + 1) ^ sw));
+        s0 += (to_float(v0[0]) * x0[0] + to_float(v0[1]) * x0[1]) +
+              (to_float(v0[2]) * x0[2] + to_float(v0[3]) * x0[3]);
+        s1 += (to_float(v1[0]) * x1[0] + to_float(v1[1]) * x1[1]) +
+              (to_float(v1[2]) * x1[2] + to_float(v1[3]) * x1[3]);
     }
-    return s;
+    return s0 + s1;
 }
 
 // Sum over each aligned group of WIDTH consecutive lanes, result in every lane of the
@@ -241,15 +246,17 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
 }
 
 // The per-chunk vector sums (column sums of tiles and the like) are cut into jobs of 64
-// rows, one wave each, and dealt out from the last wave downwards: the weight blocks of
-// phase A go to the first waves, so these fill the waves that would otherwise idle there.
-// Job (kind, part) covers rows [64 part, 64 part + 64) of vector number `kind`.
-template <int NW, int D>
+// rows, one wave each.  The NPAIRS weight blocks of phase A are dealt round-robin from
+// wave 0, so the last waves carry one block less than the first; the jobs go to those,
+// from the last wave downwards.  Job (kind, part) covers rows [64 part, 64 part + 64) of
+// vector number `kind`.
+template <int NW, int D, int NPAIRS>
 struct VecJobs {
     static constexpr int PER = D / 64;
+    static constexpr int LIGHT = (NPAIRS % NW) ? NW - NPAIRS % NW : NW;  // waves with fewer blocks
     static __device__ __forceinline__ bool mine(int kind, int part, int w)
     {
-        return w == NW - 1 - (kind * PER + part) % NW;
+        return w == NW - 1 - (kind * PER + part) % LIGHT;
     }
 };
 
@@ -525,7 +532,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     constexpr int C = F::C, NW = F::NW, NT = F::NT, NB = F::NB, NRB = F::NRB, KT = F::KT;
     constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;  // tiles only the masked path needs shrink to nothing
-    typedef VecJobs<NW, D> VJ;
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
     __shared__ __align__(16) T Qs[C * LDR];
     __shared__ __align__(16) T Ks[TS * C * LDR + 4];
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
@@ -730,7 +737,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64) ? 2 : 3)) void 
     // 1/g of the chunk's rows (two buffers: the next chunk's are written while this one's
     // are still read), dprime, delta, sum k
     __shared__ __align__(16) float rsb[2][C], dl[C], dls[C], csk[D];
-    typedef VecJobs<NW, D> VJ;
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -943,7 +950,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
     // written while this one's are still read
     float *fac = reinterpret_cast<float *>(lds);
     float *csu = fac + 6 * C, *csw = csu + D;
-    typedef VecJobs<NW, D> VJ;
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
     T *CmT = reinterpret_cast<T *>(csw + D), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
