@@ -355,25 +355,29 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
 }
 
 // One 16 x 16 block  X_rows(xr) . Y_rows(yr)^T  of two row-major tiles, contraction over D.
+// A block is a short chain of MFMAs on one accumulator, too short to cover an LDS round
+// trip per k-tile, so the fragments of up to four k-tiles are requested together.
 template <typename T, int D>
 __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, const T *ys, int yr,
                                               int c, int g)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
-    constexpr int KT = F::KT, LDR = F::LDR;
-    typedef XsY<M, 1> B;
+    constexpr int KT = F::KT, LDR = F::LDR, STEPS = D / KT, BATCH = STEPS < 4 ? STEPS : 4;
     int lane0 = c * LDR;  // opaque to the compiler, see outer_update
     asm volatile("" : "+v"(lane0));
-    pipeline<D / KT>(
-        D / KT,
-        [&](int kt) {
-            B b;
-            b.x[0] = M::load(xs + xr * LDR + lane0 + kt * KT, g);
-            b.y = M::load(ys + yr * LDR + lane0 + kt * KT, g);
-            return b;
-        },
-        [&](int, const B &b) { M::mma(acc, b.x[0], b.y); });
+#pragma unroll
+    for (int k0 = 0; k0 < STEPS; k0 += BATCH) {
+        typename M::Frag x[BATCH], y[BATCH];
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            x[k] = M::load(xs + xr * LDR + lane0 + (k0 + k) * KT, g);
+            y[k] = M::load(ys + yr * LDR + lane0 + (k0 + k) * KT, g);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) M::mma(acc, x[k], y[k]);
+    }
 }
 
 // acc += X_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T over chunk rows, where X is a
@@ -409,6 +413,56 @@ __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, in
 #pragma unroll
                 for (int q = 0; q < NYP; ++q)
                     if (p + q < 2) M::mma(acc, b.x[p], b.y[q]);
+        });
+}
+
+// acc[m] += X_rows(xr) . Y_rows((ib0 + m) * 16)^T for m = 0..NBL-1 over the chunk rows up to
+// the diagonal block of row block ib0 + m (k-tiles 0 .. ceil(16 (ib0 + m + 1) / KT) - 1): the
+// weight-block products of the ascending kernels, all row blocks in one software
+// pipeline so that only the first fragment load is exposed.  X is a swizzled transposed
+// tile (one plane), Y a weight tile with NYP planes (plane stride yps).
+template <typename T, int D, int NBL, int NYP>
+__device__ __forceinline__ void chunk_products_lower(Blk (&acc)[NBL], int ib0, const T *xt, int xr,
+                                                     const T *yt, int yps, int c, int g, SwzOff xo)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, 16> M;
+    constexpr int KT = F::KT, LDT = F::LDT;
+    typedef XsYs<M, 1, NYP> B;
+    int lane0 = c * LDT;  // opaque to the compiler, see outer_update
+    asm volatile("" : "+v"(lane0));
+    auto kts = [&](int m) { return ((ib0 + m + 1) * 16 + KT - 1) / KT; };
+    int steps = 0;
+#pragma unroll
+    for (int m = 0; m < NBL; ++m) steps += kts(m);
+    // step s -> (m, kt); s is a constant after unrolling, so this folds away
+    auto where = [&](int s, int &m, int &kt) {
+        m = 0;
+        while (m + 1 < NBL && s >= kts(m)) s -= kts(m++);
+        kt = s;
+    };
+    constexpr int MAXSTEPS = NBL * ((F::C + KT - 1) / KT);
+    pipeline<MAXSTEPS>(
+        steps,
+        [&](int s) {
+            int m, kt;
+            where(s, m, kt);
+            B b;
+            b.x[0] = M::load_off(xt + xr * LDT + lane0 + kt * KT, xo);
+#pragma unroll
+            for (int p = 0; p < NYP; ++p)
+                b.y[p] = M::load(yt + p * yps + (ib0 + m) * 16 * LDT + lane0 + kt * KT, g);
+            return b;
+        },
+        [&](int s, const B &b) {
+            int m, kt;
+            where(s, m, kt);
+#pragma unroll
+            for (int mm = 0; mm < NBL; ++mm)  // constant index into the accumulator array
+                if (mm == m) {
+#pragma unroll
+                    for (int q = 0; q < NYP; ++q) M::mma(acc[mm], b.x[0], b.y[q]);
+                }
         });
 }
 
@@ -651,31 +705,41 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
         __syncthreads();
 
         // ---- phase B: denominators; per row block b S^T Q^T + V^T P^T, normalise, store ----
-        if (l < C) {
-            float gv = b * qzs[l] + a * (CAUSAL ? (float)c0 : (float)N);
-            if constexpr (CAUSAL) {
-                for (int nb = 0; nb <= l / 16; ++nb) gv += psum[nb][l];
-            }
-            ginv[w][l] = 1.f / gv;
-            if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
-        }
-        __builtin_amdgcn_wave_barrier();
         {
+            // the row's q.z and block row sums: requested now, used after the state product
+            float qz = 0.f, ps = 0.f;
+            if (l < C) {
+                qz = qzs[l];
+                if constexpr (CAUSAL) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const float x = psum[nb][l];
+                        ps += (nb <= l / 16) ? x : 0.f;
+                    }
+                }
+            }
             Blk facc[NB];  // rows j = 16w + 4g + e, columns i
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
             state_product<T, D, NB>(facc, st, b, Qs, c, g);
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) {
-                if constexpr (CAUSAL)
-                    chunk_product<T, D, 1, PP>(facc[ib], VTt, 0, w * 16, Ps, PSZ, ib * 16, 0,
-                                               ((ib + 1) * 16 + KT - 1) / KT, c, g, wo);
-                const float gi = ginv[w][ib * 16 + c];
-                store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
-                               (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi,
-                               (facc[ib].get(1) + p4[1]) * gi, (facc[ib].get(2) + p4[2]) * gi,
-                               (facc[ib].get(3) + p4[3]) * gi);
+            if (l < C) {
+                const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
+                ginv[w][l] = 1.f / gv;
+                if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
             }
+            __builtin_amdgcn_wave_barrier();
+            if constexpr (CAUSAL)
+                chunk_products_lower<T, D, NB, PP>(facc, 0, VTt, w * 16, Ps, PSZ, c, g, wo);
+            float gi[NB];
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) gi[ib] = ginv[w][ib * 16 + c];
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib)
+                store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
+                               (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi[ib],
+                               (facc[ib].get(1) + p4[1]) * gi[ib],
+                               (facc[ib].get(2) + p4[2]) * gi[ib],
+                               (facc[ib].get(3) + p4[3]) * gi[ib]);
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, ql, wo);
@@ -874,22 +938,27 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64) ? 2 : 3)) void 
         // (two row blocks at a time: bounds the accumulators and fragments alive at once)
 #pragma unroll
         for (int i0 = 0; i0 < NB; i0 += 2) {
+            float sc[2], di[2];  // requested now, used in the epilogue
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                sc[ii] = rs[(i0 + ii) * 16 + c];
+                di[ii] = dl[(i0 + ii) * 16 + c];
+            }
             Blk acc[2];
             acc[0].zero();
             acc[1].zero();
             state_product<T, D, 2>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
+            if constexpr (CAUSAL)
+                chunk_products_lower<T, D, 2, PP>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
-                if constexpr (CAUSAL)
-                    chunk_product<T, D, 1, PP>(acc[ii], KTt, 0, w * 16, Cms, PSZ, ib * 16, 0,
-                                               ((ib + 1) * 16 + KT - 1) / KT, c, g, wo);
-                const int r_loc = ib * 16 + c;
-                const float sc = b * rs[r_loc], di = dl[r_loc];
+                const float f = b * sc[ii];
                 store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
-                               (int)(row1 - c0) - ib * 16, l, sc * (acc[ii].get(0) - di * z4[0]),
-                               sc * (acc[ii].get(1) - di * z4[1]), sc * (acc[ii].get(2) - di * z4[2]),
-                               sc * (acc[ii].get(3) - di * z4[3]));
+                               (int)(row1 - c0) - ib * 16, l, f * (acc[ii].get(0) - di[ii] * z4[0]),
+                               f * (acc[ii].get(1) - di[ii] * z4[1]),
+                               f * (acc[ii].get(2) - di[ii] * z4[2]),
+                               f * (acc[ii].get(3) - di[ii] * z4[3]));
             }
         }
         if constexpr (CAUSAL) {
