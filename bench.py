@@ -248,6 +248,13 @@ def main():
                     "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T}
     pass_bytes = (12 * D * e + 8) * T  # every input once, every output once, forward + backward
     pass_gbs = pass_bytes / (ms_per_step * 1e-3) / 1e9
+    # Algorithmic matrix flops of the recurrences per token-head (Sec. 3.1 / 3.2): forward
+    # 4 D^2 (update S, read it out), backward 10 D^2 (rebuild S, S OmegaHat, update R, R v,
+    # R^T k); without the mask the sums are formed once per slice and the rebuild is free.
+    # The chunked kernels execute more (the chunk's own C x C blocks, the per-segment sums).
+    pass_flops = (14 if cfg.causal else 12) * D * D * T
+    pass_tflops = pass_flops / (ms_per_step * 1e-3) / 1e12
+    mfma_peak = 157.3 if cfg.dtype == "f32" else 2516.0  # TFLOP/s, dense, datasheet
 
     out = {
         "metric": "fwd+bwd tokens/s",
@@ -268,7 +275,9 @@ def main():
                    else "la_forward_save + la_backward_saved"},
         "token_heads_per_s": T / (ms_per_step * 1e-3),
         "whole_pass": {"compulsory_bytes": pass_bytes, "achieved_GBs": pass_gbs,
-                       "frac_of_hbm_peak": pass_gbs / HBM_PEAK_GBS},
+                       "frac_of_hbm_peak": pass_gbs / HBM_PEAK_GBS,
+                       "algorithmic_flops": pass_flops, "achieved_TFLOPs": pass_tflops,
+                       "mfma_peak_TFLOPs": mfma_peak, "frac_of_mfma_peak": pass_tflops / mfma_peak},
         "kernels_ms": kernels_ms,
         "peak_device_bytes": int(peak_bytes),
         "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel(), "saved": nsv},
