@@ -86,18 +86,24 @@ def cpu_baseline(cfg, budget_slices):
     x = wl.config_inputs(idx, bh_subset=list(range(n)))
     Q, K, V, dO = (x[k][1] for k in ("Q", "K", "V", "dO"))
     oracle.forward_rec(Q[:1, :64], K[:1, :64], V[:1, :64], cfg.a, cfg.b, cfg.causal)  # load lib
+    # repeat the sample until about a second of wall time (10-20 s of CPU work) has passed
+    reps, dt = 0, 0.0
     t0 = time.perf_counter()
-    O, G = oracle.forward_rec(Q, K, V, cfg.a, cfg.b, cfg.causal)
-    oracle.backward_rec(Q, K, V, O, G, dO, cfg.a, cfg.b, cfg.causal)
-    dt = time.perf_counter() - t0
-    tokens = n * cfg.N / cfg.H  # a token is one (batch, position); it has H heads
+    while reps < 20 and dt < 1.0:
+        O, G = oracle.forward_rec(Q, K, V, cfg.a, cfg.b, cfg.causal)
+        oracle.backward_rec(Q, K, V, O, G, dO, cfg.a, cfg.b, cfg.causal)
+        reps += 1
+        dt = time.perf_counter() - t0
+    tokens = reps * n * cfg.N / cfg.H  # a token is one (batch, position); it has H heads
+    cores = min(oracle.num_threads(), n)
     return {
         "value": tokens / dt,
         "unit": "tokens/s",
-        "cores": min(oracle.num_threads(), n),
+        "cores": cores,
         "kind": "oracle",
         "sample": "%d of %d (batch,head) slices of %s, fp64 running-sum forward+backward, "
-                  "%.1f s wall" % (n, cfg.B * cfg.H, cfg.name, dt),
+                  "%d passes, %.1f s wall on %d threads" % (n, cfg.B * cfg.H, cfg.name, reps, dt,
+                                                            cores),
     }
 
 
