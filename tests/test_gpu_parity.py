@@ -87,6 +87,9 @@ SMALL = [
     # B, H, N, D
     (1, 1, 1, 16), (1, 2, 5, 16), (2, 1, 16, 16), (1, 1, 17, 32), (1, 3, 100, 32),
     (1, 1, 256, 16), (2, 2, 300, 64), (1, 2, 129, 128), (1, 1, 700, 64), (1, 1, 520, 128),
+    # matrix-core path at its edges: a single row, one short chunk, one row past a chunk,
+    # exactly one chunk, one row past a 64-row segment boundary
+    (1, 1, 1, 64), (1, 1, 31, 64), (1, 2, 33, 128), (1, 1, 64, 64), (3, 1, 65, 64), (1, 1, 1, 128),
 ]
 
 
