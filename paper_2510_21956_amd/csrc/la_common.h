@@ -93,7 +93,7 @@ struct Tracer {
 void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off, int len, int mode,
                        int lo, int hi, hipStream_t st);
 
-// Matrix-core path (la_fast.hip): fp32 D = 64 (and D = 128 forward only), bf16 D = 128.
+// Matrix-core path (la_fast.hip): D = 64 and D = 128, fp32 and bf16, both passes.
 bool fast_supported(const Problem &pr, int is_backward);
 // `saved` (may be null) is the forward-to-backward hand-over buffer described in Plan.
 la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,

@@ -780,7 +780,7 @@ struct BwdSlot {
 // that will start from them.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64) ? 2 : 3)) void kf_bwd_dq(
+__global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4) ? 2 : 3)) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
@@ -998,7 +998,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64) ? 2 : 3)) void 
 // columns r for dK (contraction over j).
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_bwd_dkv(
+__global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
@@ -1293,8 +1293,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
 bool fast_supported(const Problem &pr, int is_backward)
 {
     (void)is_backward;
-    if (pr.dt == LA_F32) return pr.D == 64 || pr.D == 128;
-    return pr.D == 128;
+    return pr.D == 64 || pr.D == 128;
 }
 
 la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
@@ -1306,6 +1305,8 @@ la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const 
         return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_F32 && pr.D == 128)
         return fast_bwd<float, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
+    if (pr.dt == LA_BF16 && pr.D == 64)
+        return fast_bwd<__bf16, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_BF16 && pr.D == 128)
         return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     return LA_ERR_UNSUPPORTED;
@@ -1318,8 +1319,9 @@ la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const v
     if (pr.dt == LA_F32) {
         if (pr.D == 64) return fast_fwd<float, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 128) return fast_fwd<float, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
-    } else if (pr.D == 128) {
-        return fast_fwd<__bf16, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
+    } else {
+        if (pr.D == 64) return fast_fwd<__bf16, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
+        if (pr.D == 128) return fast_fwd<__bf16, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     }
     return LA_ERR_UNSUPPORTED;
 }
