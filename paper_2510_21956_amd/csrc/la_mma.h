@@ -61,14 +61,6 @@ struct Acc<16> {
     __device__ __forceinline__ void set(int i, float x) { v[i] = x; }
 };
 
-// Row of the block that register i of lane-group g holds.
-template <int BS>
-__device__ __forceinline__ int acc_row(int i, int g)
-{
-    constexpr int NG = 64 / BS;
-    return (i % 4) + 4 * g + 4 * NG * (i / 4);
-}
-
 // ---- operand fragments and the MFMA itself ------------------------------------
 // Swizzled tiles: element offsets inside a k-tile.  SwzLane is the part of them that
 // depends on the lane, for the four possible low swizzle bits of a row block:
@@ -131,11 +123,6 @@ struct Mma<float, BS> {
             else
                 c.v = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], c.v, 0, 0, 0);
         }
-    }
-    // X operand exact, Y operand an intermediate (possibly split): c += a * b.
-    static __device__ __forceinline__ void mma2(Acc<BS> &c, Frag a, const Frag2 &b)
-    {
-        mma(c, a, b.hi);
     }
     // The intermediate (possibly split) is the X operand: c += a * b.
     static __device__ __forceinline__ void mma2x(Acc<BS> &c, const Frag2 &a, Frag b)
@@ -212,11 +199,6 @@ struct Mma<__bf16, BS> {
             c.v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c.v, 0, 0, 0);
         else
             c.v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c.v, 0, 0, 0);
-    }
-    static __device__ __forceinline__ void mma2(Acc<BS> &c, Frag a, const Frag2 &b)
-    {
-        mma(c, a, b.hi);
-        mma(c, a, b.lo);
     }
     static __device__ __forceinline__ void mma2x(Acc<BS> &c, const Frag2 &a, Frag b)
     {
