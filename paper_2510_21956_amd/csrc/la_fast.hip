@@ -1154,35 +1154,46 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
 
         // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
         //      OmegaHat^T W; store ----
+        // (two row blocks per pass: the state is turned into operand fragments once for both)
 #pragma unroll 1
-        for (int nb = 0; nb < NB; ++nb) {
-            const size_t o = (size_t)(c0 + nb * 16) * D;
-            const int valid = (int)(row1 - c0) - nb * 16;
+        for (int n0 = 0; n0 < NB; n0 += 2) {
             {
-                Blk ak[1];
+                Blk ak[2];
                 ak[0].zero();
-                state_product<T, D, 1>(ak, Rb, 1.f, Vs + nb * 16 * LDR, c, g);
-                if constexpr (CAUSAL)
-                    chunk_product<T, D, 1, PP>(ak[0], QTt, 0, w * 16, CmT, PSZ, nb * 16,
-                                               (nb * 16) / KT, C / KT, c, g, wo);
-                store_block<T>(dKp + o, D, w * 16, valid, l, b * (ak[0].get(0) - u4[0]),
-                               b * (ak[0].get(1) - u4[1]), b * (ak[0].get(2) - u4[2]),
-                               b * (ak[0].get(3) - u4[3]));
+                ak[1].zero();
+                state_product<T, D, 2>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const int nb = n0 + m;
+                    if constexpr (CAUSAL)
+                        chunk_product<T, D, 1, PP>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
+                                                   (nb * 16) / KT, C / KT, c, g, wo);
+                    store_block<T>(dKp + (size_t)(c0 + nb * 16) * D, D, w * 16,
+                                   (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
+                                   b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
+                                   b * (ak[m].get(3) - u4[3]));
+                }
             }
             {
-                Blk av[1];
+                Blk av[2];
                 av[0].zero();
-                state_product<T, D, 1>(av, Ra, b, Ks + nb * 16 * LDR, c, g);
-                if constexpr (CAUSAL) {
-                    // both operands are intermediates: hi (hi + lo), then lo hi
-                    chunk_product<T, D, 1, PP>(av[0], OHt, 0, w * 16, WT, PSZ, nb * 16,
-                                               (nb * 16) / KT, C / KT, c, g, wo);
-                    if constexpr (PP == 2)
-                        chunk_product<T, D, 1, 1>(av[0], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
-                                                  (nb * 16) / KT, C / KT, c, g, wo);
+                av[1].zero();
+                state_product<T, D, 2>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const int nb = n0 + m;
+                    if constexpr (CAUSAL) {
+                        // both operands are intermediates: hi (hi + lo), then lo hi
+                        chunk_product<T, D, 1, PP>(av[m], OHt, 0, w * 16, WT, PSZ, nb * 16,
+                                                   (nb * 16) / KT, C / KT, c, g, wo);
+                        if constexpr (PP == 2)
+                            chunk_product<T, D, 1, 1>(av[m], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
+                                                      (nb * 16) / KT, C / KT, c, g, wo);
+                    }
+                    store_block<T>(dVp + (size_t)(c0 + nb * 16) * D, D, w * 16,
+                                   (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
+                                   av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3]);
                 }
-                store_block<T>(dVp + o, D, w * 16, valid, l, av[0].get(0) + w4[0],
-                               av[0].get(1) + w4[1], av[0].get(2) + w4[2], av[0].get(3) + w4[3]);
             }
         }
         if constexpr (CAUSAL) {
