@@ -1154,16 +1154,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
 
         // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
         //      OmegaHat^T W; store ----
-        // (two row blocks per pass: the state is turned into operand fragments once for both)
+        constexpr int NPB = NB;
 #pragma unroll 1
-        for (int n0 = 0; n0 < NB; n0 += 2) {
+        for (int n0 = 0; n0 < NB; n0 += NPB) {
             {
-                Blk ak[2];
-                ak[0].zero();
-                ak[1].zero();
-                state_product<T, D, 2>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+                Blk ak[NPB];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) {
+                for (int m = 0; m < NPB; ++m) ak[m].zero();
+                state_product<T, D, NPB>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+#pragma unroll
+                for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
                     if constexpr (CAUSAL)
                         chunk_product<T, D, 1, PP>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
@@ -1175,12 +1175,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 }
             }
             {
-                Blk av[2];
-                av[0].zero();
-                av[1].zero();
-                state_product<T, D, 2>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+                Blk av[NPB];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) {
+                for (int m = 0; m < NPB; ++m) av[m].zero();
+                state_product<T, D, NPB>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+#pragma unroll
+                for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
                     if constexpr (CAUSAL) {
                         // both operands are intermediates: hi (hi + lo), then lo hi
