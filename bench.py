@@ -198,27 +198,34 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     peak_bytes = free0 - torch.cuda.mem_get_info()[0]
 
-    # Per-kernel durations: a second timed loop of the same steps with the library
-    # recording HIP events between its kernels on the stream it launches on.
-    evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
-    trf, trb = la.la_trace(), la.la_trace()
-    trf.events, trf.capacity = ctypes.cast(evf.handles, ctypes.POINTER(ctypes.c_void_p)), \
-        la.LA_MAX_TRACE + 1
-    trb.events, trb.capacity = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p)), \
-        la.LA_MAX_TRACE + 1
-    ksum, kcount = {}, {}
-    reps = max(5, min(args.steps, 30))
+    # Per-kernel durations: the same steps again, back to back and straight after the timed
+    # loop (so at the same clocks), with the library recording HIP events between its kernels
+    # on the stream it launches on.  Every repetition has event handles of its own; nothing
+    # waits until all of them are enqueued.
+    reps = max(5, min(args.steps, 50))
+    traces = []
     for i in range(reps):
+        evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
+        trf, trb = la.la_trace(), la.la_trace()
+        trf.events = ctypes.cast(evf.handles, ctypes.POINTER(ctypes.c_void_p))
+        trb.events = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p))
+        trf.capacity = trb.capacity = la.LA_MAX_TRACE + 1
+        traces.append((trf, evf, trb, evb))
+    for i in range(min(5, args.warmup)):  # handle creation took a while: back to speed first
+        step(sets[i % n_sets])
+    for i, (trf, evf, trb, evb) in enumerate(traces):
         step(sets[i % n_sets], trf, trb)
-        torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    ksum, kcount = {}, {}
+    for trf, evf, trb, evb in traces:
         for tr, ev, tag in ((trf, evf, "fwd"), (trb, evb, "bwd")):
             for k in range(tr.recorded - 1):
                 name = tag + ":" + tr.names[k].decode()
                 ksum[name] = ksum.get(name, 0.0) + ev.elapsed_ms(k, k + 1)
                 kcount[name] = kcount.get(name, 0) + 1
+        evf.destroy()
+        evb.destroy()
     kernels_ms = {k: ksum[k] / kcount[k] for k in ksum}
-    evf.destroy()
-    evb.destroy()
 
     # Roofline of the dominant kernel.  Algorithmic bytes per token-head of each step
     # of the path (every operand the step needs read once, every result written once;
