@@ -81,9 +81,8 @@ def cpu_baseline(cfg, budget_slices):
     import la_workloads as wl
     import oracle
 
-    idx = wl.CONFIGS.index(cfg)
     n = min(budget_slices, cfg.B * cfg.H)
-    x = wl.config_inputs(idx, bh_subset=list(range(n)))
+    x = wl.workload_inputs(cfg, bh_subset=list(range(n)))
     Q, K, V, dO = (x[k][1] for k in ("Q", "K", "V", "dO"))
     oracle.forward_rec(Q[:1, :64], K[:1, :64], V[:1, :64], cfg.a, cfg.b, cfg.causal)  # load lib
     # repeat the sample until about a second of wall time (10-20 s of CPU work) has passed
@@ -113,6 +112,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into la_workloads.CONFIGS")
+    ap.add_argument("--workload", default=None,
+                    help="a workload by name instead of --config: one of la_workloads.CONFIGS "
+                         "or la_workloads.PAPER_SHAPES (the paper's own benchmark shapes)")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="time la_forward alone (the quantity of the paper's Table 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--independent", action="store_true",
                     help="time la_forward + la_backward (no hand-over of running sums)")
@@ -149,7 +153,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.find_workload(args.workload) if args.workload else wl.CONFIGS[args.config]
     B, H, N, D = cfg.B, cfg.H, cfg.N, cfg.D
     e = 4 if cfg.dtype == "f32" else 2
     dt = la.LA_F32 if cfg.dtype == "f32" else la.LA_BF16
@@ -175,7 +179,10 @@ def main():
     saved = torch.empty(nsv, dtype=torch.uint8, device="cuda") if nsv else None
 
     def step(t, trf=None, trb=None):
-        if args.independent:
+        if args.forward_only:
+            la.la_forward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b,
+                                 cfg.causal, wsf, None, trf)
+        elif args.independent:
             la.la_forward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b,
                                  cfg.causal, wsf, None, trf)
             la.la_backward_traced(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
@@ -259,18 +266,19 @@ def main():
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T}
-    pass_bytes = (12 * D * e + 8) * T  # every input once, every output once, forward + backward
+    # every input once, every output once: forward + backward, or the forward pass alone
+    pass_bytes = ((4 * D * e + 4) if args.forward_only else (12 * D * e + 8)) * T
     pass_gbs = pass_bytes / (ms_per_step * 1e-3) / 1e9
     # Algorithmic matrix flops of the recurrences per token-head (Sec. 3.1 / 3.2): forward
     # 4 D^2 (update S, read it out), backward 10 D^2 (rebuild S, S OmegaHat, update R, R v,
     # R^T k); without the mask the sums are formed once per slice and the rebuild is free.
     # The chunked kernels execute more (the chunk's own C x C blocks, the per-segment sums).
-    pass_flops = (14 if cfg.causal else 12) * D * D * T
+    pass_flops = (4 if args.forward_only else (14 if cfg.causal else 12)) * D * D * T
     pass_tflops = pass_flops / (ms_per_step * 1e-3) / 1e12
     mfma_peak = 157.3 if cfg.dtype == "f32" else 2516.0  # TFLOP/s, dense, datasheet
 
     out = {
-        "metric": "fwd+bwd tokens/s",
+        "metric": "fwd tokens/s" if args.forward_only else "fwd+bwd tokens/s",
         "value": cfg.tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,

@@ -49,6 +49,25 @@ CONFIGS = [
 ]
 
 
+# The paper's own stand-alone layer benchmark (Sec. 5.1: B = 4, H = 16, fp32, causal; the
+# sequence-length sweep at D = 128 and the head-size sweep at N = 4096).  Same value recipe;
+# not part of the five benchmark configurations above.  D = 256 is not supported by the library.
+PAPER_SHAPES = (
+    [Config("paper_causal_f32_B4_H16_N%d_D128" % n, 4, 16, n, 128, True, "f32")
+     for n in (1000, 10000, 100000, 300000)]
+    + [Config("paper_causal_f32_B4_H16_N4096_D%d" % d, 4, 16, 4096, d, True, "f32")
+       for d in (32, 64, 128)]
+)
+
+
+def find_workload(name):
+    """A configuration of CONFIGS or PAPER_SHAPES by name."""
+    for c in list(CONFIGS) + list(PAPER_SHAPES):
+        if c.name == name:
+            return c
+    raise KeyError(name)
+
+
 def bf16_round_bits(x):
     """float array -> uint16 bfloat16 bit patterns, round-to-nearest-even."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
@@ -129,3 +148,16 @@ def config_inputs(index, bh_subset=None):
     """Inputs of benchmark configuration ``index`` (0-based into CONFIGS)."""
     c = CONFIGS[index]
     return make_inputs(c.B, c.H, c.N, c.D, c.dtype, SEED_BASE + index, True, bh_subset)
+
+
+def workload_seed(c):
+    """Seed of a named workload: the five configurations keep theirs, the paper's shapes
+    follow with 100 + their position."""
+    if c in CONFIGS:
+        return SEED_BASE + CONFIGS.index(c)
+    return SEED_BASE + 100 + list(PAPER_SHAPES).index(c)
+
+
+def workload_inputs(c, bh_subset=None):
+    """Inputs of a configuration of CONFIGS or PAPER_SHAPES."""
+    return make_inputs(c.B, c.H, c.N, c.D, c.dtype, workload_seed(c), True, bh_subset)

@@ -141,6 +141,25 @@ def test_full_configs(oracle_mod, la, seg_len_env, index, slices):
     check_against_oracle(oracle_mod, la, dev, ref, slices, c.dtype, c.a, c.b, c.causal, c.name)
 
 
+# The paper's own benchmark shapes (Sec. 5.1), the ones the oracle finishes in seconds on a
+# few sampled slices: the two shorter lengths of the D = 128 sweep (N = 10000 is not a
+# multiple of any tile size) and the three head sizes at N = 4096.
+PAPER = [("paper_causal_f32_B4_H16_N1000_D128", [0, 21, 63]),
+         ("paper_causal_f32_B4_H16_N10000_D128", [0, 40]),
+         ("paper_causal_f32_B4_H16_N4096_D32", [0, 50]),
+         ("paper_causal_f32_B4_H16_N4096_D64", [7]),
+         ("paper_causal_f32_B4_H16_N4096_D128", [63])]
+
+
+@pytest.mark.parametrize("name,slices", PAPER)
+def test_paper_shapes(oracle_mod, la, seg_len_env, name, slices):
+    os.environ.pop("LA_SEG_LEN", None)
+    c = wl.find_workload(name)
+    print("case", c.name, "slices", slices, flush=True)
+    dev, ref = upload_case(c.B, c.H, c.N, c.D, c.dtype, wl.workload_seed(c), slices)
+    check_against_oracle(oracle_mod, la, dev, ref, slices, c.dtype, c.a, c.b, c.causal, c.name)
+
+
 def test_definition_rows_on_long_config(oracle_mod, la, seg_len_env):
     """Long-sequence configuration: sampled rows recomputed one by one from the
     O(N^2 D) definition (not the running sums)."""
