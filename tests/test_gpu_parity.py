@@ -180,6 +180,32 @@ def test_definition_rows_on_long_config(oracle_mod, la, seg_len_env):
     assert excess(g_gpu, g_ref, TOL["f32"]) <= 1.0
 
 
+@pytest.mark.parametrize("dtype,causal", [("f32", True), ("bf16", True), ("f32", False)])
+def test_autograd_wrapper(oracle_mod, la, seg_len_env, dtype, causal):
+    """The torch.autograd wrapper: gradients of sum(O * dO) obtained through
+    torch's backward() against the oracle's (chained: the wrapper's backward consumes the
+    wrapper's own O and g)."""
+    os.environ.pop("LA_SEG_LEN", None)
+    B, H, N, D = 2, 3, 700, 64
+    a, b = 1.0, 0.5
+    slices = list(range(B * H))
+    dev, ref = upload_case(B, H, N, D, dtype, 4242, slices)
+    O_ref, G_ref = oracle_mod.forward_rec(ref["Q"], ref["K"], ref["V"], a, b, causal)
+    grads_ref = oracle_mod.backward_rec(ref["Q"], ref["K"], ref["V"], O_ref, G_ref, ref["dO"], a, b,
+                                        causal)
+    Q, K, V = (dev[n].clone().requires_grad_(True) for n in ("Q", "K", "V"))
+    O = la.linear_attention(Q, K, V, a, b, causal)
+    (O.float() * dev["dO"].float()).sum().backward()
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    got = {"O": O.detach(), "dQ": Q.grad, "dK": K.grad, "dV": V.grad}
+    want = {"O": O_ref, "dQ": grads_ref[0], "dK": grads_ref[1], "dV": grads_ref[2]}
+    for name in got:
+        e = excess(to_f64(got[name].reshape(B * H, N, D)), want[name], tol)
+        print("autograd", dtype, causal, name, round(e, 4), flush=True)
+        assert e <= 1.0, "%s exceeds tolerance by factor %.3g" % (name, e)
+
+
 def test_run_to_run_determinism(la, seg_len_env):
     os.environ.pop("LA_SEG_LEN", None)
     dev, _ = upload_case(2, 4, 1500, 64, "f32", 99, [])
