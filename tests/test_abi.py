@@ -80,3 +80,14 @@ def test_argument_checks_precede_any_launch(lib):
     rc = lib.la_backward(fake, fake, fake, fake, fake, fake, fake, fake, fake, 4, 16, 4096, 64,
                          1.0, 0.5, 1, 0, fake, 16, vp(0))
     assert rc == 5
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/la.h is a C header: it must compile as C and as C++ on its own."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "la.h")
+    for cc, lang in (("gcc", "c"), ("g++", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip("%s not available" % cc)
+        subprocess.run([cc, "-fsyntax-only", "-Wall", "-Werror", "-x", lang, hdr], check=True)
