@@ -47,6 +47,15 @@ def test_workspace_bytes(lib):
     assert la.la_workspace_bytes(4, 16, 4096, 48, la.LA_F32, 1, 0) == 0      # unsupported D
     assert la.la_workspace_bytes(0, 16, 4096, 64, la.LA_F32, 1, 0) == 0      # bad shape
     assert la.la_workspace_bytes(1, 1, 1, 64, 7, 1, 0) == 0                  # bad dtype
+    # size limits: B*H*N*D < 2^40 elements, B*H < 2^31 / 4096
+    assert la.la_workspace_bytes(1, 1, 2 ** 31 - 1, 128, la.LA_F32, 1, 0) > 0
+    assert la.la_workspace_bytes(64, 64, 2 ** 21, 128, la.LA_F32, 1, 0) == 0   # 2^40 elements
+    assert la.la_workspace_bytes(1024, 1024, 64, 64, la.LA_F32, 1, 0) == 0     # too many slices
+    # the hand-over buffer: present for the matrix-core head sizes, absent otherwise
+    assert la.la_saved_state_bytes(4, 16, 4096, 64, la.LA_F32, 1) > 0
+    assert la.la_saved_state_bytes(4, 16, 4096, 128, la.LA_BF16, 0) > 0
+    assert la.la_saved_state_bytes(4, 16, 4096, 16, la.LA_F32, 1) == 0
+    assert la.la_saved_state_bytes(4, 16, 4096, 48, la.LA_F32, 1) == 0
 
 
 def test_argument_checks_precede_any_launch(lib):
