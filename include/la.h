@@ -21,17 +21,23 @@
  *     LA_BF16 (bfloat16 bit patterns, round-to-nearest-even on store).  All
  *     accumulation is float32; G is always float32.
  *   - The caller owns every buffer, including the workspace.  The library
- *     allocates no memory, keeps no state between calls and is re-entrant.
- *     Calls that share a workspace must not overlap in time.
+ *     allocates no memory and keeps no state between calls (the one exception
+ *     is the test hook la_debug_override below); calls on different buffers
+ *     may run concurrently.  Calls that share a workspace must not overlap in
+ *     time.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  The call returns without synchronising.
- *   - Outputs are overwritten, never accumulated into.  No output may alias
- *     an input or another output.
+ *   - Outputs are overwritten, never accumulated into.  No written buffer
+ *     (outputs, workspace, hand-over buffer) may overlap any other buffer of
+ *     the call: this is checked and reported as LA_ERR_ALIAS.
  *   - Supported: D in {16, 32, 64, 128}; B, H, N >= 1 with B*H*N*D < 2^40;
  *     any N (a ragged last chunk is handled).
  *   - Errors are reported by return code only.  Every argument check happens
  *     before anything is enqueued, so a failed call has no side effect.
- *     LA_ERR_LAUNCH carries a failed kernel enqueue (hipGetLastError).
+ *     LA_ERR_LAUNCH carries a failed kernel enqueue (hipGetLastError).  A HIP
+ *     error already pending on the calling thread when the call is made is
+ *     also reported as LA_ERR_LAUNCH; it is left pending and nothing is
+ *     enqueued.
  *   - Numerical precondition (not checked): g_i != 0.  It holds when
  *     a > |b| * max|q.k|, e.g. unit-norm rows of Q and K (the normalisation of
  *     Sec. 3.3, which is the caller's job) with a = 1, b = 0.5.
@@ -54,7 +60,8 @@ typedef enum la_status {
     LA_ERR_UNSUPPORTED = 3, /* D or dtype not supported                        */
     LA_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                */
     LA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than required         */
-    LA_ERR_LAUNCH = 6       /* a kernel enqueue failed                         */
+    LA_ERR_LAUNCH = 6,      /* a kernel enqueue failed                         */
+    LA_ERR_ALIAS = 7        /* an output overlaps another buffer of the call   */
 } la_status;
 
 typedef enum la_dtype {
@@ -70,7 +77,8 @@ LA_API const char *la_status_string(la_status s);
 
 /*
  * Bytes of device workspace la_forward (is_backward = 0) or la_backward
- * (is_backward != 0) needs for this problem.  Returns 0 for invalid or
+ * (is_backward = 1; is_backward = 2: la_backward called with O or G NULL, which
+ * recomputes them) needs for this problem.  Returns 0 for invalid or
  * unsupported arguments.  The workspace holds the per-segment running-sum
  * states (S = sum k v^T, z = sum k, p = sum v of Eq. xy; and the reverse sums
  * of Eq. endd for the backward pass) that let segments of one sequence run in
@@ -85,7 +93,9 @@ LA_API size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int ca
  *   out: O         [B,H,N,D] of `dt`      o_i = f_i / g_i
  *        G         [B,H,N]   float32      g_i, the denominators; part of the
  *                                         set {Q,K,V,O,g} kept for the
- *                                         backward pass (Sec. 3.2)
+ *                                         backward pass (Sec. 3.2).  May be
+ *                                         NULL: g is then not stored, and
+ *                                         la_backward must recompute it.
  *   a, b   : kernel coefficients; causal != 0 applies the causal mask.
  *   workspace / workspace_bytes: device scratch of at least
  *            la_workspace_bytes(..., 0) bytes, 256-byte aligned.
@@ -100,8 +110,13 @@ LA_API la_status la_forward(const void *Q, const void *K, const void *V,
  * Backward pass (Sec. 3.2: Eq. bound, back1, back2, endd).
  *   in : Q, K, V, O, dO [B,H,N,D] of `dt`; G [B,H,N] float32 -- O and G exactly
  *        as written by la_forward for the same Q, K, V, a, b, causal.
+ *        O and/or G may be NULL (a caller that keeps only {Q,K,V} of the saved
+ *        set of Sec. 3.2): the forward pass is then run again inside the call,
+ *        into the workspace, and whichever of the two was NULL takes its
+ *        result.  That costs one forward pass and O(B*H*N*D) workspace.
  *   out: dQ, dK, dV     [B,H,N,D] of `dt`: gradients of sum(O * dO).
- *   workspace: at least la_workspace_bytes(..., 1) bytes, 256-byte aligned.
+ *   workspace: 256-byte aligned; at least la_workspace_bytes(..., 1) bytes, or
+ *        la_workspace_bytes(..., 2) bytes when O or G is NULL.
  */
 LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       const void *O, const float *G, const void *dO,
@@ -109,6 +124,19 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       int B, int H, int N, int D,
                       float a, float b, int causal, la_dtype dt,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Test and profiling hook -- the only process-wide state of the library.
+ * seg_len > 0 forces the number of rows per segment (rounded up to a multiple
+ * of 64; 0 restores the automatic choice); force_generic != 0 routes every
+ * head size to the plain-ALU kernels.  Both change la_workspace_bytes and
+ * la_saved_state_bytes and the private layout of those buffers, so a size
+ * query and the calls that use its result must see the same setting; a buffer
+ * filled by la_forward_save under one setting must not be given to
+ * la_backward_saved under another.  Not synchronised with calls in flight on
+ * other threads.  Production callers never call it.
+ */
+LA_API void la_debug_override(int seg_len, int force_generic);
 
 /*
  * Optional hand-over of the forward pass's running sums to the backward pass.

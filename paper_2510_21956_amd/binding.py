@@ -19,7 +19,7 @@ LA_MAX_TRACE = 8
 
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
-           "la_backward_saved")
+           "la_backward_saved", "la_debug_override")
 
 
 class la_trace(ctypes.Structure):
@@ -73,6 +73,8 @@ def load_library():
     lib.la_forward_save.argtypes = lib.la_forward.argtypes[:-1] + [vp, sz, vp, tp]
     lib.la_backward_saved.restype = i
     lib.la_backward_saved.argtypes = lib.la_backward.argtypes[:-1] + [vp, sz, vp, tp]
+    lib.la_debug_override.restype = None
+    lib.la_debug_override.argtypes = [i, i]
     _lib = lib
     return lib
 
@@ -85,6 +87,11 @@ def la_status_string(code):
     return load_library().la_status_string(int(code)).decode()
 
 
+def la_debug_override(seg_len=0, force_generic=0):
+    """la_debug_override of include/la.h (test / profiling hook; 0, 0 = automatic)."""
+    load_library().la_debug_override(int(seg_len), int(bool(force_generic)))
+
+
 def _dtype_code(t):
     if t.dtype == torch.float32:
         return LA_F32
@@ -94,8 +101,9 @@ def _dtype_code(t):
 
 
 def la_workspace_bytes(B, H, N, D, dt, causal, is_backward):
+    """is_backward: 0 forward, 1 backward, 2 backward that recomputes O / G (given as None)."""
     return int(load_library().la_workspace_bytes(B, H, N, D, dt, int(bool(causal)),
-                                                 int(bool(is_backward))))
+                                                 int(is_backward)))
 
 
 def la_saved_state_bytes(B, H, N, D, dt, causal):
@@ -104,6 +112,8 @@ def la_saved_state_bytes(B, H, N, D, dt, causal):
 
 def _check_tensors(ref, *ts):
     for t in ts:
+        if t is None:
+            continue
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError("tensors must be contiguous device tensors")
         if t.device != ref.device:
@@ -116,7 +126,7 @@ def _stream_ptr(stream, device):
 
 
 def _ptr(t):
-    return ctypes.c_void_p(t.data_ptr())
+    return ctypes.c_void_p(None if t is None else t.data_ptr())
 
 
 def la_forward(Q, K, V, O, G, a, b, causal, workspace, stream=None):
@@ -150,10 +160,12 @@ def _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, save)
         raise ValueError("Q must be [B, H, N, D]")
     B, H, N, D = Q.shape
     _check_tensors(Q, K, V, O, G, workspace)
-    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape or G.shape != Q.shape[:3]:
+    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape:
         raise ValueError("shape mismatch")
-    if not (K.dtype == V.dtype == O.dtype == Q.dtype) or G.dtype != torch.float32:
+    if not (K.dtype == V.dtype == O.dtype == Q.dtype):
         raise TypeError("dtype mismatch")
+    if G is not None and (G.shape != Q.shape[:3] or G.dtype != torch.float32):
+        raise ValueError("G must be [B, H, N] float32 (or None)")
     lib = load_library()
     head = (_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), B, H, N, D, float(a), float(b),
             int(bool(causal)), _dtype_code(Q), _ptr(workspace),
@@ -191,13 +203,17 @@ def _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, str
         raise ValueError("Q must be [B, H, N, D]")
     B, H, N, D = Q.shape
     _check_tensors(Q, K, V, O, G, dO, dQ, dK, dV, workspace)
-    for t in (K, V, O, dO, dQ, dK, dV):
+    for name, t in (("K", K), ("V", V), ("O", O), ("dO", dO), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        if t is None:
+            if name == "O":
+                continue  # recomputed inside the call
+            raise ValueError("%s is required" % name)
         if t.shape != Q.shape:
             raise ValueError("shape mismatch")
         if t.dtype != Q.dtype:
             raise TypeError("dtype mismatch")
-    if G.shape != Q.shape[:3] or G.dtype != torch.float32:
-        raise ValueError("G must be [B, H, N] float32")
+    if G is not None and (G.shape != Q.shape[:3] or G.dtype != torch.float32):
+        raise ValueError("G must be [B, H, N] float32 (or None)")
     lib = load_library()
     head = (_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
             B, H, N, D, float(a), float(b), int(bool(causal)), _dtype_code(Q), _ptr(workspace),

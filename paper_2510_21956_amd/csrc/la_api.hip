@@ -1,9 +1,13 @@
 // C ABI entry points: argument validation, segment plan, dispatch.
-#include <stdlib.h>
+#include <atomic>
 
 #include "la_common.h"
 
 namespace la {
+
+// Test / profiling override (la_debug_override): 0 = automatic.
+static std::atomic<int> g_seg_len_override{0};
+static std::atomic<int> g_force_generic{0};
 
 static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
@@ -15,7 +19,7 @@ static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 12
 // slices x segments is about 256 x that residency: every compute unit then gets the
 // same number of equally long segments in a single round.
 // Segments are also kept long enough that the D x D state a segment hands over stays
-// small next to the rows it covers.  LA_SEG_LEN (rows, rounded up to 64) overrides.
+// small next to the rows it covers.  la_debug_override can force a length (rounded up to 64).
 Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
 {
     Plan p;
@@ -29,11 +33,8 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
     long seg_len = (N + want - 1) / want;
-    const char *env = getenv("LA_SEG_LEN");
-    if (env) {
-        long v = atol(env);
-        if (v > 0) seg_len = v;
-    }
+    const int forced = g_seg_len_override.load(std::memory_order_relaxed);
+    if (forced > 0) seg_len = forced;
     seg_len = (long)round_up((size_t)seg_len, 64);
     p.seg_len = (int)seg_len;
     p.nseg = (int)((N + seg_len - 1) / seg_len);
@@ -59,21 +60,63 @@ static la_status check_shape(int B, int H, int N, int D, la_dtype dt)
     return LA_OK;
 }
 
+// The launch grid is slices x segments in one int.
+static bool grid_ok(int B, int H, const Plan &pl)
+{
+    return (double)B * H * pl.nseg <= 2147483647.0;
+}
+
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 
-// LA_PATH=generic forces the plain-ALU kernels (for A/B comparison and debugging).
+struct Range {
+    const void *p;
+    size_t bytes;
+};
+static bool overlap(const Range &x, const Range &y)
+{
+    if (!x.p || !y.p || !x.bytes || !y.bytes) return false;
+    const uintptr_t a0 = (uintptr_t)x.p, a1 = a0 + x.bytes, b0 = (uintptr_t)y.p, b1 = b0 + y.bytes;
+    return a0 < b1 && b0 < a1;
+}
+// No written buffer (outs) may overlap any other buffer of the call.
+static bool any_alias(const Range *ins, int nin, const Range *outs, int nout)
+{
+    for (int i = 0; i < nout; ++i) {
+        for (int j = 0; j < nin; ++j)
+            if (overlap(outs[i], ins[j])) return true;
+        for (int j = i + 1; j < nout; ++j)
+            if (overlap(outs[i], outs[j])) return true;
+    }
+    return false;
+}
+
+// la_debug_override can force the plain-ALU kernels (for A/B comparison and debugging).
 static bool use_fast(const Problem &pr, int is_backward)
 {
-    const char *env = getenv("LA_PATH");
-    if (env && env[0] == 'g') return false;
+    if (g_force_generic.load(std::memory_order_relaxed)) return false;
     return fast_supported(pr, is_backward);
+}
+
+// Extra workspace of a backward pass that recomputes O and g (either handed in as NULL):
+// the forward pass's own workspace, then O, then g, each rounded up to 256 bytes.
+struct Recompute {
+    size_t fwd_ws_off, o_off, g_off, total_bytes;
+};
+static Recompute recompute_layout(const Plan &bwd, const Plan &fwd, size_t T, int D, la_dtype dt)
+{
+    Recompute r;
+    r.fwd_ws_off = round_up(bwd.total_bytes, 256);
+    r.o_off = r.fwd_ws_off + round_up(fwd.total_bytes, 256);
+    r.g_off = r.o_off + round_up(T * D * (dt == LA_F32 ? 4 : 2), 256);
+    r.total_bytes = r.g_off + round_up(T * 4, 256);
+    return r;
 }
 
 }  // namespace la
 
 extern "C" {
 
-int la_version(void) { return 100; }
+int la_version(void) { return 200; }
 
 const char *la_status_string(la_status s)
 {
@@ -85,14 +128,28 @@ const char *la_status_string(la_status s)
         case LA_ERR_ALIGN: return "LA_ERR_ALIGN: pointer not 16-byte aligned";
         case LA_ERR_WORKSPACE: return "LA_ERR_WORKSPACE: workspace missing, misaligned or too small";
         case LA_ERR_LAUNCH: return "LA_ERR_LAUNCH: kernel enqueue failed";
+        case LA_ERR_ALIAS: return "LA_ERR_ALIAS: an output overlaps another buffer of the call";
     }
     return "unknown la_status";
+}
+
+void la_debug_override(int seg_len, int force_generic)
+{
+    // rows, a multiple of 64 after rounding; bounded so that the segment count stays an int
+    if (seg_len < 0) seg_len = 0;
+    if (seg_len > (1 << 30)) seg_len = 1 << 30;
+    la::g_seg_len_override.store(seg_len, std::memory_order_relaxed);
+    la::g_force_generic.store(force_generic ? 1 : 0, std::memory_order_relaxed);
 }
 
 size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
 {
     if (la::check_shape(B, H, N, D, dt) != LA_OK) return 0;
-    return la::make_plan(B, H, N, D, dt, causal, is_backward).total_bytes;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, is_backward ? 1 : 0);
+    if (!la::grid_ok(B, H, pl)) return 0;
+    if (is_backward != 2) return pl.total_bytes;
+    const la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
+    return la::recompute_layout(pl, pf, (size_t)B * H * N, D, dt).total_bytes;
 }
 
 size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal)
@@ -104,7 +161,7 @@ size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal)
 }
 
 // `saved` == nullptr: the plain entry points.  Otherwise the buffer must be present and
-// large enough whenever the library would use it.
+// large enough whenever the library would use it.  G may be NULL (then g is not stored).
 static la_status forward_impl(const void *Q, const void *K, const void *V, void *O, float *G,
                               int B, int H, int N, int D, float a, float b, int causal,
                               la_dtype dt, void *workspace, size_t workspace_bytes, bool save,
@@ -112,11 +169,12 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
-    if (!Q || !K || !V || !O || !G) return LA_ERR_NULL;
+    if (!Q || !K || !V || !O) return LA_ERR_NULL;
     if (!la::aligned16(Q) || !la::aligned16(K) || !la::aligned16(V) || !la::aligned16(O) ||
         !la::aligned16(G))
         return LA_ERR_ALIGN;
     const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 0);
+    if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
     if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
@@ -128,6 +186,14 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
         sv = (float *)saved;
     }
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
+    {
+        const size_t T = (size_t)B * H * N, tb = T * D * (dt == LA_F32 ? 4 : 2);
+        const la::Range ins[] = {{Q, tb}, {K, tb}, {V, tb}};
+        const la::Range outs[] = {{O, tb}, {G, T * 4}, {workspace, pl.total_bytes},
+                                  {sv, sv ? pl.saved_bytes : 0}};
+        if (la::any_alias(ins, 3, outs, 4)) return LA_ERR_ALIAS;
+    }
+    if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;  // left pending, nothing enqueued
     la::Tracer tc(trace, (hipStream_t)hip_stream);
     if (fast)
         return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace, sv,
@@ -136,6 +202,8 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
                                (hipStream_t)hip_stream, tc);
 }
 
+// O and G may be NULL: the forward pass is then run first into the tail of the workspace
+// (sized by la_workspace_bytes(..., 2)) and the pointers that were NULL take its results.
 static la_status backward_impl(const void *Q, const void *K, const void *V, const void *O,
                                const float *G, const void *dO, void *dQ, void *dK, void *dV,
                                int B, int H, int N, int D, float a, float b, int causal,
@@ -145,12 +213,18 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
-    if (!Q || !K || !V || !O || !G || !dO || !dQ || !dK || !dV) return LA_ERR_NULL;
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return LA_ERR_NULL;
     const void *ptrs[] = {Q, K, V, O, G, dO, dQ, dK, dV};
     for (const void *p : ptrs)
         if (!la::aligned16(p)) return LA_ERR_ALIGN;
     const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 1);
-    if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
+    if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
+    const bool recompute = !O || !G;
+    const la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
+    const size_t T = (size_t)B * H * N;
+    const la::Recompute rc = la::recompute_layout(pl, pf, T, D, dt);
+    const size_t need = recompute ? rc.total_bytes : pl.total_bytes;
+    if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
     const bool fast = la::use_fast(pr, 1);
@@ -161,12 +235,33 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         sv = (const float *)saved;
     }
     if (trace && (!trace->events || trace->capacity < 1)) return LA_ERR_NULL;
-    la::Tracer tc(trace, (hipStream_t)hip_stream);
+    {
+        const size_t tb = T * D * (dt == LA_F32 ? 4 : 2);
+        const la::Range ins[] = {{Q, tb}, {K, tb}, {V, tb}, {O, tb}, {G, T * 4}, {dO, tb},
+                                 {sv, sv ? pl.saved_bytes : 0}};
+        const la::Range outs[] = {{dQ, tb}, {dK, tb}, {dV, tb}, {workspace, need}};
+        if (la::any_alias(ins, 7, outs, 4)) return LA_ERR_ALIAS;
+    }
+    if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;  // left pending, nothing enqueued
+    hipStream_t st = (hipStream_t)hip_stream;
+    la::Tracer tc(trace, st);
+    if (recompute) {
+        char *wsb = (char *)workspace;
+        void *o2 = wsb + rc.o_off;
+        float *g2 = (float *)(wsb + rc.g_off);
+        const bool ffast = la::use_fast(pr, 0);
+        s = ffast ? la::fast_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off),
+                                     nullptr, st, tc)
+                  : la::generic_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
+                                        tc);
+        if (s != LA_OK) return s;
+        if (!O) O = o2;
+        if (!G) G = g2;
+    }
     if (fast)
-        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv,
-                                 (hipStream_t)hip_stream, tc);
-    return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace,
-                                (hipStream_t)hip_stream, tc);
+        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
+                                 tc);
+    return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st, tc);
 }
 
 la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,

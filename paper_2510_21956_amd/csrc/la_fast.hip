@@ -725,7 +725,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             if (l < C) {
                 const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 ginv[w][l] = 1.f / gv;
-                if (w == 0 && c0 + l < row1) Gp[c0 + l] = gv;
+                if (w == 0 && G && c0 + l < row1) Gp[c0 + l] = gv;
             }
             __builtin_amdgcn_wave_barrier();
             if constexpr (CAUSAL)

@@ -284,7 +284,7 @@ __global__ __launch_bounds__(NT) void k_fwd_apply(const T *__restrict__ Q, const
                 s += a * (float)N;
             }
             g[t] = s;
-            if (c0 + t < row1) Gp[c0 + t] = s;
+            if (G && c0 + t < row1) Gp[c0 + t] = s;
         }
         __syncthreads();
         for (int e = t; e < C * D; e += NT) {

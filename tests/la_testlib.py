@@ -47,6 +47,12 @@ def _dt(la, Q):
     return la.LA_F32 if Q.dtype == torch.float32 else la.LA_BF16
 
 
+def scratch(nbytes, device):
+    """A workspace / hand-over buffer filled with 0xFF (NaN patterns), so that a kernel
+    that reads a part of it nobody wrote shows up in the results."""
+    return torch.full((max(int(nbytes), 256),), 0xFF, dtype=torch.uint8, device=device)
+
+
 def gpu_forward(la, dev, a, b, causal):
     """dev: dict of device tensors Q, K, V [B,H,N,D].  Returns O, G (poisoned first,
     so that rows the kernels fail to write are caught)."""
@@ -54,8 +60,7 @@ def gpu_forward(la, dev, a, b, causal):
     B, H, N, D = Q.shape
     O = torch.full_like(Q, float("nan"))
     G = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=Q.device)
-    wf = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 0), 256),
-                     dtype=torch.uint8, device=Q.device)
+    wf = scratch(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 0), Q.device)
     la.la_forward(Q, K, V, O, G, a, b, causal, wf)
     torch.cuda.synchronize()
     return O, G
@@ -66,8 +71,7 @@ def gpu_backward(la, dev, O, G, a, b, causal):
     Q, K, V, dO = dev["Q"], dev["K"], dev["V"], dev["dO"]
     B, H, N, D = Q.shape
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-    wb = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 1), 256),
-                     dtype=torch.uint8, device=Q.device)
+    wb = scratch(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 1), Q.device)
     la.la_backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, wb)
     torch.cuda.synchronize()
     return dQ, dK, dV
@@ -80,10 +84,9 @@ def gpu_forward_save(la, dev, a, b, causal):
     B, H, N, D = Q.shape
     O = torch.full_like(Q, float("nan"))
     G = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=Q.device)
-    wf = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 0), 256),
-                     dtype=torch.uint8, device=Q.device)
+    wf = scratch(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 0), Q.device)
     nb = la.la_saved_state_bytes(B, H, N, D, _dt(la, Q), causal)
-    saved = torch.full((nb,), 0xFF, dtype=torch.uint8, device=Q.device) if nb else None
+    saved = scratch(nb, Q.device) if nb else None
     la.la_forward_save(Q, K, V, O, G, a, b, causal, wf, saved)
     torch.cuda.synchronize()
     return O, G, saved
@@ -94,8 +97,7 @@ def gpu_backward_saved(la, dev, O, G, saved, a, b, causal):
     Q, K, V, dO = dev["Q"], dev["K"], dev["V"], dev["dO"]
     B, H, N, D = Q.shape
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
-    wb = torch.empty(max(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 1), 256),
-                     dtype=torch.uint8, device=Q.device)
+    wb = scratch(la.la_workspace_bytes(B, H, N, D, _dt(la, Q), causal, 1), Q.device)
     la.la_backward_saved(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, wb, saved)
     torch.cuda.synchronize()
     return dQ, dK, dV
@@ -116,14 +118,27 @@ def saved_set(O_ref, G_ref, dtype):
     return O_bits, O_64, G_32, G_32.astype(np.float64)
 
 
-def upload_case(B, H, N, D, dtype, seed, keep_slices, normalise=True):
+def upload_case(B, H, N, D, dtype, seed, keep_slices, normalise=True, only_kept=False):
     """Draw the inputs slice by slice, upload all of them, and keep float64 copies
-    of the slices in ``keep_slices`` (flat b*H+h indices) for the oracle."""
+    of the slices in ``keep_slices`` (flat b*H+h indices) for the oracle.
+
+    ``only_kept``: for the largest shapes only the kept slices follow the seeded
+    recipe; the others (never compared) are drawn on the device from the same
+    distributions, which saves minutes of host-side drawing."""
     td = torch_dtype(dtype)
     dev = {n: torch.empty((B * H, N, D), dtype=td, device="cuda") for n in ("Q", "K", "V", "dO")}
     kept = {n: [] for n in ("Q", "K", "V", "dO")}
     keep = set(keep_slices)
-    for s in range(B * H):
+    if only_kept:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        for n in dev:
+            for s in range(B * H):
+                x = torch.randn((N, D), device="cuda", dtype=torch.float32, generator=gen)
+                if normalise and n in ("Q", "K"):
+                    x = x / x.norm(dim=-1, keepdim=True)
+                dev[n][s].copy_(x.to(td))
+    for s in (sorted(keep) if only_kept else range(B * H)):
         sl = wl.make_slice(N, D, dtype, seed, s, normalise)
         for n in dev:
             dev[n][s].copy_(to_device(sl[n][0], dtype))

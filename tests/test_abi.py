@@ -35,8 +35,9 @@ def test_version_and_strings(lib):
     import paper_2510_21956_amd as la
     assert la.la_version() >= 100
     assert la.la_status_string(0) == "LA_OK"
-    for code in range(1, 7):
+    for code in range(1, 8):
         assert la.la_status_string(code).startswith("LA_ERR_")
+    assert la.la_status_string(99) == "unknown la_status"
 
 
 def test_workspace_bytes(lib):
@@ -51,6 +52,22 @@ def test_workspace_bytes(lib):
     assert la.la_workspace_bytes(1, 1, 2 ** 31 - 1, 128, la.LA_F32, 1, 0) > 0
     assert la.la_workspace_bytes(64, 64, 2 ** 21, 128, la.LA_F32, 1, 0) == 0   # 2^40 elements
     assert la.la_workspace_bytes(1024, 1024, 64, 64, la.LA_F32, 1, 0) == 0     # too many slices
+    # a backward pass that recomputes O and g needs room for them and for the forward pass
+    assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 2) >= \
+        la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 1) + \
+        la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0) + 4 * 16 * 4096 * (64 * 4 + 4)
+    # the test hook changes the plan, hence the sizes; 0, 0 restores the automatic plan
+    auto = la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0)
+    la.la_debug_override(64, 0)
+    assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0) > auto
+    la.la_debug_override(0, 1)
+    assert la.la_saved_state_bytes(4, 16, 4096, 64, la.LA_F32, 1) == 0
+    la.la_debug_override(0, 0)
+    assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0) == auto
+    # slices x segments must fit the launch grid
+    la.la_debug_override(64, 0)
+    assert la.la_workspace_bytes(1, 4096, 2 ** 26, 16, la.LA_F32, 1, 0) == 0
+    la.la_debug_override(0, 0)
     # the hand-over buffer: present for the matrix-core head sizes, absent otherwise
     assert la.la_saved_state_bytes(4, 16, 4096, 64, la.LA_F32, 1) > 0
     assert la.la_saved_state_bytes(4, 16, 4096, 128, la.LA_BF16, 0) > 0
@@ -86,6 +103,18 @@ def test_argument_checks_precede_any_launch(lib):
     rc = lib.la_backward(fake, fake, fake, fake, fake, fake, fake, fake, vp(0), 1, 1, 64, 16, 1.0,
                          0.5, 1, 0, fake, 1 << 20, vp(0))
     assert rc == 1
+    # overlapping buffers (distinct 1 MiB-spaced fakes; O on top of Q, then dK on top of dQ)
+    f = [vp(0x10000000 + k * (1 << 20)) for k in range(12)]
+    rc = lib.la_forward(f[0], f[1], f[2], f[0], f[4], 1, 1, 64, 16, 1.0, 0.5, 1, 0, f[5], 1 << 20,
+                        vp(0))
+    assert rc == 7
+    rc = lib.la_backward(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[6], f[8], 1, 1, 64, 16, 1.0,
+                         0.5, 1, 0, f[9], 1 << 20, vp(0))
+    assert rc == 7
+    # a workspace that overlaps an input
+    rc = lib.la_forward(f[0], f[1], f[2], f[3], f[4], 1, 1, 64, 16, 1.0, 0.5, 1, 0, f[1], 1 << 20,
+                        vp(0))
+    assert rc == 7
     rc = lib.la_backward(fake, fake, fake, fake, fake, fake, fake, fake, fake, 4, 16, 4096, 64,
                          1.0, 0.5, 1, 0, fake, 16, vp(0))
     assert rc == 5

@@ -4,8 +4,6 @@ oracle on the same seeded inputs.
 Tolerance (stated by the benchmark spec: max relative error 1e-4 for fp32 I/O, 2e-2 for
 bf16 I/O with fp32 accumulation), applied per element as
 |gpu - ref| <= tol * (|ref| + rms(ref)) for each output tensor."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -27,13 +25,10 @@ def la():
 
 
 @pytest.fixture
-def seg_len_env():
-    old = os.environ.get("LA_SEG_LEN")
-    yield
-    if old is None:
-        os.environ.pop("LA_SEG_LEN", None)
-    else:
-        os.environ["LA_SEG_LEN"] = old
+def knobs(la):
+    """la_debug_override for the duration of one test: knobs(seg_len, force_generic)."""
+    yield la.la_debug_override
+    la.la_debug_override(0, 0)
 
 
 def check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, a, b, causal, tag):
@@ -96,17 +91,14 @@ SMALL = [
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("causal", [True, False])
 @pytest.mark.parametrize("shape", SMALL)
-def test_small_shapes(oracle_mod, la, seg_len_env, shape, causal, dtype):
+def test_small_shapes(oracle_mod, la, knobs, shape, causal, dtype):
     """Sizes the oracle finishes in well under a second; several chunks, ragged
     tails, single rows; segments forced short so that several segments and a
     ragged last segment occur."""
     B, H, N, D = shape
     a, b = 1.0, 0.5
     for seg in ("64", "192", None):
-        if seg is None:
-            os.environ.pop("LA_SEG_LEN", None)
-        else:
-            os.environ["LA_SEG_LEN"] = seg
+        knobs(int(seg) if seg else 0, 0)
         tag = "small B%d H%d N%d D%d %s %s seg=%s" % (B, H, N, D, dtype,
                                                       "causal" if causal else "full", seg)
         print("case", tag, flush=True)
@@ -115,15 +107,71 @@ def test_small_shapes(oracle_mod, la, seg_len_env, shape, causal, dtype):
         check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, a, b, causal, tag)
 
 
-@pytest.mark.parametrize("ab", [(2.0, -0.7), (0.5, 0.0), (1.0, 0.9)])
-def test_other_coefficients(oracle_mod, la, seg_len_env, ab):
-    os.environ["LA_SEG_LEN"] = "64"
+# General coefficients on every path.  With a = 1 every factor `a` in the kernels is
+# invisible, so: a != 1 with b < 0, b = 0 (the linear term vanishes), b close to a (small
+# denominators), and a = b = 1, the kernel the paper's own implementation fixes (Sec. 4).
+# 64-row segments and N = 203 give four segments with a ragged tail in the last chunk.
+COEFS = [(2.0, -0.7), (0.5, 0.0), (1.0, 0.9), (1.0, 1.0)]
+
+
+@pytest.mark.parametrize("ab", COEFS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [32, 64, 128])
+def test_other_coefficients(oracle_mod, la, knobs, D, dtype, ab):
+    knobs(64, 0)
     a, b = ab
     for causal in (True, False):
         slices = [0, 1]
-        dev, ref = upload_case(1, 2, 200, 32, "f32", 77, slices)
-        check_against_oracle(oracle_mod, la, dev, ref, slices, "f32", a, b, causal,
-                             "coef a=%g b=%g causal=%d" % (a, b, causal))
+        tag = "coef D=%d %s a=%g b=%g causal=%d" % (D, dtype, a, b, causal)
+        print("case", tag, flush=True)
+        dev, ref = upload_case(1, 2, 203, D, dtype, 77 + D, slices)
+        check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, a, b, causal, tag)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_plain_alu_path_at_large_heads(oracle_mod, la, knobs, D, dtype):
+    """The plain-ALU kernels are compiled for every head size; force them where the
+    matrix-core kernels would normally run."""
+    knobs(128, 1)
+    for causal in (True, False):
+        slices = [0, 1, 2]
+        tag = "plain-ALU D=%d %s causal=%d" % (D, dtype, causal)
+        print("case", tag, flush=True)
+        dev, ref = upload_case(1, 3, 300, D, dtype, 501 + D, slices)
+        check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, 1.5, 0.6, causal, tag)
+
+
+def test_optional_saved_set(la, knobs):
+    """G = NULL in la_forward; O and/or G = NULL in la_backward (recomputed inside the call).
+    The recomputation runs the same kernels on the same plan, so gradients must equal the
+    chained run's bit for bit."""
+    for (B, H, N, D, dtype, seg) in ((2, 2, 700, 64, "f32", 0), (1, 2, 333, 128, "bf16", 64),
+                                     (1, 2, 100, 32, "f32", 0)):
+        knobs(seg, 0)
+        for causal in (True, False):
+            print("case optional", B, H, N, D, dtype, seg, causal, flush=True)
+            dev, _ = upload_case(B, H, N, D, dtype, 31 + D, [])
+            O, G, dQ, dK, dV = run_gpu(la, dev, 1.0, 0.5, causal)
+            dt = la.LA_F32 if dtype == "f32" else la.LA_BF16
+            from la_testlib import scratch
+            O2 = torch.full_like(O, float("nan"))
+            la.la_forward(dev["Q"], dev["K"], dev["V"], O2, None, 1.0, 0.5, causal,
+                          scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 0), "cuda"))
+            assert torch.equal(O2, O)
+            for Oin, Gin in ((None, None), (O, None), (None, G)):
+                g = [torch.full_like(O, float("nan")) for _ in range(3)]
+                wb = scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 2), "cuda")
+                la.la_backward(dev["Q"], dev["K"], dev["V"], Oin, Gin, dev["dO"], g[0], g[1], g[2],
+                               1.0, 0.5, causal, wb)
+                torch.cuda.synchronize()
+                assert torch.equal(g[0], dQ) and torch.equal(g[1], dK) and torch.equal(g[2], dV)
+            # the plain workspace size is not enough for the recomputation
+            with pytest.raises(la.LaError) as e:
+                wb = scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 1), "cuda")
+                la.la_backward(dev["Q"], dev["K"], dev["V"], None, None, dev["dO"], g[0], g[1],
+                               g[2], 1.0, 0.5, causal, wb)
+            assert e.value.code == 5
 
 
 # Full-size configurations, in the launch configuration the benchmark times.  The
@@ -133,8 +181,8 @@ FULL = [(0, [0]), (1, [0, 37, 63]), (2, [0, 41]), (3, [0, 127]), (4, [5])]
 
 
 @pytest.mark.parametrize("index,slices", FULL)
-def test_full_configs(oracle_mod, la, seg_len_env, index, slices):
-    os.environ.pop("LA_SEG_LEN", None)
+def test_full_configs(oracle_mod, la, knobs, index, slices):
+    knobs(0, 0)
     c = wl.CONFIGS[index]
     print("case", c.name, "slices", slices, flush=True)
     dev, ref = upload_case(c.B, c.H, c.N, c.D, c.dtype, wl.SEED_BASE + index, slices)
@@ -152,18 +200,57 @@ PAPER = [("paper_causal_f32_B4_H16_N1000_D128", [0, 21, 63]),
 
 
 @pytest.mark.parametrize("name,slices", PAPER)
-def test_paper_shapes(oracle_mod, la, seg_len_env, name, slices):
-    os.environ.pop("LA_SEG_LEN", None)
+def test_paper_shapes(oracle_mod, la, knobs, name, slices):
+    knobs(0, 0)
     c = wl.find_workload(name)
     print("case", c.name, "slices", slices, flush=True)
     dev, ref = upload_case(c.B, c.H, c.N, c.D, c.dtype, wl.workload_seed(c), slices)
     check_against_oracle(oracle_mod, la, dev, ref, slices, c.dtype, c.a, c.b, c.causal, c.name)
 
 
-def test_definition_rows_on_long_config(oracle_mod, la, seg_len_env):
+@pytest.mark.parametrize("name,with_backward", [("paper_causal_f32_B4_H16_N100000_D128", True),
+                                                ("paper_causal_f32_B4_H16_N300000_D128", False)])
+def test_paper_long_shapes(oracle_mod, la, knobs, name, with_backward):
+    """The two long rows of the paper's length sweep (Sec. 5.1) in the launch configuration
+    the benchmark times: sampled rows of O, g recomputed one by one from the O(N^2 D)
+    definition, and (N = 10^5) every row of one slice's gradients against the running-sum
+    oracle fed the stored set."""
+    knobs(0, 0)
+    c = wl.find_workload(name)
+    s = 29
+    print("case", c.name, "slice", s, flush=True)
+    dev, ref = upload_case(c.B, c.H, c.N, c.D, c.dtype, wl.workload_seed(c), [s], only_kept=True)
+    O, G = gpu_forward(la, dev, c.a, c.b, c.causal)
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, c.N - 1], rng.integers(0, c.N, 120)]))
+    o_ref, g_ref = oracle_mod.forward_def_rows(ref["Q"][0], ref["K"][0], ref["V"][0], rows,
+                                               c.a, c.b, c.causal)
+    o_gpu = to_f64(O.reshape(c.B * c.H, c.N, c.D)[s][rows])
+    g_gpu = to_f64(G.reshape(c.B * c.H, c.N)[s][rows])
+    eo, eg = excess(o_gpu, o_ref, TOL[c.dtype]), excess(g_gpu, g_ref, TOL["f32"])
+    print(c.name, "rows: O", round(eo, 4), "G", round(eg, 4), flush=True)
+    assert eo <= 1.0 and eg <= 1.0
+    if not with_backward:
+        return
+    O_ref, G_ref = oracle_mod.forward_rec(ref["Q"], ref["K"], ref["V"], c.a, c.b, c.causal)
+    O_bits, O_64, G_32, G_64 = saved_set(O_ref, G_ref, c.dtype)
+    grads_ref = oracle_mod.backward_rec(ref["Q"], ref["K"], ref["V"], O_64, G_64, ref["dO"],
+                                        c.a, c.b, c.causal)
+    assert excess(to_f64(O.reshape(c.B * c.H, c.N, c.D)[s]), O_ref[0], TOL[c.dtype]) <= 1.0
+    O.view(c.B * c.H, c.N, c.D)[s] = to_device(O_bits, c.dtype)[0]
+    G.view(c.B * c.H, c.N)[s] = torch.from_numpy(G_32).cuda()[0]
+    dQ, dK, dV = gpu_backward(la, dev, O, G, c.a, c.b, c.causal)
+    for nm, got, want in (("dQ", dQ, grads_ref[0]), ("dK", dK, grads_ref[1]),
+                          ("dV", dV, grads_ref[2])):
+        e = excess(to_f64(got.reshape(c.B * c.H, c.N, c.D)[s]), want[0], TOL[c.dtype])
+        print(c.name, nm, round(e, 4), flush=True)
+        assert e <= 1.0, "%s exceeds tolerance by factor %.3g" % (nm, e)
+
+
+def test_definition_rows_on_long_config(oracle_mod, la, knobs):
     """Long-sequence configuration: sampled rows recomputed one by one from the
     O(N^2 D) definition (not the running sums)."""
-    os.environ.pop("LA_SEG_LEN", None)
+    knobs(0, 0)
     index = 4
     c = wl.CONFIGS[index]
     s = 11
@@ -181,11 +268,11 @@ def test_definition_rows_on_long_config(oracle_mod, la, seg_len_env):
 
 
 @pytest.mark.parametrize("dtype,causal", [("f32", True), ("bf16", True), ("f32", False)])
-def test_autograd_wrapper(oracle_mod, la, seg_len_env, dtype, causal):
+def test_autograd_wrapper(oracle_mod, la, knobs, dtype, causal):
     """The torch.autograd wrapper: gradients of sum(O * dO) obtained through
     torch's backward() against the oracle's (chained: the wrapper's backward consumes the
     wrapper's own O and g)."""
-    os.environ.pop("LA_SEG_LEN", None)
+    knobs(0, 0)
     B, H, N, D = 2, 3, 700, 64
     a, b = 1.0, 0.5
     slices = list(range(B * H))
@@ -206,8 +293,8 @@ def test_autograd_wrapper(oracle_mod, la, seg_len_env, dtype, causal):
         assert e <= 1.0, "%s exceeds tolerance by factor %.3g" % (name, e)
 
 
-def test_run_to_run_determinism(la, seg_len_env):
-    os.environ.pop("LA_SEG_LEN", None)
+def test_run_to_run_determinism(la, knobs):
+    knobs(0, 0)
     dev, _ = upload_case(2, 4, 1500, 64, "f32", 99, [])
     r1 = run_gpu(la, dev, 1.0, 0.5, True)
     r2 = run_gpu(la, dev, 1.0, 0.5, True)
@@ -232,6 +319,15 @@ def test_argument_errors(la):
     with pytest.raises(la.LaError) as e:
         la.la_forward(mis, Q.clone(), Q.clone(), Q.clone(), G, 1.0, 0.5, True, ws)
     assert e.value.code == 4
+    # an output that overlaps an input, and two outputs that overlap each other
+    with pytest.raises(la.LaError) as e:
+        la.la_forward(Q, Q.clone(), Q.clone(), Q, G, 1.0, 0.5, True, ws)
+    assert e.value.code == 7
+    with pytest.raises(la.LaError) as e:
+        dq = Q.clone()
+        la.la_backward(Q, Q.clone(), Q.clone(), Q.clone(), G, Q.clone(), dq, dq, Q.clone(), 1.0,
+                       0.5, True, ws)
+    assert e.value.code == 7
     # hand-over buffer: none is used for D = 16, one is required for D = 64
     assert la.la_saved_state_bytes(1, 1, 64, 16, la.LA_F32, 1) == 0
     la.la_forward_save(Q, Q.clone(), Q.clone(), Q.clone(), G, 1.0, 0.5, True, ws, None)
