@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--independent", action="store_true",
                     help="time la_forward + la_backward (no hand-over of running sums)")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
     ap.add_argument("--cpu-slices", type=int, default=64)
     ap.add_argument("--buffer-sets", type=int, default=0,
                     help="independent input/output sets rotated through (0: enough to exceed "
@@ -154,6 +156,64 @@ def main():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
     cfg = wl.find_workload(args.workload) if args.workload else wl.CONFIGS[args.config]
+    out = measure(cfg, args, args.steps, args.warmup, torch, wl, la)
+    if not args.no_all_configs and not args.workload and not args.forward_only:
+        # the other benchmark configurations (the smallest is a parity case only), same
+        # entry points, fewer steps: timed rows next to the headline one
+        rows = {}
+        for i, c in enumerate(wl.CONFIGS):
+            if i == 0 or c is cfg:
+                continue
+            r = measure(c, args, max(10, args.steps // 4), max(5, args.warmup // 2), torch, wl, la)
+            rows[c.name] = {
+                "ms_per_step": r["ms_per_step"], "tokens_per_s": r["value"],
+                "whole_pass_frac_of_hbm_peak": r["whole_pass"]["frac_of_hbm_peak"],
+                "dominant_kernel": r["roofline"]["kernel"] if r["roofline"] else None,
+                "dominant_kernel_frac": r["roofline"]["frac"] if r["roofline"] else None,
+                "kernels_ms": r["kernels_ms"], "steps": r["steps"], "dtype": r["dtype"]}
+        out["all_configs"] = rows
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_slices)
+    print(json.dumps(out))
+
+
+def source_digest():
+    """sha256 over the HIP sources: profiles/traffic.json records the digest of the sources
+    its counters were collected with, so that stale counters are not quoted."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2510_21956_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def algorithmic_bytes(D, e, causal):
+    """Algorithmic HBM bytes per token-head of each kernel: every operand the kernel needs
+    read once, every result written once (G, delta' are one float per token-head).
+
+      with the mask                                      without it (states are global sums)
+      fwd_state: K, V in                      2De       the same
+      fwd_apply: Q, K, V in; O, G out         4De + 4   Q in; O, G out                 2De + 4
+      bwd_state: K, V in                      2De       the same
+      bwd_dq   : Q, K, V, O, dO, G in;                  Q, O, dO, G in;
+                 dQ, delta' out               6De + 8   dQ, delta' out                 4De + 8
+      bwd_dkv  : Q, K, V, dO, G, delta' in;             K, V in; dK, dV out            4De
+                 dK, dV out                   6De + 8
+      plain-ALU path: generic_bwd_state reads Q, K, V, O, dO, G and writes delta (5De + 8);
+      generic_bwd_apply reads Q, K, V, dO, G, delta and writes dQ, dK, dV (7De + 8)."""
+    De = D * e
+    m = bool(causal)
+    return {"fwd_state": 2 * De, "fwd_apply": (4 * De + 4) if m else (2 * De + 4),
+            "bwd_state": 2 * De, "bwd_dq": (6 * De + 8) if m else (4 * De + 8),
+            "bwd_dkv": (6 * De + 8) if m else 4 * De,
+            "generic_fwd_state": 2 * De, "generic_fwd_apply": (4 * De + 4) if m else (2 * De + 4),
+            "generic_bwd_state": 5 * De + 8, "generic_bwd_apply": 7 * De + 8}
+
+
+def measure(cfg, args, steps, warmup, torch, wl, la):
+    """Time `steps` steps of one workload and the library's kernels inside a step."""
     B, H, N, D = cfg.B, cfg.H, cfg.N, cfg.D
     e = 4 if cfg.dtype == "f32" else 2
     dt = la.LA_F32 if cfg.dtype == "f32" else la.LA_BF16
@@ -163,7 +223,8 @@ def main():
     # the 256 MB memory-side cache left there by the previous step.
     set_bytes = 8 * T * D * e + 4 * T
     n_sets = args.buffer_sets or max(2, min(8, int(1.5 * 1024 ** 3 // set_bytes) or 1))
-    free0 = torch.cuda.mem_get_info()[0]
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
     sets = make_device_inputs(cfg, torch, n_sets)
     wsf = torch.empty(max(256, la.la_workspace_bytes(B, H, N, D, dt, cfg.causal, 0)),
                       dtype=torch.uint8, device="cuda")
@@ -194,22 +255,22 @@ def main():
                                  t["dK"], t["dV"], cfg.a, cfg.b, cfg.causal, wsb, saved, None,
                                  trb)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(sets[i % n_sets])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(sets[i % n_sets])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    peak_bytes = free0 - torch.cuda.mem_get_info()[0]
+    ms_per_step = elapsed * 1e3 / steps
+    peak_bytes = torch.cuda.max_memory_allocated()
 
     # Per-kernel durations: the same steps again, back to back and straight after the timed
     # loop (so at the same clocks), with the library recording HIP events between its kernels
     # on the stream it launches on.  Every repetition has event handles of its own; nothing
     # waits until all of them are enqueued.
-    reps = max(5, min(args.steps, 50))
+    reps = max(5, min(steps, 50))
     traces = []
     for i in range(reps):
         evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
@@ -218,7 +279,7 @@ def main():
         trb.events = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p))
         trf.capacity = trb.capacity = la.LA_MAX_TRACE + 1
         traces.append((trf, evf, trb, evb))
-    for i in range(min(5, args.warmup)):  # handle creation took a while: back to speed first
+    for i in range(min(5, warmup)):  # handle creation took a while: back to speed first
         step(sets[i % n_sets])
     for i, (trf, evf, trb, evb) in enumerate(traces):
         step(sets[i % n_sets], trf, trb)
@@ -234,41 +295,39 @@ def main():
         evb.destroy()
     kernels_ms = {k: ksum[k] / kcount[k] for k in ksum}
 
-    # Roofline of the dominant kernel.  Algorithmic bytes per token-head of each step
-    # of the path (every operand the step needs read once, every result written once;
-    # G, delta' are one float per token-head):
-    #   fwd_state: K, V in                                   2 D e
-    #   fwd_apply: Q, K, V in; O, G out                      4 D e + 4
-    #   bwd_state: K, V in                                   2 D e
-    #   bwd_dq   : Q, K, V, O, dO, G in; dQ, delta' out      6 D e + 8
-    #   bwd_dkv  : Q, K, V, dO, G, delta' in; dK, dV out     6 D e + 8
-    #   plain-ALU path: generic_bwd_state reads Q, K, V, O, dO, G and writes delta
-    #   (5 D e + 8); generic_bwd_apply reads Q, K, V, dO, G, delta and writes dQ, dK, dV
-    #   (7 D e + 8)
-    alg_bytes = {"fwd_state": 2 * D * e, "fwd_apply": 4 * D * e + 4, "bwd_state": 2 * D * e,
-                 "bwd_dq": 6 * D * e + 8, "bwd_dkv": 6 * D * e + 8,
-                 "generic_fwd_state": 2 * D * e, "generic_fwd_apply": 4 * D * e + 4,
-                 "generic_bwd_state": 5 * D * e + 8, "generic_bwd_apply": 7 * D * e + 8}
+    # Roofline of the dominant kernel (the one with the longest average duration).
+    alg_bytes = algorithmic_bytes(D, e, cfg.causal)
     dom = max(kernels_ms, key=kernels_ms.get)
     dom_key = dom.split(":")[1] if dom.split(":")[1] in alg_bytes else None
     dom_ms = kernels_ms[dom]
-    roofline = None
-    if dom_key:
-        achieved = alg_bytes[dom_key] * T / (dom_ms * 1e-3) / 1e9
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        if os.path.exists(tpath):
-            # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-            # scaled by a copy kernel of known size (see profiles/)
-            rec = json.load(open(tpath)).get(cfg.name, {}).get(dom.split(":")[1])
-            if rec:
-                traffic = rec["fetch_bytes"] + rec["write_bytes"]
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T}
     # every input once, every output once: forward + backward, or the forward pass alone
     pass_bytes = ((4 * D * e + 4) if args.forward_only else (12 * D * e + 8)) * T
     pass_gbs = pass_bytes / (ms_per_step * 1e-3) / 1e9
+    roofline = None
+    if dom_key:
+        achieved = alg_bytes[dom_key] * T / (dom_ms * 1e-3) / 1e9
+        traffic, traffic_note = None, "no counter record for this workload"
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+            # scaled by a copy kernel of known size (see profiles/); quoted only while the
+            # kernels are still the ones the counters were collected with
+            tj = json.load(open(tpath))
+            rec = tj.get(cfg.name, {}).get(dom.split(":")[1])
+            if rec and tj.get("source_sha256") != source_digest():
+                traffic_note = "profiles/traffic.json predates the current kernels: not quoted"
+            elif rec:
+                traffic = rec["fetch_bytes"] + rec["write_bytes"]
+                traffic_note = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch (profiles/)"
+                # a kernel cannot move less than its operands: if this fails, the table of
+                # algorithmic bytes above credits the kernel with operands it does not touch
+                assert alg_bytes[dom_key] * T <= 1.05 * traffic, (dom, alg_bytes[dom_key] * T,
+                                                                    traffic)
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "traffic_note": traffic_note,
+                    "kernel_ms": dom_ms, "algorithmic_bytes_per_launch": alg_bytes[dom_key] * T,
+                    "whole_pass_frac": pass_gbs / HBM_PEAK_GBS}
     # Algorithmic matrix flops of the recurrences per token-head (Sec. 3.1 / 3.2): forward
     # 4 D^2 (update S, read it out), backward 10 D^2 (rebuild S, S OmegaHat, update R, R v,
     # R^T k); without the mask the sums are formed once per slice and the rebuild is free.
@@ -282,8 +341,8 @@ def main():
         "value": cfg.tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -300,13 +359,13 @@ def main():
                        "algorithmic_flops": pass_flops, "achieved_TFLOPs": pass_tflops,
                        "mfma_peak_TFLOPs": mfma_peak, "frac_of_mfma_peak": pass_tflops / mfma_peak},
         "kernels_ms": kernels_ms,
-        "peak_device_bytes": int(peak_bytes),
+        "peak_allocated_device_bytes": int(peak_bytes),
         "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel(), "saved": nsv},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_slices)
-    print(json.dumps(out))
+    del sets, wsf, wsb, saved
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -13,6 +13,7 @@ Functions (paper passages in the C file's comments):
   forward_def_rows                -- definition at selected rows of one slice
 """
 import ctypes
+import hashlib
 import os
 import subprocess
 
@@ -20,16 +21,34 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "la_oracle.c")
-_LIB = os.path.join(_HERE, "libla_oracle.so")
 _lib = None
 
 
+def _cpu_tag():
+    """The library is built with -march=native, so one build serves one kind of CPU only:
+    the file name carries a digest of this host's instruction-set flags, and a host with
+    other flags builds its own copy instead of loading code it may not be able to run."""
+    flags = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("flags"):
+                flags = line
+                break
+    except OSError:
+        pass
+    return hashlib.sha1(flags.encode()).hexdigest()[:10]
+
+
+_LIB = os.path.join(_HERE, "libla_oracle_%s.so" % _cpu_tag())
+
+
 def build(force=False):
-    """Compile la_oracle.c into libla_oracle.so next to it (gcc, OpenMP)."""
+    """Compile la_oracle.c into a shared library next to it (gcc -O3 -march=native, OpenMP;
+    -std=c11 keeps floating-point contraction and reassociation off)."""
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB
-    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+    cmd = ["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
            "-o", _LIB, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
     return _LIB
