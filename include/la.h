@@ -126,6 +126,26 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * la_forward for callers that cannot allocate or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same computation and results as la_forward, with the workspace in a static
+ * device array inside the library (LA_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends).  The call allocates nothing and frees nothing.  Problems
+ * whose la_workspace_bytes(..., 0) exceeds LA_STATIC_SCRATCH_BYTES are
+ * rejected with LA_ERR_WORKSPACE (nothing enqueued); the five benchmark
+ * configurations fit.  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams, different threads) race, and
+ * the caller must order them.  The first call on each GPU resolves the
+ * array's device address (make it outside graph capture); if that fails the
+ * call returns LA_ERR_LAUNCH.
+ */
+#define LA_STATIC_SCRATCH_BYTES (32u << 20)
+LA_API la_status la_forward_static(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt, void *hip_stream);
+
+/*
  * Test and profiling hook -- the only process-wide state of the library.
  * seg_len > 0 forces the number of rows per segment (rounded up to a multiple
  * of 64; 0 restores the automatic choice); force_generic != 0 routes every

@@ -19,7 +19,7 @@ LA_MAX_TRACE = 8
 
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
-           "la_backward_saved", "la_debug_override")
+           "la_backward_saved", "la_debug_override", "la_forward_static")
 
 
 class la_trace(ctypes.Structure):
@@ -73,6 +73,8 @@ def load_library():
     lib.la_forward_save.argtypes = lib.la_forward.argtypes[:-1] + [vp, sz, vp, tp]
     lib.la_backward_saved.restype = i
     lib.la_backward_saved.argtypes = lib.la_backward.argtypes[:-1] + [vp, sz, vp, tp]
+    lib.la_forward_static.restype = i
+    lib.la_forward_static.argtypes = lib.la_forward.argtypes[:-3] + [vp]
     lib.la_debug_override.restype = None
     lib.la_debug_override.argtypes = [i, i]
     _lib = lib
@@ -135,6 +137,28 @@ def la_forward(Q, K, V, O, G, a, b, causal, workspace, stream=None):
     Q, K, V, O: [B, H, N, D] float32 or bfloat16; G: [B, H, N] float32;
     workspace: uint8 device tensor of at least la_workspace_bytes(..., 0) bytes."""
     la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream, None)
+
+
+LA_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def la_forward_static(Q, K, V, O, G, a, b, causal, stream=None):
+    """la_forward_static of include/la.h: la_forward with the library's own static scratch."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, N, D]")
+    B, H, N, D = Q.shape
+    _check_tensors(Q, K, V, O, G)
+    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape:
+        raise ValueError("shape mismatch")
+    if not (K.dtype == V.dtype == O.dtype == Q.dtype):
+        raise TypeError("dtype mismatch")
+    if G is not None and (G.shape != Q.shape[:3] or G.dtype != torch.float32):
+        raise ValueError("G must be [B, H, N] float32 (or None)")
+    rc = load_library().la_forward_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), B, H, N, D,
+                                          float(a), float(b), int(bool(causal)), _dtype_code(Q),
+                                          _stream_ptr(stream, Q.device))
+    if rc != 0:
+        raise LaError(rc, "la_forward_static")
 
 
 def la_forward_traced(Q, K, V, O, G, a, b, causal, workspace, stream=None, trace=None):

@@ -5,6 +5,11 @@
 
 namespace la {
 
+// Scratch of la_forward_static: one copy per GPU the library runs on, held until the process
+// ends.  The name is a host-side stand-in, not a device address: host code resolves the
+// address once per device (static_scratch below) and passes that to the kernels.
+static __device__ __align__(256) unsigned char scratch[LA_STATIC_SCRATCH_BYTES];
+
 // Test / profiling override (la_debug_override): 0 = automatic.
 static std::atomic<int> g_seg_len_override{0};
 static std::atomic<int> g_force_generic{0};
@@ -262,6 +267,40 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
                                  tc);
     return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st, tc);
+}
+
+// Device address of `scratch` on the current device, resolved on the first call on that
+// device and kept.  Returns nullptr if the runtime cannot resolve it.
+static void *static_scratch()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> ptrs[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = ptrs[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(la::scratch)) != hipSuccess || !p) return nullptr;
+    ptrs[dev].store(p, std::memory_order_release);  // racing first calls store the same value
+    return p;
+}
+
+la_status la_forward_static(const void *Q, const void *K, const void *V, void *O, float *G, int B,
+                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                            void *hip_stream)
+{
+    // everything the host can reject is rejected before the runtime is touched
+    la_status s = la::check_shape(B, H, N, D, dt);
+    if (s != LA_OK) return s;
+    if (!Q || !K || !V || !O) return LA_ERR_NULL;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 0);
+    if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
+    if (pl.total_bytes > (size_t)LA_STATIC_SCRATCH_BYTES) return LA_ERR_WORKSPACE;
+    void *ws = static_scratch();
+    if (!ws) return LA_ERR_LAUNCH;
+    // nothing in the forward workspace has to start at zero: every slot that is read has
+    // been written by this call's own kernels first
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, ws, LA_STATIC_SCRATCH_BYTES,
+                        false, nullptr, 0, hip_stream, nullptr);
 }
 
 la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,
