@@ -122,6 +122,8 @@ def main():
                     help="time la_forward + la_backward (no hand-over of running sums)")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
+    ap.add_argument("--seg-len", type=int, default=0,
+                    help="force the rows per segment (la_debug_override; 0: the library's plan)")
     ap.add_argument("--cpu-slices", type=int, default=64)
     ap.add_argument("--buffer-sets", type=int, default=0,
                     help="independent input/output sets rotated through (0: enough to exceed "
@@ -155,6 +157,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    la.la_debug_override(args.seg_len, 0)
     cfg = wl.find_workload(args.workload) if args.workload else wl.CONFIGS[args.config]
     out = measure(cfg, args, args.steps, args.warmup, torch, wl, la)
     if not args.no_all_configs and not args.workload and not args.forward_only:
@@ -350,7 +353,7 @@ def measure(cfg, args, steps, warmup, torch, wl, la):
         "dtype": "f32" if cfg.dtype == "f32" else "bf16 I/O, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "H": H, "N": N, "D": D, "causal": cfg.causal,
-                   "a": cfg.a, "b": cfg.b, "buffer_sets": n_sets,
+                   "a": cfg.a, "b": cfg.b, "buffer_sets": n_sets, "seg_len_override": args.seg_len,
                    "entry_points": "la_forward + la_backward" if args.independent
                    else "la_forward_save + la_backward_saved"},
         "token_heads_per_s": T / (ms_per_step * 1e-3),

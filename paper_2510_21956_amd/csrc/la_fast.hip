@@ -147,7 +147,7 @@ struct Stager {
 
     // Transposed tile with the elements of this thread's row i multiplied by s[i] in fp32;
     // with bf16 a second plane at tr + plane holds what the first plane's rounding lost.
-    __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, f4v s) const
+    __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, f4v s, bool lo_on) const
     {
         typedef typename Vec4<T>::type V4;
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
@@ -159,9 +159,11 @@ struct Stager {
             T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * (rq ^ F::swz(dg * F::EPV + e));
             *reinterpret_cast<V4 *>(dst) = v;
             if constexpr (Mma<T, F::BS>::PLANES == 2) {
-                V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
-                         from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
-                *reinterpret_cast<V4 *>(dst + plane) = vl;
+                if (lo_on) {
+                    V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
+                             from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
+                    *reinterpret_cast<V4 *>(dst + plane) = vl;
+                }
             }
         }
     }
@@ -329,7 +331,7 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
 // acc[m][j][i] += scale * sum_k col[k][j] * ys[m*16 + i][k]:  rows j = the wave's state
 // columns, columns i = rows of block m of the row-major tile `ys`, contraction over D.
 // col = the accumulator-resident state column.
-template <typename T, int D, int NM>
+template <typename T, int D, int NM, int SP = Mma<T, 16>::PLANES>  // SP planes of the state
 __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D / 16],
                                               float scale, const T *ys, int c, int g)
 {
@@ -350,7 +352,10 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
         [&](int kt, const B &b) {
             const typename M::Frag2 fx = column_frag<T, 16, NRB>(col, kt, scale);
 #pragma unroll
-            for (int m = 0; m < NM; ++m) M::mma2x(acc[m], fx, b.y[m]);
+            for (int m = 0; m < NM; ++m) {
+                if constexpr (SP == 2) M::mma2x(acc[m], fx, b.y[m]);
+                else M::mma(acc[m], fx.hi, b.y[m]);  // the unused second plane folds away
+            }
         });
 }
 
@@ -472,7 +477,7 @@ __device__ __forceinline__ void chunk_products_lower(Blk (&acc)[NBL], int ib0, c
 // are four consecutive rows, i.e. one 4-element vector store per plane.
 template <typename T, int D>
 __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0, int row0, int c,
-                                                   int g, const float (&vals)[4])
+                                                   int g, const float (&vals)[4], bool lo_on)
 {
     typedef Mma<T, 16> M;
     typedef typename Vec4<T>::type V4;
@@ -483,9 +488,11 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
     V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]), from_float<T>(hi[3])};
     *reinterpret_cast<V4 *>(dst) = vh;
     if constexpr (M::PLANES == 2) {
-        V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
-                 from_float<T>(lo[3])};
-        *reinterpret_cast<V4 *>(dst + plane) = vl;
+        if (lo_on) {
+            V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
+                     from_float<T>(lo[3])};
+            *reinterpret_cast<V4 *>(dst + plane) = vl;
+        }
     }
 }
 
@@ -579,7 +586,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
-    int nseg, int seg_len, size_t slot_floats, size_t saved_floats, float a, float b)
+    int nseg, int seg_len, size_t slot_floats, size_t saved_floats, float a, float b, int lo_rows)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -639,6 +646,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     if constexpr (CAUSAL) s2.load(Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
+        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of the weights: early rows
         if (h0) {
             s1.store_rows(Qs);
             if constexpr (CAUSAL) s2.store_cols(VTt);
@@ -670,11 +678,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                         vals[e] = x;
                         rs += x;
                     }
-                    store_weight_block<T, D>(Ps, PSZ, ib * 16, nb * 16, c, g, vals);
+                    store_weight_block<T, D>(Ps, PSZ, ib * 16, nb * 16, c, g, vals, lo_on);
                     if (KT > 16 && nb == ib && ib % 2 == 0) {
                         // the k-tile of the products below also covers the next block: zeros
                         const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-                        store_weight_block<T, D>(Ps, PSZ, ib * 16, (nb + 1) * 16, c, g, zero);
+                        store_weight_block<T, D>(Ps, PSZ, ib * 16, (nb + 1) * 16, c, g, zero, lo_on);
                     }
                     rs = reduce_lane_groups(rs);
                     if (g == 0) psum[nb][ib * 16 + c] = rs;
@@ -721,15 +729,18 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             Blk facc[NB];  // rows j = 16w + 4g + e, columns i
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
-            state_product<T, D, NB>(facc, st, b, Qs, c, g);
+            if (lo_on) state_product<T, D, NB>(facc, st, b, Qs, c, g);
+            else state_product<T, D, NB, 1>(facc, st, b, Qs, c, g);
             if (l < C) {
                 const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 ginv[w][l] = 1.f / gv;
                 if (w == 0 && G && c0 + l < row1) Gp[c0 + l] = gv;
             }
             __builtin_amdgcn_wave_barrier();
-            if constexpr (CAUSAL)
-                chunk_products_lower<T, D, NB, PP>(facc, 0, VTt, w * 16, Ps, PSZ, c, g, wo);
+            if constexpr (CAUSAL) {
+                if (lo_on) chunk_products_lower<T, D, NB, PP>(facc, 0, VTt, w * 16, Ps, PSZ, c, g, wo);
+                else chunk_products_lower<T, D, NB, 1>(facc, 0, VTt, w * 16, Ps, PSZ, c, g, wo);
+            }
             float gi[NB];
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) gi[ib] = ginv[w][ib * 16 + c];
@@ -784,7 +795,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
-    float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b)
+    float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b,
+    int lo_rows)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -859,6 +871,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         const float *rs = rsb[par];
+        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of weights and OmegaHat
         if (h0) {
             const f4v r4 = *reinterpret_cast<const f4v *>(rs + 4 * rq);
             // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
@@ -878,7 +891,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                 }
             }
             s1.store_rows(dOs);
-            if (need_R) s1.store_cols_scaled(OHt, TSZ, r4);
+            if (need_R) s1.store_cols_scaled(OHt, TSZ, r4, lo_on);
         } else if constexpr (CAUSAL) {
             s1.store_rows(Vs);
             s1.store_cols(VTt);
@@ -909,10 +922,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                         if (nb == ib && 4 * g + e > c) x = 0.f;
                         vals[e] = x;
                     }
-                    store_weight_block<T, D>(Cms, PSZ, ib * 16, nb * 16, c, g, vals);
+                    store_weight_block<T, D>(Cms, PSZ, ib * 16, nb * 16, c, g, vals, lo_on);
                     if (KT > 16 && nb == ib && ib % 2 == 0) {
                         const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-                        store_weight_block<T, D>(Cms, PSZ, ib * 16, (nb + 1) * 16, c, g, zero);
+                        store_weight_block<T, D>(Cms, PSZ, ib * 16, (nb + 1) * 16, c, g, zero, lo_on);
                     }
                 }
             }
@@ -927,7 +940,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                 const int r = 64 * part + l;
                 if (VJ::mine(1, part, w)) {
                     vw += tile_row_sum<T, D>(OHt, r);
-                    if constexpr (PP == 2) vw += tile_row_sum<T, D>(OHt + TSZ, r);
+                    if constexpr (PP == 2) {
+                        if (lo_on) vw += tile_row_sum<T, D>(OHt + TSZ, r);
+                    }
                 }
                 if (VJ::mine(2, part, w)) vu += tile_row_dot<T, D>(QTt, r, dls);
             }
@@ -947,9 +962,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             Blk acc[2];
             acc[0].zero();
             acc[1].zero();
-            state_product<T, D, 2>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
-            if constexpr (CAUSAL)
-                chunk_products_lower<T, D, 2, PP>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
+            if (lo_on) state_product<T, D, 2>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
+            else state_product<T, D, 2, 1>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
+            if constexpr (CAUSAL) {
+                if (lo_on) chunk_products_lower<T, D, 2, PP>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
+                else chunk_products_lower<T, D, 2, 1>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
+            }
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
@@ -965,9 +983,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
             z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
-        if (need_R)
-            outer_update<T, D, (sizeof(T) == 4 && D == 64) ? 4 : 2, 1, PP>(accR, QTt, 0, OHt, TSZ, w,
-                                                                           c, ql, wo);
+        if (need_R) {
+            constexpr int GRP = (sizeof(T) == 4 && D == 64) ? 4 : 2;
+            if (lo_on) outer_update<T, D, GRP, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
+            else outer_update<T, D, GRP, 1, 1>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
+        }
         par ^= 1;
         post_factors(c0 + C, par);
     }
@@ -1002,7 +1022,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
-    size_t slot_floats, float a, float b)
+    size_t slot_floats, float a, float b, int lo_rows)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1088,6 +1108,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     for (long ci = nchunks - 1; ci >= 0; --ci) {
         const long c0 = row0 + ci * C;
         const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
+        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of weights and OmegaHat
         __syncthreads();
         if (h0) {
             s1.store_rows(Ks);
@@ -1099,7 +1120,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
             s1.store_rows(Vs);
             if constexpr (CAUSAL) {
                 s2.store_rows(dOs);
-                s2.store_cols_scaled(OHt, TSZ, *reinterpret_cast<const f4v *>(rs + 4 * rq));
+                s2.store_cols_scaled(OHt, TSZ, *reinterpret_cast<const f4v *>(rs + 4 * rq), lo_on);
             }
         }
         __syncthreads();
@@ -1129,13 +1150,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                         vc[e] = off ? 0.f : r4[e] * (pc.get(e) - d4[e]);
                         vw[e] = off ? 0.f : a + b * pw.get(e);
                     }
-                    store_weight_block<T, D>(CmT, PSZ, nb * 16, ib * 16, c, g, vc);
-                    store_weight_block<T, D>(WT, PSZ, nb * 16, ib * 16, c, g, vw);
+                    store_weight_block<T, D>(CmT, PSZ, nb * 16, ib * 16, c, g, vc, lo_on);
+                    store_weight_block<T, D>(WT, PSZ, nb * 16, ib * 16, c, g, vw, lo_on);
                     if (KT > 16 && nb == ib && nb % 2 == 1) {
                         // the first k-tile of the products below starts one block earlier: zeros
                         const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-                        store_weight_block<T, D>(CmT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero);
-                        store_weight_block<T, D>(WT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero);
+                        store_weight_block<T, D>(CmT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero, lo_on);
+                        store_weight_block<T, D>(WT, PSZ, nb * 16, (ib - 1) * 16, c, g, zero, lo_on);
                     }
                 }
             }
@@ -1144,7 +1165,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 const int r = 64 * part + l;
                 if (VJ::mine(0, part, w)) {
                     float s = tile_row_sum<T, D>(OHt, r);
-                    if constexpr (PP == 2) s += tile_row_sum<T, D>(OHt + TSZ, r);
+                    if constexpr (PP == 2) {
+                        if (lo_on) s += tile_row_sum<T, D>(OHt + TSZ, r);
+                    }
                     csw[r] = s;
                 }
                 if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
@@ -1161,13 +1184,19 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 Blk ak[NPB];
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) ak[m].zero();
-                state_product<T, D, NPB>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+                if (lo_on) state_product<T, D, NPB>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+                else state_product<T, D, NPB, 1>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
-                    if constexpr (CAUSAL)
-                        chunk_product<T, D, 1, PP>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
-                                                   (nb * 16) / KT, C / KT, c, g, wo);
+                    if constexpr (CAUSAL) {
+                        if (lo_on)
+                            chunk_product<T, D, 1, PP>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
+                                                       (nb * 16) / KT, C / KT, c, g, wo);
+                        else
+                            chunk_product<T, D, 1, 1>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
+                                                      (nb * 16) / KT, C / KT, c, g, wo);
+                    }
                     store_block<T>(dKp + (size_t)(c0 + nb * 16) * D, D, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
                                    b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
@@ -1178,17 +1207,23 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 Blk av[NPB];
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) av[m].zero();
-                state_product<T, D, NPB>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+                if (lo_on) state_product<T, D, NPB>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+                else state_product<T, D, NPB, 1>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
                     if constexpr (CAUSAL) {
                         // both operands are intermediates: hi (hi + lo), then lo hi
-                        chunk_product<T, D, 1, PP>(av[m], OHt, 0, w * 16, WT, PSZ, nb * 16,
-                                                   (nb * 16) / KT, C / KT, c, g, wo);
-                        if constexpr (PP == 2)
-                            chunk_product<T, D, 1, 1>(av[m], OHt + TSZ, 0, w * 16, WT, 0, nb * 16,
+                        if (lo_on) {
+                            chunk_product<T, D, 1, PP>(av[m], OHt, 0, w * 16, WT, PSZ, nb * 16,
+                                                       (nb * 16) / KT, C / KT, c, g, wo);
+                            if constexpr (PP == 2)
+                                chunk_product<T, D, 1, 1>(av[m], OHt + TSZ, 0, w * 16, WT, 0,
+                                                          nb * 16, (nb * 16) / KT, C / KT, c, g, wo);
+                        } else {
+                            chunk_product<T, D, 1, 1>(av[m], OHt, 0, w * 16, WT, PSZ, nb * 16,
                                                       (nb * 16) / KT, C / KT, c, g, wo);
+                        }
                     }
                     store_block<T>(dVp + (size_t)(c0 + nb * 16) * D, D, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
@@ -1197,14 +1232,29 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
             }
         }
         if constexpr (CAUSAL) {
-            outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
-            outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
+            if (lo_on) {
+                outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
+                outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
+            } else {
+                outer_update<T, D, 2, 1, 1>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
+                outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
+            }
             u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
             w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
         }
         par ^= 1;
         post_factors(ci > 0 ? c0 - C : c0, par);
     }
+}
+
+// Rows [0, lo_rows) of every sequence carry a second bf16 plane of the weight blocks and of
+// OmegaHat (see la_mma.h): that is where a row's sums are short, so that the rounding of
+// single weights does not average out, while the tensor-wide error allowance is set by
+// exactly those rows.  Beyond, one plane is below the rounding of the bf16 outputs themselves.
+inline int lo_rows(int N)
+{
+    const int r = N / LA_LO_ROWS_DIV;
+    return r < 128 ? 128 : r;
 }
 
 inline la_status launch_status()
@@ -1233,11 +1283,11 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_fwd_apply<T, D, true><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b);
+            pr.b, lo_rows(pr.N));
     else
         kf_fwd_apply<T, D, false><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b);
+            pr.b, lo_rows(pr.N));
     tc.mark("fwd_apply");
     return launch_status();
 }
@@ -1271,11 +1321,13 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                       sinit_floats, dprime, pr.N, nseg,
-                                                      pl.seg_len, pl.slot_floats, pr.b);
+                                                      pl.seg_len, pl.slot_floats, pr.b,
+                                                      lo_rows(pr.N));
     else
         kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                        sinit_floats, dprime, pr.N, nseg,
-                                                       pl.seg_len, pl.slot_floats, pr.b);
+                                                       pl.seg_len, pl.slot_floats, pr.b,
+                                                       lo_rows(pr.N));
     tc.mark("bwd_dq");
     // reverse-running sums left by the ascending sweep
     if (pr.causal) {
@@ -1286,14 +1338,14 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
         }
         kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                        nseg, pl.seg_len, pl.slot_floats, pr.a,
-                                                       pr.b);
+                                                       pr.b, lo_rows(pr.N));
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
         kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                         nseg, pl.seg_len, pl.slot_floats, pr.a,
-                                                        pr.b);
+                                                        pr.b, lo_rows(pr.N));
     }
     tc.mark("bwd_dkv");
     return launch_status();
