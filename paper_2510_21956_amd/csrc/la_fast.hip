@@ -20,6 +20,10 @@
 #include "la_common.h"
 #include "la_mma.h"
 
+#ifndef LA_SP_DEPTH
+#define LA_SP_DEPTH 1
+#endif
+
 namespace la {
 namespace {
 
@@ -155,15 +159,12 @@ struct Stager {
         for (int e = 0; e < F::EPV; ++e) {
             const float x0 = s[0] * elem(raw[0], e), x1 = s[1] * elem(raw[1], e),
                         x2 = s[2] * elem(raw[2], e), x3 = s[3] * elem(raw[3], e);
-            V4 v = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2), from_float<T>(x3)};
+            const f4v x = {x0, x1, x2, x3};
+            const V4 v = pack4(x, T());
             T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * (rq ^ F::swz(dg * F::EPV + e));
             *reinterpret_cast<V4 *>(dst) = v;
             if constexpr (Mma<T, F::BS>::PLANES == 2) {
-                if (lo_on) {
-                    V4 vl = {from_float<T>(x0 - to_float(v[0])), from_float<T>(x1 - to_float(v[1])),
-                             from_float<T>(x2 - to_float(v[2])), from_float<T>(x3 - to_float(v[3]))};
-                    *reinterpret_cast<V4 *>(dst + plane) = vl;
-                }
+                if (lo_on) *reinterpret_cast<V4 *>(dst + plane) = pack4(x - unpack4(v), T());
             }
         }
     }
@@ -176,46 +177,6 @@ __device__ __forceinline__ float load_row_float(const float *x, long c0, int N, 
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(x + c0), 0, (int)(rows * sizeof(float)), kBufferFlags);
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, 4 * r, 0, 0));
-}
-
-// Sum of the C entries of row `r` of a transposed tile.
-template <typename T, int D>
-__device__ __forceinline__ float tile_row_sum(const T *tr, int r)
-{
-    typedef FC<T, D> F;
-    typedef typename Vec4<T>::type V4;
-    float s = 0.f;
-#pragma unroll
-    for (int n = 0; n < F::C; n += 4) {
-        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
-        s += (to_float(v[0]) + to_float(v[1])) + (to_float(v[2]) + to_float(v[3]));
-    }
-    return s;
-}
-
-// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.  The row's
-// swizzle is made opaque to the compiler first: otherwise each step's un-swizzled weight
-// address sits in a register of its own for the whole kernel.
-template <typename T, int D>
-__device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *wgt)
-{
-    typedef FC<T, D> F;
-    typedef typename Vec4<T>::type V4;
-    float s0 = 0.f, s1 = 0.f;
-    int sw = F::swz(r);
-    asm volatile("" : "+v"(sw));
-#pragma unroll
-    for (int m = 0; m < F::C / 4; m += 2) {
-        V4 v0 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m);
-        V4 v1 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m + 4);
-        f4v x0 = *reinterpret_cast<const f4v *>(wgt + 4 * (m ^ sw));
-        f4v x1 = *reinterpret_cast<const f4v *>(wgt + 4 * ((m + 1) ^ sw));
-        s0 += (to_float(v0[0]) * x0[0] + to_float(v0[1]) * x0[1]) +
-              (to_float(v0[2]) * x0[2] + to_float(v0[3]) * x0[3]);
-        s1 += (to_float(v1[0]) * x1[0] + to_float(v1[1]) * x1[1]) +
-              (to_float(v1[2]) * x1[2] + to_float(v1[3]) * x1[3]);
-    }
-    return s0 + s1;
 }
 
 // Sum over each aligned group of WIDTH consecutive lanes, result in every lane of the
@@ -247,21 +208,6 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
     return x;
 }
 
-// The per-chunk vector sums (column sums of tiles and the like) are cut into jobs of 64
-// rows, one wave each.  The NPAIRS weight blocks of phase A are dealt round-robin from
-// wave 0, so the last waves carry one block less than the first; the jobs go to those,
-// from the last wave downwards.  Job (kind, part) covers rows [64 part, 64 part + 64) of
-// vector number `kind`.
-template <int NW, int D, int NPAIRS>
-struct VecJobs {
-    static constexpr int PER = D / 64;
-    static constexpr int LIGHT = (NPAIRS % NW) ? NW - NPAIRS % NW : NW;  // waves with fewer blocks
-    static __device__ __forceinline__ bool mine(int kind, int part, int w)
-    {
-        return w == NW - 1 - (kind * PER + part) % LIGHT;
-    }
-};
-
 // Fragment bundles of one pipeline step.
 template <typename M, int NX>
 struct XsY {
@@ -284,15 +230,34 @@ typedef Acc<16> Blk;  // 16 x 16 accumulator block: lane (c, g) holds rows 4g..4
 // This is the rank-C update of the 16 columns of a running state that wave w owns.
 // Either operand may be an intermediate split over NAP resp. NBP planes (plane strides
 // aps, bps); every fragment is read once and used for all the planes of the other side.
+//
+// The same fragments also give the chunk's vector sums on the matrix pipe, for one more
+// MFMA each and no further LDS traffic:
+//   sum_a (if given) += sum_n A[16w + i][n] wa[n],   sum_b (if given) += sum_n B[16w + i][n] wb[n]
+// with the weights wa, wb (C floats in LDS, `wplanes` bf16 planes of them) or all ones where
+// the pointer is null.  Lane (c, g) then holds rows 16w + 4g .. 4g + 3 in its four registers,
+// the same in every lane group column c.
+struct VecSums {
+    Blk *sum_a = nullptr, *sum_b = nullptr;
+    const float *wa = nullptr, *wb = nullptr;
+    int wplanes = 1;
+};
 template <typename T, int D, int GRP = 4, int NAP = 1, int NBP = 1>  // GRP row blocks per pass
 __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int aps, const T *bt,
-                                             int bps, int w, int c, const SwzLane &ql, SwzOff wo)
+                                             int bps, int w, int c, int g, const SwzLane &ql,
+                                             SwzOff wo, const VecSums sums = VecSums())
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDT = F::LDT, C = F::C;
     static_assert(NAP == 1 || NBP == 1, "products of two second planes are never needed");
     typedef XsYs<M, GRP * NAP, NBP> B;
+    // weight fragment of k-tile kt: the lane's contraction indices of that tile
+    auto weights = [&](const float *wgt, int kt) {
+        if (!wgt) return M::ones2();
+        return M::from_groups(*reinterpret_cast<const f4v *>(wgt + kt * KT + 4 * g),
+                              *reinterpret_cast<const f4v *>(wgt + kt * KT + KT / 2 + 4 * g));
+    };
     // An offset of zero the compiler cannot see through: the fragment addresses below are
     // then worked out here, a few integer adds, instead of each being kept in a register of
     // its own across the whole chunk loop.
@@ -316,7 +281,7 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
                                         F::swz((r0 + rb) * 16));
                 return b;
             },
-            [&](int, const B &b) {
+            [&](int kt, const B &b) {
 #pragma unroll
                 for (int rb = 0; rb < GRP; ++rb)
 #pragma unroll
@@ -324,16 +289,38 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
 #pragma unroll
                         for (int qb = 0; qb < NBP; ++qb)
                             M::mma(st[r0 + rb], b.x[rb * NAP + qa], b.y[qb]);
+                if (sums.sum_b && r0 == 0) {
+                    const typename M::Frag2 wf = weights(sums.wb, kt);
+#pragma unroll
+                    for (int qb = 0; qb < NBP; ++qb) {
+                        M::mma(*sums.sum_b, b.y[qb], wf.hi);
+                        if (M::PLANES == 2 && sums.wb && sums.wplanes == 2 && qb == 0)
+                            M::mma(*sums.sum_b, b.y[qb], M::lo_of(wf));
+                    }
+                }
+                if (sums.sum_a && w >= r0 && w < r0 + GRP) {
+                    const typename M::Frag2 wf = weights(sums.wa, kt);
+#pragma unroll
+                    for (int rb = 0; rb < GRP; ++rb)
+                        if (r0 + rb == w) {
+#pragma unroll
+                            for (int qa = 0; qa < NAP; ++qa) {
+                                M::mma(*sums.sum_a, b.x[rb * NAP + qa], wf.hi);
+                                if (M::PLANES == 2 && sums.wa && sums.wplanes == 2 && qa == 0)
+                                    M::mma(*sums.sum_a, b.x[rb * NAP + qa], M::lo_of(wf));
+                            }
+                        }
+                }
             });
     }
 }
 
-// acc[m][j][i] += scale * sum_k col[k][j] * ys[m*16 + i][k]:  rows j = the wave's state
+// acc[m][j][i] += sum_k col[k][j] * ys[m*16 + i][k]:  rows j = the wave's state
 // columns, columns i = rows of block m of the row-major tile `ys`, contraction over D.
 // col = the accumulator-resident state column.
-template <typename T, int D, int NM, int SP = Mma<T, 16>::PLANES>  // SP planes of the state
+template <typename T, int D, int NM, int SP = Mma<T, 16>::PLANES, int DEPTH = LA_SP_DEPTH>
 __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D / 16],
-                                              float scale, const T *ys, int c, int g)
+                                              const T *ys, int c, int g)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -341,7 +328,7 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
     typedef Ys<M, NM> B;
     int lane0 = c * LDR;  // opaque to the compiler, see outer_update
     asm volatile("" : "+v"(lane0));
-    pipeline<D / KT>(
+    pipeline<D / KT, DEPTH>(
         D / KT,
         [&](int kt) {
             B b;
@@ -350,11 +337,14 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
             return b;
         },
         [&](int kt, const B &b) {
-            const typename M::Frag2 fx = column_frag<T, 16, NRB>(col, kt, scale);
+            if constexpr (SP == 2) {
+                const typename M::Frag2 fx = column_frag<T, 16, NRB>(col, kt);
 #pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                if constexpr (SP == 2) M::mma2x(acc[m], fx, b.y[m]);
-                else M::mma(acc[m], fx.hi, b.y[m]);  // the unused second plane folds away
+                for (int m = 0; m < NM; ++m) M::mma2x(acc[m], fx, b.y[m]);
+            } else {
+                const typename M::Frag fx = column_frag_hi<T, 16, NRB>(col, kt);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) M::mma(acc[m], fx, b.y[m]);
             }
         });
 }
@@ -481,18 +471,12 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
 {
     typedef Mma<T, 16> M;
     typedef typename Vec4<T>::type V4;
-    float hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) M::split(vals[e], hi[e], lo[e]);
+    const f4v x = {vals[0], vals[1], vals[2], vals[3]};
     T *dst = tile + (col0 + c) * FC<T, D>::LDT + row0 + 4 * g;
-    V4 vh = {from_float<T>(hi[0]), from_float<T>(hi[1]), from_float<T>(hi[2]), from_float<T>(hi[3])};
+    const V4 vh = pack4(x, T());
     *reinterpret_cast<V4 *>(dst) = vh;
     if constexpr (M::PLANES == 2) {
-        if (lo_on) {
-            V4 vl = {from_float<T>(lo[0]), from_float<T>(lo[1]), from_float<T>(lo[2]),
-                     from_float<T>(lo[3])};
-            *reinterpret_cast<V4 *>(dst + plane) = vl;
-        }
+        if (lo_on) *reinterpret_cast<V4 *>(dst + plane) = pack4(x - unpack4(vh), T());
     }
 }
 
@@ -511,7 +495,7 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
         f4v v = {__shfl(x0, src), __shfl(x1, src), __shfl(x2, src), __shfl(x3, src)};
         if (row < rows_valid) *reinterpret_cast<f4v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
     } else {
-        bf4v p = {from_float<T>(x0), from_float<T>(x1), from_float<T>(x2), from_float<T>(x3)};
+        bf4v p = to_bf4(f4v{x0, x1, x2, x3});
         u2v u = *reinterpret_cast<u2v *>(&p);
         u2v v = {(unsigned)__shfl((int)u[0], src), (unsigned)__shfl((int)u[1], src)};
         if (row < rows_valid) *reinterpret_cast<u2v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
@@ -546,7 +530,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     Blk st[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) st[rb].zero();
-    float vec = 0.f;  // t < D: p[t];  D <= t < 2D: z[t-D]
+    Blk zacc, pacc;  // z[16w + 4g + e], p[16w + 4g + e] in register e of every lane column
+    zacc.zero();
+    pacc.zero();
+    VecSums vs;
+    if constexpr (TRANSPOSED) {
+        vs.sum_b = &zacc;  // B = K
+    } else {
+        vs.sum_a = &zacc;  // A = K
+        vs.sum_b = &pacc;  // B = V
+    }
 
     Stager<T, D> s1;  // half 0: K, half 1: V
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
@@ -557,23 +550,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
         __syncthreads();
         // next chunk, in flight during the products (after the last one: that one again)
         s1.load(h0 ? Kp : Vp, min(c0 + C, c_last), N);
-        if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
-        else outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, ql, wo);
-        if (t < D) {
-            if constexpr (!TRANSPOSED) vec += tile_row_sum<T, D>(VTt, t);
-        } else if (t < 2 * D) {
-            vec += tile_row_sum<T, D>(KTt, t - D);
-        }
+        if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, g, ql, wo, vs);
+        else outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
     }
     float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) slot[(rb * 16 + 4 * g + i) * D + w * 16 + c] = st[rb].get(i);
-    if (t < D) {
-        if constexpr (!TRANSPOSED) slot[D * D + D + t] = vec;  // p
-    } else if (t < 2 * D) {
-        slot[D * D + (t - D)] = vec;  // z
+    if (c == 0) {
+        *reinterpret_cast<f4v *>(slot + D * D + w * 16 + 4 * g) = zacc.v;
+        if constexpr (!TRANSPOSED) *reinterpret_cast<f4v *>(slot + D * D + D + w * 16 + 4 * g) = pacc.v;
     }
 }
 
@@ -593,13 +580,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     constexpr int C = F::C, NW = F::NW, NT = F::NT, NB = F::NB, NRB = F::NRB, KT = F::KT;
     constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;  // tiles only the masked path needs shrink to nothing
-    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
     __shared__ __align__(16) T Qs[C * LDR];
     __shared__ __align__(16) T Ks[TS * C * LDR + 4];
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
     __shared__ __align__(16) T VTt[TS * D * LDT + 4];
     __shared__ __align__(16) T Ps[TS * PP * PSZ + 4];  // weight blocks: hi plane (+ lo plane)
-    __shared__ __align__(16) float psum[NB][C], qzs[C], ginv[NW][C], zs[D], csv[D], csk[D];
+    __shared__ __align__(16) float psum[NB][C], qzs[C], ginv[NW][C], zs[D];
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -624,9 +610,19 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             st[rb].set(i, zero_init ? 0.f : slot[(rb * 16 + 4 * g + i) * D + w * 16 + c]);
-    f4v p4 = {0.f, 0.f, 0.f, 0.f};  // a * p[16w + 4g + 0..3]
-    if (!zero_init) p4 = a * *reinterpret_cast<const f4v *>(slot + D * D + D + w * 16 + 4 * g);
+    // p[16w + 4g + e] and z[16w + 4g + e], kept up by the rank-C update; z is also mirrored
+    // in LDS for the q.z of every row
+    Blk pacc, zacc;
+    pacc.zero();
+    zacc.zero();
+    if (!zero_init) {
+        pacc.v = *reinterpret_cast<const f4v *>(slot + D * D + D + w * 16 + 4 * g);
+        zacc.v = *reinterpret_cast<const f4v *>(slot + D * D + w * 16 + 4 * g);
+    }
     if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
+    VecSums vs;
+    vs.sum_a = &zacc;  // A = K
+    vs.sum_b = &pacc;  // B = V
     // Hand-over to the backward pass (if asked for): entry s = [S^T | z] summed over all
     // rows before segment s.  Without the mask every segment starts from the sums over the
     // whole sequence and segment 0 writes them to entry 0.
@@ -688,11 +684,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                     if (g == 0) psum[nb][ib * 16 + c] = rs;
                 }
             }
-#pragma unroll
-            for (int part = 0; part < VJ::PER; ++part) {
-                if (VJ::mine(0, part, w)) csv[64 * part + l] = tile_row_sum<T, D>(VTt, 64 * part + l);
-                if (VJ::mine(1, part, w)) csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
-            }
         }
         {
             typedef typename Vec4<T>::type V4;
@@ -729,8 +720,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             Blk facc[NB];  // rows j = 16w + 4g + e, columns i
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
-            if (lo_on) state_product<T, D, NB>(facc, st, b, Qs, c, g);
-            else state_product<T, D, NB, 1>(facc, st, b, Qs, c, g);
+            if (lo_on) state_product<T, D, NB>(facc, st, Qs, c, g);
+            else state_product<T, D, NB, 1>(facc, st, Qs, c, g);
+#pragma unroll
+            for (int ib = 0; ib < NB; ++ib) facc[ib].v *= b;  // b S^T Q^T, before the block products
             if (l < C) {
                 const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 ginv[w][l] = 1.f / gv;
@@ -744,6 +737,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             float gi[NB];
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib) gi[ib] = ginv[w][ib * 16 + c];
+            const f4v p4 = a * pacc.v;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib)
                 store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
@@ -753,9 +747,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                                (facc[ib].get(3) + p4[3]) * gi[ib]);
         }
         if constexpr (CAUSAL) {
-            outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, ql, wo);
-            p4 += a * *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
-            if (t >= D && t < 2 * D) zs[t - D] += csk[t - D];
+            outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
+            // every wave read zs before the barrier that followed phase A; the next read is
+            // behind the two barriers at the top of the next chunk
+            if (c == 0) *reinterpret_cast<f4v *>(zs + w * 16 + 4 * g) = zacc.v;
         }
     }
     // with the mask, the state this segment ends with is what the next one starts from
@@ -764,7 +759,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
             *reinterpret_cast<f4v *>(dst + (w * 16 + c) * D + rb * 16 + 4 * g) = st[rb].v;
-        if (t >= D && t < 2 * D) dst[D * D + t - D] = zs[t - D];  // written by this very thread
+        if (c == 0) *reinterpret_cast<f4v *>(dst + D * D + w * 16 + 4 * g) = zacc.v;
     }
 }
 
@@ -812,8 +807,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
     // 1/g of the chunk's rows (two buffers: the next chunk's are written while this one's
     // are still read), dprime, delta, sum k
-    __shared__ __align__(16) float rsb[2][C], dl[C], dls[C], csk[D];
-    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
+    __shared__ __align__(16) float rsb[2][C], dl[C], dls[C];
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -842,12 +836,22 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             st[jb].set(i, zero_init ? 0.f : slot[SL::ST + (jb * 16 + 4 * g + i) * D + w * 16 + c]);
-    f4v z4 = {0.f, 0.f, 0.f, 0.f};  // z[16w + 4g + 0..3]
-    if (!zero_init) z4 = *reinterpret_cast<const f4v *>(slot + SL::Z + w * 16 + 4 * g);
+    Blk zacc;  // z[16w + 4g + e], kept up by the rank-C update (B = K)
+    zacc.zero();
+    if (!zero_init) zacc.v = *reinterpret_cast<const f4v *>(slot + SL::Z + w * 16 + 4 * g);
     Blk accR[NRB];  // this segment's R: rows r, columns j = 16w + c
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) accR[rb].zero();
-    float vw = 0.f, vu = 0.f;  // on the waves that own those jobs: w[r], u[r]
+    // this segment's w[16w + 4g + e] = sum OmegaHat and u[16w + 4g + e] = sum delta q, formed
+    // with R (B = OmegaHat; A = Q weighted by delta)
+    Blk wacc, uacc;
+    wacc.zero();
+    uacc.zero();
+    VecSums vz, vr;
+    vz.sum_b = &zacc;
+    vr.sum_b = &wacc;
+    vr.sum_a = &uacc;
+    vr.wa = dls;
 
     // staging: half 0: dO (rows, scaled columns) and O (for dprime);
     //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
@@ -929,23 +933,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                     }
                 }
             }
-#pragma unroll
-            for (int part = 0; part < VJ::PER; ++part)
-                if (VJ::mine(0, part, w)) csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
-        }
-        if (need_R) {
-            // this chunk's share of w = sum OmegaHat and u = sum delta q
-#pragma unroll
-            for (int part = 0; part < VJ::PER; ++part) {
-                const int r = 64 * part + l;
-                if (VJ::mine(1, part, w)) {
-                    vw += tile_row_sum<T, D>(OHt, r);
-                    if constexpr (PP == 2) {
-                        if (lo_on) vw += tile_row_sum<T, D>(OHt + TSZ, r);
-                    }
-                }
-                if (VJ::mine(2, part, w)) vu += tile_row_dot<T, D>(QTt, r, dls);
-            }
         }
         if constexpr (CAUSAL) __syncthreads();
 
@@ -953,6 +940,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         // (two row blocks at a time: bounds the accumulators and fragments alive at once)
 #pragma unroll
         for (int i0 = 0; i0 < NB; i0 += 2) {
+            const f4v z4 = zacc.v;
             float sc[2], di[2];  // requested now, used in the epilogue
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
@@ -962,8 +950,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             Blk acc[2];
             acc[0].zero();
             acc[1].zero();
-            if (lo_on) state_product<T, D, 2>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
-            else state_product<T, D, 2, 1>(acc, st, 1.f, dOs + i0 * 16 * LDR, c, g);
+            if (lo_on) state_product<T, D, 2>(acc, st, dOs + i0 * 16 * LDR, c, g);
+            else state_product<T, D, 2, 1>(acc, st, dOs + i0 * 16 * LDR, c, g);
             if constexpr (CAUSAL) {
                 if (lo_on) chunk_products_lower<T, D, 2, PP>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
                 else chunk_products_lower<T, D, 2, 1>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
@@ -980,13 +968,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             }
         }
         if constexpr (CAUSAL) {
-            outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, ql, wo);
-            z4 += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
+            outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, g, ql, wo, vz);
         }
         if (need_R) {
             constexpr int GRP = (sizeof(T) == 4 && D == 64) ? 4 : 2;
-            if (lo_on) outer_update<T, D, GRP, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
-            else outer_update<T, D, GRP, 1, 1>(accR, QTt, 0, OHt, TSZ, w, c, ql, wo);
+            vr.wplanes = lo_on ? 2 : 1;
+            if (lo_on) outer_update<T, D, GRP, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vr);
+            else outer_update<T, D, GRP, 1, 1>(accR, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vr);
         }
         par ^= 1;
         post_factors(c0 + C, par);
@@ -1001,10 +989,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                 out[SL::R + r * D + j] = accR[rb].get(i);
                 out[SL::RT + j * D + r] = accR[rb].get(i);
             }
-#pragma unroll
-        for (int part = 0; part < VJ::PER; ++part) {
-            if (VJ::mine(1, part, w)) out[SL::W + 64 * part + l] = vw;
-            if (VJ::mine(2, part, w)) out[SL::U + 64 * part + l] = vu;
+        if (c == 0) {
+            *reinterpret_cast<f4v *>(out + SL::W + w * 16 + 4 * g) = wacc.v;
+            *reinterpret_cast<f4v *>(out + SL::U + w * 16 + 4 * g) = uacc.v;
         }
     }
 }
@@ -1034,13 +1021,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // plus a constant the instruction can carry, instead of one base register per array.
     constexpr int RM = C * LDR;  // elements of a row-major tile
     constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ);
-    __shared__ __align__(16) unsigned char lds[(6 * C + 2 * D) * 4 + NELEM * sizeof(T)];
+    __shared__ __align__(16) unsigned char lds[6 * C * 4 + NELEM * sizeof(T)];
     // 1/g, dprime, delta of the chunk's rows: two buffers of [3][C], the next chunk's being
     // written while this one's are still read
     float *fac = reinterpret_cast<float *>(lds);
-    float *csu = fac + 6 * C, *csw = csu + D;
-    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
-    T *CmT = reinterpret_cast<T *>(csw + D), *WT = CmT + TS * PP * PSZ;
+    T *CmT = reinterpret_cast<T *>(fac + 6 * C), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
 
@@ -1070,11 +1055,18 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
             Ra[rb].set(i, zero_init ? 0.f : slot[SL::R + row * D + col]);
             Rb[rb].set(i, zero_init ? 0.f : slot[SL::RT + row * D + col]);
         }
-    f4v u4 = {0.f, 0.f, 0.f, 0.f}, w4 = {0.f, 0.f, 0.f, 0.f};  // u[16w+4g+e], a * w[16w+4g+e]
+    // u[16w + 4g + e] = sum delta q and w[16w + 4g + e] = sum OmegaHat, kept up by the rank-C
+    // updates (B = Q weighted by delta; B = OmegaHat)
+    Blk uacc, wacc;
+    uacc.zero();
+    wacc.zero();
     if (!zero_init) {
-        u4 = *reinterpret_cast<const f4v *>(slot + SL::U + w * 16 + 4 * g);
-        w4 = a * *reinterpret_cast<const f4v *>(slot + SL::W + w * 16 + 4 * g);
+        uacc.v = *reinterpret_cast<const f4v *>(slot + SL::U + w * 16 + 4 * g);
+        wacc.v = *reinterpret_cast<const f4v *>(slot + SL::W + w * 16 + 4 * g);
     }
+    VecSums vw_, vu_;
+    vw_.sum_b = &wacc;
+    vu_.sum_b = &uacc;
 
     // staging: half 0: K (rows), Q (rows, columns); half 1: V (rows), dO (rows, scaled
     // columns) and the row factors; unmasked: K and V only
@@ -1160,20 +1152,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                     }
                 }
             }
-#pragma unroll
-            for (int part = 0; part < VJ::PER; ++part) {
-                const int r = 64 * part + l;
-                if (VJ::mine(0, part, w)) {
-                    float s = tile_row_sum<T, D>(OHt, r);
-                    if constexpr (PP == 2) {
-                        if (lo_on) s += tile_row_sum<T, D>(OHt + TSZ, r);
-                    }
-                    csw[r] = s;
-                }
-                if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
-            }
             __syncthreads();
         }
+        const f4v u4 = uacc.v, w4 = a * wacc.v;
 
         // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
         //      OmegaHat^T W; store ----
@@ -1184,8 +1165,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 Blk ak[NPB];
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) ak[m].zero();
-                if (lo_on) state_product<T, D, NPB>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
-                else state_product<T, D, NPB, 1>(ak, Rb, 1.f, Vs + n0 * 16 * LDR, c, g);
+                if (lo_on) state_product<T, D, NPB>(ak, Rb, Vs + n0 * 16 * LDR, c, g);
+                else state_product<T, D, NPB, 1>(ak, Rb, Vs + n0 * 16 * LDR, c, g);
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
@@ -1207,8 +1188,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 Blk av[NPB];
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) av[m].zero();
-                if (lo_on) state_product<T, D, NPB>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
-                else state_product<T, D, NPB, 1>(av, Ra, b, Ks + n0 * 16 * LDR, c, g);
+                if (lo_on) state_product<T, D, NPB>(av, Ra, Ks + n0 * 16 * LDR, c, g);
+                else state_product<T, D, NPB, 1>(av, Ra, Ks + n0 * 16 * LDR, c, g);
+#pragma unroll
+                for (int m = 0; m < NPB; ++m) av[m].v *= b;  // b K R, before the block products
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
@@ -1232,15 +1215,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
             }
         }
         if constexpr (CAUSAL) {
+            vu_.wb = dls;
+            vu_.wplanes = lo_on ? 2 : 1;
             if (lo_on) {
-                outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
-                outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
+                outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vw_);
+                outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
             } else {
-                outer_update<T, D, 2, 1, 1>(Ra, QTt, 0, OHt, TSZ, w, c, ql, wo);
-                outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, ql, wo);
+                outer_update<T, D, 2, 1, 1>(Ra, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vw_);
+                outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
             }
-            u4 += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
-            w4 += a * *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
         }
         par ^= 1;
         post_factors(ci > 0 ? c0 - C : c0, par);

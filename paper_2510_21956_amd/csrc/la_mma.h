@@ -33,6 +33,18 @@ typedef float f4v __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf4v __attribute__((ext_vector_type(4)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+typedef float f2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+
+// Four floats to four bf16 (round to nearest even) as two packed conversions: written on
+// pairs because only the two-element form is turned into one instruction per pair.
+__device__ __forceinline__ bf4v to_bf4(f4v x)
+{
+    const bf2v p = __builtin_convertvector((f2v{x[0], x[1]}), bf2v);
+    const bf2v q = __builtin_convertvector((f2v{x[2], x[3]}), bf2v);
+    return __builtin_shufflevector(p, q, 0, 1, 2, 3);
+}
+__device__ __forceinline__ f4v bf4_to_float(bf4v x) { return __builtin_convertvector(x, f4v); }
 
 // ---- accumulator blocks -----------------------------------------------------
 template <int BS>
@@ -119,6 +131,9 @@ struct Mma<float, BS> {
         return *reinterpret_cast<const f4v *>(p + o.lo);
     }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v) { return Frag2{g0}; }
+    static __device__ __forceinline__ Frag from_groups_hi(f4v g0, f4v) { return g0; }
+    static __device__ __forceinline__ Frag2 ones2() { return Frag2{f4v{1.f, 1.f, 1.f, 1.f}}; }
+    static __device__ __forceinline__ Frag lo_of(const Frag2 &f) { return f.hi; }  // never used
     static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
     {
 #pragma unroll
@@ -188,16 +203,29 @@ struct Mma<__bf16, BS> {
     }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v g1)
     {
+        const bf4v h0 = to_bf4(g0), h1 = to_bf4(g1);
+        const bf4v l0 = to_bf4(g0 - bf4_to_float(h0)), l1 = to_bf4(g1 - bf4_to_float(h1));
+        Frag2 r;
+        r.hi = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+        r.lo = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        return r;
+    }
+    // first plane only
+    static __device__ __forceinline__ Frag from_groups_hi(f4v g0, f4v g1)
+    {
+        return __builtin_shufflevector(to_bf4(g0), to_bf4(g1), 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    static __device__ __forceinline__ Frag2 ones2()
+    {
         Frag2 r;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            r.hi[e] = (__bf16)g0[e];
-            r.lo[e] = (__bf16)(g0[e] - (float)r.hi[e]);
-            r.hi[4 + e] = (__bf16)g1[e];
-            r.lo[4 + e] = (__bf16)(g1[e] - (float)r.hi[4 + e]);
+        for (int e = 0; e < 8; ++e) {
+            r.hi[e] = (__bf16)1.f;
+            r.lo[e] = (__bf16)0.f;
         }
         return r;
     }
+    static __device__ __forceinline__ Frag lo_of(const Frag2 &f) { return f.lo; }
     static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
     {
         if constexpr (BS == 32)
@@ -225,40 +253,60 @@ __device__ __forceinline__ f4v column_group(const Acc<BS> (&col)[NRB], int q)
     return col[q / Acc<BS>::GROUPS].group(q % Acc<BS>::GROUPS);
 }
 
-// Operand fragment for k-tile kt of a contraction over the rows of `col`, each
-// value multiplied by `scale` in fp32 first.
+// Operand fragment(s) for k-tile kt of a contraction over the rows of `col`: both planes,
+// or the first plane only.
 template <typename T, int BS, int NRB>
-__device__ __forceinline__ typename Mma<T, BS>::Frag2 column_frag(const Acc<BS> (&col)[NRB],
-                                                                   int kt, float scale)
+__device__ __forceinline__ typename Mma<T, BS>::Frag2 column_frag(const Acc<BS> (&col)[NRB], int kt)
 {
     typedef Mma<T, BS> M;
     if constexpr (M::GPT == 1)
-        return M::from_groups(column_group<BS, NRB>(col, kt) * scale, f4v{0.f, 0.f, 0.f, 0.f});
+        return M::from_groups(column_group<BS, NRB>(col, kt), f4v{0.f, 0.f, 0.f, 0.f});
     else
-        return M::from_groups(column_group<BS, NRB>(col, 2 * kt) * scale,
-                              column_group<BS, NRB>(col, 2 * kt + 1) * scale);
+        return M::from_groups(column_group<BS, NRB>(col, 2 * kt),
+                              column_group<BS, NRB>(col, 2 * kt + 1));
+}
+template <typename T, int BS, int NRB>
+__device__ __forceinline__ typename Mma<T, BS>::Frag column_frag_hi(const Acc<BS> (&col)[NRB],
+                                                                     int kt)
+{
+    typedef Mma<T, BS> M;
+    if constexpr (M::GPT == 1)
+        return M::from_groups_hi(column_group<BS, NRB>(col, kt), f4v{0.f, 0.f, 0.f, 0.f});
+    else
+        return M::from_groups_hi(column_group<BS, NRB>(col, 2 * kt),
+                                 column_group<BS, NRB>(col, 2 * kt + 1));
 }
 
-// Software pipeline over the k-tiles of a product: the fragments of step s+1 are
+// Software pipeline over the k-tiles of a product: the fragments of step s+DEPTH are
 // requested from LDS before the MFMAs of step s are issued, so that the LDS
 // latency is covered by matrix work instead of stalling it.
 //   load(s)        -> a bundle of fragments for step s
 //   compute(s, b)  -> the MFMAs of step s on bundle b
-template <int MAXSTEPS, typename LoadFn, typename ComputeFn>
+template <int MAXSTEPS, int DEPTH = 1, typename LoadFn, typename ComputeFn>
 __device__ __forceinline__ void pipeline(int steps, LoadFn load, ComputeFn compute)
 {
     if (steps <= 0) return;
+    static_assert(DEPTH == 1 || DEPTH == 2, "one or two steps ahead");
     auto cur = load(0);
+    decltype(cur) nxt = cur;
+    if constexpr (DEPTH == 2) {
+        if (steps > 1) nxt = load(1);
+    }
 #pragma unroll
     for (int s = 0; s < MAXSTEPS; ++s) {
         if (s < steps) {
-            decltype(cur) nxt = cur;
-            if (s + 1 < steps) nxt = load(s + 1);
-            // keep the order written here: next step's LDS reads, then this step's MFMAs
+            decltype(cur) ahead = nxt;
+            if (s + DEPTH < steps) ahead = load(s + DEPTH);
+            // keep the order written here: the LDS reads of a later step, then this step's MFMAs
             __builtin_amdgcn_sched_barrier(0);
             compute(s, cur);
             __builtin_amdgcn_sched_barrier(0);
-            cur = nxt;
+            if constexpr (DEPTH == 2) {
+                cur = nxt;
+                nxt = ahead;
+            } else {
+                cur = ahead;
+            }
         }
     }
 }
@@ -274,6 +322,11 @@ __device__ __forceinline__ T from_float(float x)
 
 template <typename T>
 struct Vec4;
+// four floats rounded to the element type at once
+__device__ __forceinline__ f4v pack4(f4v x, float) { return x; }
+__device__ __forceinline__ bf4v pack4(f4v x, __bf16) { return to_bf4(x); }
+__device__ __forceinline__ f4v unpack4(f4v x) { return x; }
+__device__ __forceinline__ f4v unpack4(bf4v x) { return bf4_to_float(x); }
 template <>
 struct Vec4<float> {
     typedef f4v type;
