@@ -45,19 +45,54 @@ struct FC {
     static constexpr int NB = C / BS;    // row blocks per chunk
     static constexpr int NRB = D / BS;   // row blocks of a state column
     static constexpr int KT = Mma<T, BS>::KT;
-    static constexpr int LDR = D + 4;  // row-major tile  [C][LDR]
-    static constexpr int LDT = C + 4;  // transposed tile [D][LDT]
+    static constexpr bool B16 = sizeof(T) == 2;
+    static constexpr bool MS = B16;  // chunk vector sums on the matrix pipe (else vector ALU)
+    // Row strides keep every MFMA fragment one aligned 16-byte LDS read (a pair of 8-byte
+    // reads moves the same bytes at less than half the rate) and spread the 16 rows of a
+    // fragment over the banks.
+    static constexpr int LDR = D + (B16 ? 8 : 4);  // row-major tile  [C][LDR]
+    static constexpr int LDT = C + (B16 ? 8 : 4);  // transposed tile [D][LDT]
     static constexpr int EPV = 16 / sizeof(T);  // elements per 16-byte unit
     static constexpr int GPR = D / EPV;         // 16-byte units per row
     static constexpr int HT = NT / 2;           // threads per staging half
+    // bf16 tiles store the contraction index permuted inside every k-tile of 32: index
+    // 16h + 4g + e sits at position 8g + 4h + e, so that the eight values lane group g
+    // supplies to one MFMA (4g..4g+3 and 16+4g..16+4g+3, the order that lets accumulator
+    // blocks be fed back as operands) are contiguous.  In units of 4-element groups: group
+    // q (8 per k-tile) sits at offset grp_pos(q).
+    static __device__ __forceinline__ int grp_pos(int q)
+    {
+        if constexpr (!B16) return 4 * q;
+        else return 32 * (q / 8) + 8 * (q % 4) + 4 * ((q % 8) / 4);
+    }
     // Transposed tiles are written by lanes whose rows are 2*EPV... apart: EPV rows per
     // 16-byte unit of a lane, neighbouring lanes EPV rows on.  With any row padding that
-    // keeps vector alignment those rows collide in the LDS banks, so the 4-element column
-    // groups of row d are stored XOR-swizzled by swz(d); readers apply the same swizzle.
-    static constexpr int SWM = C / 8;  // swizzle values: 0 .. SWM-1 (= k-tile width in groups)
+    // keeps vector alignment those rows collide in the LDS banks, so the 16-byte units of
+    // row d (fp32: 4-element column groups; bf16: the 8-element units above, over the whole
+    // row) are stored XOR-swizzled by swz(d); readers apply the same swizzle.
+    static constexpr int SWM = C / 8;  // swizzle values: 0 .. SWM-1
     static __device__ __forceinline__ int swz(int d) { return (d / (2 * EPV)) % SWM; }
     // For row d = r0 + c with r0 a multiple of 16 and c < 16: swz(d) = swz(r0) ^ swz(c).
     static_assert(16 % (2 * EPV) == 0, "a 16-row block covers whole swizzle steps");
+    // Offset inside row d of a transposed tile of the 4-element group of chunk rows 4q .. 4q+3.
+    static __device__ __forceinline__ int tr_pos(int q, int d)
+    {
+        if constexpr (!B16) {
+            return 4 * (q ^ swz(d));
+        } else {
+            const int unit = (4 * (q / 8) + q % 4) ^ swz(d);  // 16-byte unit: k-tile and lane group
+            return 8 * unit + 4 * ((q % 8) / 4);
+        }
+    }
+    // Chunk-row quad (rows 4q .. 4q+3) staged by thread th of a half.  For bf16 two threads
+    // next to each other in this order take quads whose groups fall into the two halves of
+    // one 16-byte unit, which keeps the 8-byte transposed stores of a wave on distinct banks.
+    static __device__ __forceinline__ int row_quad(int th)
+    {
+        const int r = th / GPR;
+        if constexpr (!B16) return r;
+        else return (r & ~7) | ((r & 1) << 2) | ((r >> 1) & 3);
+    }
     static_assert(HT / GPR == C / 4, "each half of the workgroup stages one C x D tile");
     static_assert(D % KT == 0 && C % KT == 0, "tile sizes");
     static_assert(NT >= 2 * D, "vector sums use threads [0, 2D)");
@@ -67,7 +102,7 @@ struct FC {
 // Staging: C rows x D of one tensor, global -> registers -> LDS, by one half of
 // the workgroup (the other half stages another tensor at the same time).
 // Thread th of the half handles 16-byte column unit dg = th % GPR of rows
-// 4*rq .. 4*rq+3, rq = th / GPR, so that it can write the transposed tile with
+// 4*rq .. 4*rq+3, rq = row_quad(th), so that it can write the transposed tile with
 // 4-element vectors along the row index.
 // ---------------------------------------------------------------------------
 template <typename T, int D>
@@ -88,7 +123,7 @@ struct Stager {
     // the same time, so no extra memory traffic.
     __device__ __forceinline__ void load(const T *X, long c0, int N)
     {
-        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
         const long rows = (N - c0 < C) ? N - c0 : C;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<T *>(X + (size_t)c0 * D), 0, (int)(rows * D * sizeof(T)), kBufferFlags);
@@ -112,15 +147,16 @@ struct Stager {
     // Row-major tile [C][LDR]: the units are copied as they are.
     __device__ __forceinline__ void store_rows(T *rm) const
     {
-        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             T *dst = rm + (4 * rq + i) * F::LDR + dg * F::EPV;
             if constexpr (sizeof(T) == 4) {
                 *reinterpret_cast<u4v *>(dst) = raw[i];
-            } else {  // rows of a bf16 tile are 8-byte aligned only
-                *reinterpret_cast<u2v *>(dst) = u2v{raw[i][0], raw[i][1]};
-                *reinterpret_cast<u2v *>(dst + 4) = u2v{raw[i][2], raw[i][3]};
+            } else {  // the two 4-element groups of the unit go to their permuted places
+                T *row = rm + (4 * rq + i) * F::LDR;
+                *reinterpret_cast<u2v *>(row + F::grp_pos(2 * dg)) = u2v{raw[i][0], raw[i][1]};
+                *reinterpret_cast<u2v *>(row + F::grp_pos(2 * dg + 1)) = u2v{raw[i][2], raw[i][3]};
             }
         }
     }
@@ -128,12 +164,12 @@ struct Stager {
     // Transposed tile [D][LDT], unscaled: pure data movement.
     __device__ __forceinline__ void store_cols(T *tr) const
     {
-        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 *reinterpret_cast<u4v *>(tr + (dg * 4 + e) * F::LDT +
-                                         4 * (rq ^ F::swz(dg * 4 + e))) =
+                                         F::tr_pos(rq, dg * 4 + e)) =
                     u4v{raw[0][e], raw[1][e], raw[2][e], raw[3][e]};
         } else {
 #pragma unroll
@@ -142,7 +178,7 @@ struct Stager {
                 const uint32_t r0 = raw[0][wd], r1 = raw[1][wd], r2 = raw[2][wd], r3 = raw[3][wd];
                 const u2v lo = {(r0 & 0xffffu) | (r1 << 16), (r2 & 0xffffu) | (r3 << 16)};
                 const u2v hi = {(r0 >> 16) | (r1 & 0xffff0000u), (r2 >> 16) | (r3 & 0xffff0000u)};
-                const int cg = 4 * (rq ^ F::swz(dg * 8));  // the same for all 8 rows of the unit
+                const int cg = F::tr_pos(rq, dg * 8);  // the same for all 8 rows of the unit
                 *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd) * F::LDT + cg) = lo;
                 *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd + 1) * F::LDT + cg) = hi;
             }
@@ -154,14 +190,14 @@ struct Stager {
     __device__ __forceinline__ void store_cols_scaled(T *tr, int plane, f4v s, bool lo_on) const
     {
         typedef typename Vec4<T>::type V4;
-        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = th / F::GPR;
+        const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
 #pragma unroll
         for (int e = 0; e < F::EPV; ++e) {
             const float x0 = s[0] * elem(raw[0], e), x1 = s[1] * elem(raw[1], e),
                         x2 = s[2] * elem(raw[2], e), x3 = s[3] * elem(raw[3], e);
             const f4v x = {x0, x1, x2, x3};
             const V4 v = pack4(x, T());
-            T *dst = tr + (dg * F::EPV + e) * F::LDT + 4 * (rq ^ F::swz(dg * F::EPV + e));
+            T *dst = tr + (dg * F::EPV + e) * F::LDT + F::tr_pos(rq, dg * F::EPV + e);
             *reinterpret_cast<V4 *>(dst) = v;
             if constexpr (Mma<T, F::BS>::PLANES == 2) {
                 if (lo_on) *reinterpret_cast<V4 *>(dst + plane) = pack4(x - unpack4(v), T());
@@ -177,6 +213,48 @@ __device__ __forceinline__ float load_row_float(const float *x, long c0, int N, 
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(x + c0), 0, (int)(rows * sizeof(float)), kBufferFlags);
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, 4 * r, 0, 0));
+}
+
+// fp32 forms the chunk's vector sums in the vector ALU (its matrix pipe is the scarce unit;
+// bf16 forms them there, see outer_update).
+// Sum of the C entries of row `r` of a transposed tile.
+template <typename T, int D>
+__device__ __forceinline__ float tile_row_sum(const T *tr, int r)
+{
+    typedef FC<T, D> F;
+    typedef typename Vec4<T>::type V4;
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < F::C; n += 4) {
+        V4 v = *reinterpret_cast<const V4 *>(tr + r * F::LDT + n);
+        s += (to_float(v[0]) + to_float(v[1])) + (to_float(v[2]) + to_float(v[3]));
+    }
+    return s;
+}
+
+// sum_n tr[r][n] * wgt[n] over the C entries of row r of a transposed tile.  The row's
+// swizzle is made opaque to the compiler first: otherwise each step's un-swizzled weight
+// address sits in a register of its own for the whole kernel.
+template <typename T, int D>
+__device__ __forceinline__ float tile_row_dot(const T *tr, int r, const float *wgt)
+{
+    typedef FC<T, D> F;
+    typedef typename Vec4<T>::type V4;
+    float s0 = 0.f, s1 = 0.f;
+    int sw = F::swz(r);
+    asm volatile("" : "+v"(sw));
+#pragma unroll
+    for (int m = 0; m < F::C / 4; m += 2) {
+        V4 v0 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m);
+        V4 v1 = *reinterpret_cast<const V4 *>(tr + r * F::LDT + 4 * m + 4);
+        f4v x0 = *reinterpret_cast<const f4v *>(wgt + 4 * (m ^ sw));
+        f4v x1 = *reinterpret_cast<const f4v *>(wgt + 4 * ((m + 1) ^ sw));
+        s0 += (to_float(v0[0]) * x0[0] + to_float(v0[1]) * x0[1]) +
+              (to_float(v0[2]) * x0[2] + to_float(v0[3]) * x0[3]);
+        s1 += (to_float(v1[0]) * x1[0] + to_float(v1[1]) * x1[1]) +
+              (to_float(v1[2]) * x1[2] + to_float(v1[3]) * x1[3]);
+    }
+    return s0 + s1;
 }
 
 // Sum over each aligned group of WIDTH consecutive lanes, result in every lane of the
@@ -207,6 +285,21 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
     x += __shfl_xor(x, 16);
     return x;
 }
+
+// The per-chunk vector sums (column sums of tiles and the like) are cut into jobs of 64
+// rows, one wave each.  The NPAIRS weight blocks of phase A are dealt round-robin from
+// wave 0, so the last waves carry one block less than the first; the jobs go to those,
+// from the last wave downwards.  Job (kind, part) covers rows [64 part, 64 part + 64) of
+// vector number `kind`.
+template <int NW, int D, int NPAIRS>
+struct VecJobs {
+    static constexpr int PER = D / 64;
+    static constexpr int LIGHT = (NPAIRS % NW) ? NW - NPAIRS % NW : NW;  // waves with fewer blocks
+    static __device__ __forceinline__ bool mine(int kind, int part, int w)
+    {
+        return w == NW - 1 - (kind * PER + part) % LIGHT;
+    }
+};
 
 // Fragment bundles of one pipeline step.
 template <typename M, int NX>
@@ -271,13 +364,13 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
                 B b;
 #pragma unroll
                 for (int q = 0; q < NBP; ++q)
-                    b.y[q] = M::load_off(bt + q * bps + w * 16 * LDT + lane0 + kt * KT, wo);
+                    b.y[q] = M::load_off(bt + q * bps + w * 16 * LDT + lane0, kt, wo);
 #pragma unroll
                 for (int rb = 0; rb < GRP; ++rb)
 #pragma unroll
                     for (int q = 0; q < NAP; ++q)
                         b.x[rb * NAP + q] =
-                            M::load_swz(at + q * aps + (r0 + rb) * 16 * LDT + lane0 + kt * KT, ql,
+                            M::load_swz(at + q * aps + (r0 + rb) * 16 * LDT + lane0, kt, ql,
                                         F::swz((r0 + rb) * 16));
                 return b;
             },
@@ -396,7 +489,7 @@ __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, in
             B b;
 #pragma unroll
             for (int p = 0; p < NXP; ++p)
-                b.x[p] = M::load_off(xt + p * xps + xr * LDT + lane0 + (kt0 + s) * KT, xo);
+                b.x[p] = M::load_off(xt + p * xps + xr * LDT + lane0, kt0 + s, xo);
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
                 b.y[p] = M::load(yt + p * yps + (yr + c) * LDT + (kt0 + s) * KT, g);
@@ -443,7 +536,7 @@ __device__ __forceinline__ void chunk_products_lower(Blk (&acc)[NBL], int ib0, c
             int m, kt;
             where(s, m, kt);
             B b;
-            b.x[0] = M::load_off(xt + xr * LDT + lane0 + kt * KT, xo);
+            b.x[0] = M::load_off(xt + xr * LDT + lane0, kt, xo);
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
                 b.y[p] = M::load(yt + p * yps + (ib0 + m) * 16 * LDT + lane0 + kt * KT, g);
@@ -472,7 +565,7 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
     typedef Mma<T, 16> M;
     typedef typename Vec4<T>::type V4;
     const f4v x = {vals[0], vals[1], vals[2], vals[3]};
-    T *dst = tile + (col0 + c) * FC<T, D>::LDT + row0 + 4 * g;
+    T *dst = tile + (col0 + c) * FC<T, D>::LDT + FC<T, D>::grp_pos(row0 / 4 + g);
     const V4 vh = pack4(x, T());
     *reinterpret_cast<V4 *>(dst) = vh;
     if constexpr (M::PLANES == 2) {
@@ -524,7 +617,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
     // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
-    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzLane ql = Mma<T, 16>::swz_lane(g, F::swz(c));
     const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     Blk st[NRB];
@@ -534,12 +627,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     zacc.zero();
     pacc.zero();
     VecSums vs;
-    if constexpr (TRANSPOSED) {
-        vs.sum_b = &zacc;  // B = K
-    } else {
-        vs.sum_a = &zacc;  // A = K
-        vs.sum_b = &pacc;  // B = V
+    if constexpr (F::MS) {
+        if constexpr (TRANSPOSED) {
+            vs.sum_b = &zacc;  // B = K
+        } else {
+            vs.sum_a = &zacc;  // A = K
+            vs.sum_b = &pacc;  // B = V
+        }
     }
+    float vec = 0.f;  // vector-ALU sums: t < D: p[t];  D <= t < 2D: z[t-D]
 
     Stager<T, D> s1;  // half 0: K, half 1: V
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
@@ -552,15 +648,29 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
         s1.load(h0 ? Kp : Vp, min(c0 + C, c_last), N);
         if constexpr (TRANSPOSED) outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, g, ql, wo, vs);
         else outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
+        if constexpr (!F::MS) {
+            if (t < D) {
+                if constexpr (!TRANSPOSED) vec += tile_row_sum<T, D>(VTt, t);
+            } else if (t < 2 * D) {
+                vec += tile_row_sum<T, D>(KTt, t - D);
+            }
+        }
     }
     float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) slot[(rb * 16 + 4 * g + i) * D + w * 16 + c] = st[rb].get(i);
-    if (c == 0) {
-        *reinterpret_cast<f4v *>(slot + D * D + w * 16 + 4 * g) = zacc.v;
-        if constexpr (!TRANSPOSED) *reinterpret_cast<f4v *>(slot + D * D + D + w * 16 + 4 * g) = pacc.v;
+    if constexpr (F::MS) {
+        if (c == 0) {
+            *reinterpret_cast<f4v *>(slot + D * D + w * 16 + 4 * g) = zacc.v;
+            if constexpr (!TRANSPOSED)
+                *reinterpret_cast<f4v *>(slot + D * D + D + w * 16 + 4 * g) = pacc.v;
+        }
+    } else if (t < D) {
+        if constexpr (!TRANSPOSED) slot[D * D + D + t] = vec;  // p
+    } else if (t < 2 * D) {
+        slot[D * D + (t - D)] = vec;  // z
     }
 }
 
@@ -585,7 +695,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     __shared__ __align__(16) T KTt[TS * D * LDT + 4];
     __shared__ __align__(16) T VTt[TS * D * LDT + 4];
     __shared__ __align__(16) T Ps[TS * PP * PSZ + 4];  // weight blocks: hi plane (+ lo plane)
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
     __shared__ __align__(16) float psum[NB][C], qzs[C], ginv[NW][C], zs[D];
+    __shared__ __align__(16) float csv[F::MS ? 4 : D], csk[F::MS ? 4 : D];  // vector-ALU sums
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -598,7 +710,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
     // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
-    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzLane ql = Mma<T, 16>::swz_lane(g, F::swz(c));
     const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     // initial state from the scanned slot: S[r][j], j = 16w + c
@@ -619,10 +731,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
         pacc.v = *reinterpret_cast<const f4v *>(slot + D * D + D + w * 16 + 4 * g);
         zacc.v = *reinterpret_cast<const f4v *>(slot + D * D + w * 16 + 4 * g);
     }
-    if (t < D) zs[t] = zero_init ? 0.f : slot[D * D + t];
+    // zs follows the column order of the tile rows it is multiplied with
+    if (t < D) zs[F::grp_pos(t / 4) + t % 4] = zero_init ? 0.f : slot[D * D + t];
     VecSums vs;
-    vs.sum_a = &zacc;  // A = K
-    vs.sum_b = &pacc;  // B = V
+    if constexpr (F::MS) {
+        vs.sum_a = &zacc;  // A = K
+        vs.sum_b = &pacc;  // B = V
+    }
     // Hand-over to the backward pass (if asked for): entry s = [S^T | z] summed over all
     // rows before segment s.  Without the mask every segment starts from the sums over the
     // whole sequence and segment 0 writes them to entry 0.
@@ -682,6 +797,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                     }
                     rs = reduce_lane_groups(rs);
                     if (g == 0) psum[nb][ib * 16 + c] = rs;
+                }
+            }
+            if constexpr (!F::MS) {
+#pragma unroll
+                for (int part = 0; part < VJ::PER; ++part) {
+                    if (VJ::mine(0, part, w))
+                        csv[64 * part + l] = tile_row_sum<T, D>(VTt, 64 * part + l);
+                    if (VJ::mine(1, part, w))
+                        csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
                 }
             }
         }
@@ -748,9 +872,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
+            if constexpr (!F::MS) {
+                pacc.v += *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
+                zacc.v += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
+            }
             // every wave read zs before the barrier that followed phase A; the next read is
             // behind the two barriers at the top of the next chunk
-            if (c == 0) *reinterpret_cast<f4v *>(zs + w * 16 + 4 * g) = zacc.v;
+            if (c == 0) *reinterpret_cast<f4v *>(zs + F::grp_pos(4 * w + g)) = zacc.v;
         }
     }
     // with the mask, the state this segment ends with is what the next one starts from
@@ -807,7 +935,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     __shared__ __align__(16) T Cms[TS * PP * PSZ + 4];
     // 1/g of the chunk's rows (two buffers: the next chunk's are written while this one's
     // are still read), dprime, delta, sum k
-    __shared__ __align__(16) float rsb[2][C], dl[C], dls[C];
+    __shared__ __align__(16) float rsb[2][C], dl[C], dls[C], csk[F::MS ? 4 : D];
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -821,9 +950,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
     // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
-    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzLane ql = Mma<T, 16>::swz_lane(g, F::swz(c));
     const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
-    const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
+    const int dg = (t % F::HT) % F::GPR, rq = F::row_quad(t % F::HT);  // staging unit and row quad
     const bool need_R = CAUSAL ? (seg > 0) : true;  // segment 0's sums start no one
 
     // start of the ascending sweep: [S^T | z] over all rows before this segment, from the
@@ -848,10 +977,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     wacc.zero();
     uacc.zero();
     VecSums vz, vr;
-    vz.sum_b = &zacc;
-    vr.sum_b = &wacc;
-    vr.sum_a = &uacc;
-    vr.wa = dls;
+    if constexpr (F::MS) {
+        vz.sum_b = &zacc;
+        vr.sum_b = &wacc;
+        vr.sum_a = &uacc;
+        vr.wa = dls;
+    }
+    float vw = 0.f, vu = 0.f;  // vector-ALU sums, on the waves that own those jobs: w[r], u[r]
 
     // staging: half 0: dO (rows, scaled columns) and O (for dprime);
     //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
@@ -933,6 +1065,23 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                     }
                 }
             }
+            if constexpr (!F::MS) {
+#pragma unroll
+                for (int part = 0; part < VJ::PER; ++part)
+                    if (VJ::mine(0, part, w))
+                        csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
+            }
+        }
+        if constexpr (!F::MS) {
+            if (need_R) {
+                // this chunk's share of w = sum OmegaHat and u = sum delta q
+#pragma unroll
+                for (int part = 0; part < VJ::PER; ++part) {
+                    const int r = 64 * part + l;
+                    if (VJ::mine(1, part, w)) vw += tile_row_sum<T, D>(OHt, r);
+                    if (VJ::mine(2, part, w)) vu += tile_row_dot<T, D>(QTt, r, dls);
+                }
+            }
         }
         if constexpr (CAUSAL) __syncthreads();
 
@@ -969,6 +1118,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, g, ql, wo, vz);
+            if constexpr (!F::MS) zacc.v += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
         if (need_R) {
             constexpr int GRP = (sizeof(T) == 4 && D == 64) ? 4 : 2;
@@ -989,9 +1139,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                 out[SL::R + r * D + j] = accR[rb].get(i);
                 out[SL::RT + j * D + r] = accR[rb].get(i);
             }
-        if (c == 0) {
-            *reinterpret_cast<f4v *>(out + SL::W + w * 16 + 4 * g) = wacc.v;
-            *reinterpret_cast<f4v *>(out + SL::U + w * 16 + 4 * g) = uacc.v;
+        if constexpr (F::MS) {
+            if (c == 0) {
+                *reinterpret_cast<f4v *>(out + SL::W + w * 16 + 4 * g) = wacc.v;
+                *reinterpret_cast<f4v *>(out + SL::U + w * 16 + 4 * g) = uacc.v;
+            }
+        } else {
+#pragma unroll
+            for (int part = 0; part < VJ::PER; ++part) {
+                if (VJ::mine(1, part, w)) out[SL::W + 64 * part + l] = vw;
+                if (VJ::mine(2, part, w)) out[SL::U + 64 * part + l] = vu;
+            }
         }
     }
 }
@@ -1021,11 +1179,14 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // plus a constant the instruction can carry, instead of one base register per array.
     constexpr int RM = C * LDR;  // elements of a row-major tile
     constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ);
-    __shared__ __align__(16) unsigned char lds[6 * C * 4 + NELEM * sizeof(T)];
+    constexpr int NCS = F::MS ? 0 : 2 * D;  // vector-ALU sums: u and w of the chunk
+    __shared__ __align__(16) unsigned char lds[(6 * C + NCS) * 4 + NELEM * sizeof(T)];
     // 1/g, dprime, delta of the chunk's rows: two buffers of [3][C], the next chunk's being
     // written while this one's are still read
     float *fac = reinterpret_cast<float *>(lds);
-    T *CmT = reinterpret_cast<T *>(fac + 6 * C), *WT = CmT + TS * PP * PSZ;
+    float *csu = fac + 6 * C, *csw = csu + NCS / 2;
+    typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
+    T *CmT = reinterpret_cast<T *>(fac + 6 * C + NCS), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
 
@@ -1040,7 +1201,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
     // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
-    const SwzLane ql = make_swz_lane(g, F::swz(c));
+    const SwzLane ql = Mma<T, 16>::swz_lane(g, F::swz(c));
     const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
 
     const bool zero_init = CAUSAL && seg == nseg - 1;
@@ -1065,13 +1226,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         wacc.v = *reinterpret_cast<const f4v *>(slot + SL::W + w * 16 + 4 * g);
     }
     VecSums vw_, vu_;
-    vw_.sum_b = &wacc;
-    vu_.sum_b = &uacc;
+    if constexpr (F::MS) {
+        vw_.sum_b = &wacc;
+        vu_.sum_b = &uacc;
+    }
 
     // staging: half 0: K (rows), Q (rows, columns); half 1: V (rows), dO (rows, scaled
     // columns) and the row factors; unmasked: K and V only
     const long nchunks = (row1 - row0 + C - 1) / C;
-    const int dg = (t % F::HT) % F::GPR, rq = (t % F::HT) / F::GPR;  // staging unit and row quad
+    const int dg = (t % F::HT) % F::GPR, rq = F::row_quad(t % F::HT);  // staging unit and row quad
     Stager<T, D> s1, s2;
     const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
     float g_next = 1.f, d_next = 0.f;  // g, dprime of row t % C of the chunk being fetched
@@ -1152,6 +1315,14 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                     }
                 }
             }
+            if constexpr (!F::MS) {
+#pragma unroll
+                for (int part = 0; part < VJ::PER; ++part) {
+                    const int r = 64 * part + l;
+                    if (VJ::mine(0, part, w)) csw[r] = tile_row_sum<T, D>(OHt, r);
+                    if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
+                }
+            }
             __syncthreads();
         }
         const f4v u4 = uacc.v, w4 = a * wacc.v;
@@ -1215,14 +1386,20 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
             }
         }
         if constexpr (CAUSAL) {
-            vu_.wb = dls;
-            vu_.wplanes = lo_on ? 2 : 1;
+            if constexpr (F::MS) {
+                vu_.wb = dls;
+                vu_.wplanes = lo_on ? 2 : 1;
+            }
             if (lo_on) {
                 outer_update<T, D, 2, 1, PP>(Ra, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vw_);
                 outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
             } else {
                 outer_update<T, D, 2, 1, 1>(Ra, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vw_);
                 outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
+            }
+            if constexpr (!F::MS) {
+                uacc.v += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
+                wacc.v += *reinterpret_cast<const f4v *>(csw + w * 16 + 4 * g);
             }
         }
         par ^= 1;

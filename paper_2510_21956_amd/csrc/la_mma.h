@@ -79,24 +79,17 @@ struct Acc<16> {
 };
 
 // ---- operand fragments and the MFMA itself ------------------------------------
-// Swizzled tiles: element offsets inside a k-tile.  SwzLane is the part of them that
-// depends on the lane, for the four possible low swizzle bits of a row block:
-// q[j] = 4 * (g ^ lane_swizzle ^ j).  With it a fragment address is one of four lane
-// registers plus a constant, whatever the row block.  SwzOff is a fully resolved row.
+// Swizzled tiles: element offsets inside a row.  SwzLane is the part of them that depends
+// on the lane, for the four possible low swizzle bits of a row block: q[j] = unit *
+// (g ^ lane_swizzle ^ j).  With it a fragment address is one of four lane registers plus a
+// constant, whatever the row block.  SwzOff is a fully resolved row (lo: offset of the
+// lane's unit; hi: whether the row's swizzle exchanges the two k-tiles, bf16 only).
 struct SwzLane {
     int q[4];
 };
 struct SwzOff {
     int lo, hi;
 };
-__device__ __forceinline__ SwzLane make_swz_lane(int g, int lane_sw)
-{
-    SwzLane r;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r.q[j] = 4 * (g ^ lane_sw ^ j);
-    return r;
-}
-
 template <typename T, int BS>
 struct Mma;
 
@@ -117,18 +110,27 @@ struct Mma<float, BS> {
     }
     // The same from a tile whose 4-element column groups are XOR-swizzled inside the
     // k-tile: `lane` holds the lane-dependent part, s0 < NG the row block's constant part.
-    static __device__ __forceinline__ Frag load_swz(const float *p, const SwzLane &lane, int s0)
+    // (p points at the row, kt is the k-tile)
+    static __device__ __forceinline__ Frag load_swz(const float *p, int kt, const SwzLane &lane,
+                                                    int s0)
     {
-        return *reinterpret_cast<const f4v *>(p + lane.q[s0 & 3]);
+        return *reinterpret_cast<const f4v *>(p + kt * KT + lane.q[s0 & 3]);
+    }
+    static __device__ __forceinline__ SwzLane swz_lane(int g, int lane_sw)
+    {
+        SwzLane r;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.q[j] = 4 * (g ^ lane_sw ^ j);
+        return r;
     }
     // Offsets of a row whose swizzle is only known at run time, worked out once.
     static __device__ __forceinline__ SwzOff swz_offsets(int g, int lane_sw, int s0)
     {
         return SwzOff{4 * (g ^ lane_sw ^ s0), 0};
     }
-    static __device__ __forceinline__ Frag load_off(const float *p, SwzOff o)
+    static __device__ __forceinline__ Frag load_off(const float *p, int kt, SwzOff o)
     {
-        return *reinterpret_cast<const f4v *>(p + o.lo);
+        return *reinterpret_cast<const f4v *>(p + kt * KT + o.lo);
     }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v) { return Frag2{g0}; }
     static __device__ __forceinline__ Frag from_groups_hi(f4v g0, f4v) { return g0; }
@@ -171,35 +173,35 @@ struct Mma<__bf16, BS> {
     struct Frag2 {
         Frag hi, lo;
     };
+    // Tiles hold the contraction index permuted inside each k-tile so that the lane's eight
+    // values (4g..4g+3 and 16+4g..16+4g+3) are one aligned 16-byte unit, number g.
     static __device__ __forceinline__ Frag load(const __bf16 *p, int g)
     {
-        bf4v lo = *reinterpret_cast<const bf4v *>(p + 4 * g);
-        bf4v hi = *reinterpret_cast<const bf4v *>(p + KT / 2 + 4 * g);
-        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        return r;
+        return *reinterpret_cast<const bf8v *>(p + 8 * g);
     }
-    // The same from a tile whose 4-element column groups are XOR-swizzled inside the
-    // k-tile (s0 < 2 * NG).  The two low bits of the swizzle act on the lane's group
-    // number, the third swaps the two halves of the k-tile, which is a constant offset.
-    static __device__ __forceinline__ Frag load_swz(const __bf16 *p, const SwzLane &lane, int s0)
+    // The same from a transposed tile whose 16-byte units are XOR-swizzled over the whole
+    // row (p points at the row, kt is the k-tile, s0 the row block's swizzle): the two low
+    // bits act on the lane group, the next one on the k-tile.
+    static __device__ __forceinline__ Frag load_swz(const __bf16 *p, int kt, const SwzLane &lane,
+                                                    int s0)
     {
-        const int q = lane.q[s0 & 3], up = (s0 & NG) ? 4 * NG : 0;
-        bf4v lo = *reinterpret_cast<const bf4v *>(p + q + up);
-        bf4v hi = *reinterpret_cast<const bf4v *>(p + q + (4 * NG - up));
-        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return *reinterpret_cast<const bf8v *>(p + KT * (kt ^ ((s0 >> 2) & 1)) + lane.q[s0 & 3]);
+    }
+    static __device__ __forceinline__ SwzLane swz_lane(int g, int lane_sw)
+    {
+        SwzLane r;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.q[j] = 8 * (g ^ lane_sw ^ j);
         return r;
     }
     static __device__ __forceinline__ SwzOff swz_offsets(int g, int lane_sw, int s0)
     {
         const int sw = lane_sw ^ s0;
-        return SwzOff{4 * (g ^ sw), 4 * ((g + NG) ^ sw)};
+        return SwzOff{8 * (g ^ (sw & 3)), (sw >> 2) & 1};
     }
-    static __device__ __forceinline__ Frag load_off(const __bf16 *p, SwzOff o)
+    static __device__ __forceinline__ Frag load_off(const __bf16 *p, int kt, SwzOff o)
     {
-        bf4v lo = *reinterpret_cast<const bf4v *>(p + o.lo);
-        bf4v hi = *reinterpret_cast<const bf4v *>(p + o.hi);
-        Frag r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        return r;
+        return *reinterpret_cast<const bf8v *>(p + KT * (kt ^ o.hi) + o.lo);
     }
     static __device__ __forceinline__ Frag2 from_groups(f4v g0, f4v g1)
     {
