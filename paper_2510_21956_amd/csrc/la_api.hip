@@ -43,6 +43,20 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     seg_len = (long)round_up((size_t)seg_len, 64);
     p.seg_len = (int)seg_len;
     p.nseg = (int)((N + seg_len - 1) / seg_len);
+    p.map = SegMap{p.seg_len, lo_rows_of(N), 0};
+    // bf16 with the mask on the matrix-core kernels: segments of equal cost instead of equal
+    // length (the plain-ALU kernels and the unmasked ones keep no second planes)
+    if (forced <= 0 && causal && dt == LA_BF16 && (D == 64 || D == 128) &&
+        !g_force_generic.load(std::memory_order_relaxed) && p.nseg > 1) {
+        const long total = (long)kLoCost * (p.map.lo_rows < N ? p.map.lo_rows : N) +
+                           (long)kHiCost * (N > p.map.lo_rows ? N - p.map.lo_rows : 0);
+        const long cost_seg = (total + p.nseg - 1) / p.nseg;
+        if (cost_seg / kLoCost >= 128) {  // every segment keeps at least two chunks
+            p.map.cost_seg = cost_seg;
+            // rounding may leave the last segment(s) empty: drop them
+            while (p.nseg > 1 && seg_row(p.map, p.nseg - 1, p.nseg, N) >= N) --p.nseg;
+        }
+    }
     const size_t DD = (size_t)D * D;
     p.slot_floats = round_up(is_backward ? 3 * DD + 3 * D : DD + 2 * D, 64);
     const size_t slots = (size_t)BH * p.nseg * p.slot_floats;

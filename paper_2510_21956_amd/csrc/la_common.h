@@ -42,9 +42,45 @@ __device__ __forceinline__ void store_elem(bf16_t *p, size_t i, float x) { p[i] 
 // the factors a, b); R = sum q OmegaHat^T, u = sum delta q, w = sum OmegaHat
 // are those of Eq. endd.  The backward workspace also holds delta_i =
 // o_i . OmegaHat_i, one float per row, after the slots.
+// Where the segments of a sequence begin.  Uniform: segment s starts at row s * seg_len.
+// Balanced (cost_seg > 0; bf16 matrix-core kernels with the mask): the first lo_rows rows of a
+// sequence carry second bf16 planes of the intermediates and cost kLoCost units a row against
+// kHiCost for the others; segments are cut at equal cost, cost_seg units each, rounded to a
+// multiple of 64 rows, so that the workgroups of a launch, one segment each, finish together.
+constexpr int kLoCost = 5, kHiCost = 4;
+struct SegMap {
+    int seg_len;
+    int lo_rows;
+    long cost_seg;
+};
+__host__ __device__ inline long seg_row(const SegMap &m, int s, int nseg, int N)
+{
+    if (s >= nseg) return N;
+    long r;
+    if (m.cost_seg == 0) {
+        r = (long)s * m.seg_len;
+    } else {
+        const long x = (long)s * m.cost_seg, xl = (long)kLoCost * m.lo_rows;
+        r = x <= xl ? x / kLoCost : m.lo_rows + (x - xl) / kHiCost;
+        r = (r + 32) / 64 * 64;
+    }
+    return r < N ? r : N;
+}
+// Rows [0, lo_rows) of every sequence carry a second bf16 plane of the weight blocks, of
+// OmegaHat and of the running states when they become MFMA operands: that is where a row's
+// sums are short, so that the rounding of single operands does not average out, while the
+// tensor-wide error allowance is set by exactly those rows.  Beyond, one plane is below the
+// rounding of the bf16 outputs themselves.
+inline int lo_rows_of(int N)
+{
+    const int r = N / 8;
+    return r < 128 ? 128 : r;
+}
+
 struct Plan {
     int nseg;
     int seg_len;
+    SegMap map;
     size_t slot_floats;
     size_t delta_offset_floats;  // backward only
     size_t total_bytes;

@@ -603,7 +603,7 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 template <typename T, int D, bool TRANSPOSED>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
-    int nseg_run, int seg_len, size_t slot_floats, int slot_shift)
+    int nseg_run, SegMap sm, size_t slot_floats, int slot_shift)
 {
     typedef FC<T, D> F;
     constexpr int C = F::C, NRB = F::NRB, LDT = F::LDT;
@@ -611,8 +611,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     __shared__ __align__(16) T VTt[D * LDT];
     const int bh = blockIdx.x / nseg_run, seg = blockIdx.x % nseg_run;
     const T *Kp = K + (size_t)bh * N * D, *Vp = V + (size_t)bh * N * D;
-    const long row0 = (long)seg * seg_len;
-    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
@@ -683,7 +682,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
-    int nseg, int seg_len, size_t slot_floats, size_t saved_floats, float a, float b, int lo_rows)
+    int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -704,8 +703,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base;
     T *Op = O + base;
     float *Gp = G + (size_t)bh * N;
-    const long row0 = (long)seg * seg_len;
-    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
@@ -757,7 +755,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     if constexpr (CAUSAL) s2.load(Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
-        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of the weights: early rows
+        const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of the weights: early rows
         if (h0) {
             s1.store_rows(Qs);
             if constexpr (CAUSAL) s2.store_cols(VTt);
@@ -918,8 +916,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
-    float *__restrict__ dprime, int N, int nseg, int seg_len, size_t slot_floats, float b,
-    int lo_rows)
+    float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -944,8 +941,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     T *dQp = dQ + base;
     const float *Gp = G + (size_t)bh * N;
     float *dp = dprime + (size_t)bh * N;
-    const long row0 = (long)seg * seg_len;
-    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
@@ -1007,7 +1003,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
         const float *rs = rsb[par];
-        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of weights and OmegaHat
+        const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
         if (h0) {
             const f4v r4 = *reinterpret_cast<const f4v *>(rs + 4 * rq);
             // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
@@ -1166,8 +1162,8 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
-    const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, int seg_len,
-    size_t slot_floats, float a, float b, int lo_rows)
+    const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, SegMap sm,
+    size_t slot_floats, float a, float b)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1195,8 +1191,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *dOp = dO + base;
     T *dKp = dK + base, *dVp = dV + base;
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
-    const long row0 = (long)seg * seg_len;
-    const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
+    const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
     const bool h0 = w < F::NW / 2;  // first or second staging half
@@ -1263,7 +1258,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     for (long ci = nchunks - 1; ci >= 0; --ci) {
         const long c0 = row0 + ci * C;
         const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
-        const bool lo_on = PP == 2 && c0 < lo_rows;  // second plane of weights and OmegaHat
+        const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
         __syncthreads();
         if (h0) {
             s1.store_rows(Ks);
@@ -1407,16 +1402,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     }
 }
 
-// Rows [0, lo_rows) of every sequence carry a second bf16 plane of the weight blocks and of
-// OmegaHat (see la_mma.h): that is where a row's sums are short, so that the rounding of
-// single weights does not average out, while the tensor-wide error allowance is set by
-// exactly those rows.  Beyond, one plane is below the rounding of the bf16 outputs themselves.
-inline int lo_rows(int N)
-{
-    const int r = N / LA_LO_ROWS_DIV;
-    return r < 128 ? 128 : r;
-}
-
 inline la_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
@@ -1434,7 +1419,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
         kf_kv_state<T, D, false><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
-            K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
+            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0);
         tc.mark("fwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, D * D + 2 * D, pr.causal ? 0 : 2,
                           pr.causal ? 1 : 0, nseg - 1, st);
@@ -1442,12 +1427,12 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     }
     if (pr.causal)
         kf_fwd_apply<T, D, true><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, lo_rows(pr.N));
+            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
+            pr.b);
     else
         kf_fwd_apply<T, D, false><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.seg_len, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, lo_rows(pr.N));
+            Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
+            pr.b);
     tc.mark("fwd_apply");
     return launch_status();
 }
@@ -1470,7 +1455,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (!saved && nrun > 0) {
         kf_kv_state<T, D, true><<<dim3(pr.BH * nrun), block, 0, st>>>(
-            K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
+            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0);
         tc.mark("bwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST,
                           pr.causal ? 0 : 2, pr.causal ? 1 : 0, nseg - 1, st);
@@ -1481,13 +1466,11 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                       sinit_floats, dprime, pr.N, nseg,
-                                                      pl.seg_len, pl.slot_floats, pr.b,
-                                                      lo_rows(pr.N));
+                                                      pl.map, pl.slot_floats, pr.b);
     else
         kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                        sinit_floats, dprime, pr.N, nseg,
-                                                       pl.seg_len, pl.slot_floats, pr.b,
-                                                       lo_rows(pr.N));
+                                                       pl.map, pl.slot_floats, pr.b);
     tc.mark("bwd_dq");
     // reverse-running sums left by the ascending sweep
     if (pr.causal) {
@@ -1497,15 +1480,15 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
             tc.mark("scan_slots_rev");
         }
         kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
-                                                       nseg, pl.seg_len, pl.slot_floats, pr.a,
-                                                       pr.b, lo_rows(pr.N));
+                                                       nseg, pl.map, pl.slot_floats, pr.a,
+                                                       pr.b);
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
         kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
-                                                        nseg, pl.seg_len, pl.slot_floats, pr.a,
-                                                        pr.b, lo_rows(pr.N));
+                                                        nseg, pl.map, pl.slot_floats, pr.a,
+                                                        pr.b);
     }
     tc.mark("bwd_dkv");
     return launch_status();

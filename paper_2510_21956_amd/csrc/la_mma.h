@@ -22,11 +22,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// The second weight plane is kept for the first N / LA_LO_ROWS_DIV rows of a sequence.
-#ifndef LA_LO_ROWS_DIV
-#define LA_LO_ROWS_DIV 8
-#endif
-
 namespace la {
 
 typedef float f4v __attribute__((ext_vector_type(4)));

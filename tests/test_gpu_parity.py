@@ -189,6 +189,21 @@ def test_full_configs(oracle_mod, la, knobs, index, slices):
     check_against_oracle(oracle_mod, la, dev, ref, slices, c.dtype, c.a, c.b, c.causal, c.name)
 
 
+@pytest.mark.parametrize("shape", [(1, 16, 5000, 128), (2, 16, 3333, 64)])
+def test_cost_balanced_segments(oracle_mod, la, knobs, shape):
+    """bf16 with the mask: the library cuts a sequence into segments of equal cost rather than
+    equal length (the first rows cost more).  Mid-sized shapes where that plan has many
+    segments, a sequence length that is no multiple of any tile, and the boundary between
+    the two kinds of rows inside a segment."""
+    knobs(0, 0)
+    B, H, N, D = shape
+    slices = [0, 7, B * H - 1]
+    tag = "balanced B%d H%d N%d D%d bf16" % shape
+    print("case", tag, flush=True)
+    dev, ref = upload_case(B, H, N, D, "bf16", 4100 + N, slices)
+    check_against_oracle(oracle_mod, la, dev, ref, slices, "bf16", 1.0, 0.5, True, tag)
+
+
 # The paper's own benchmark shapes (Sec. 5.1), the ones the oracle finishes in seconds on a
 # few sampled slices: the two shorter lengths of the D = 128 sweep (N = 10000 is not a
 # multiple of any tile size) and the three head sizes at N = 4096.
