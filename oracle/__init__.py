@@ -11,6 +11,8 @@ Functions (paper passages in the C file's comments):
   forward_def / forward_rec       -- O, G by the definition / by running sums
   backward_def / backward_rec     -- dQ, dK, dV by the definition / running sums
   forward_def_rows                -- definition at selected rows of one slice
+  decode                          -- incremental form with a carried state (App. B.1)
+  grad_ab_def                     -- dL/da, dL/db by the definition
 """
 import ctypes
 import hashlib
@@ -72,6 +74,10 @@ def _load():
                   lib.la_oracle_forward_def_rows, lib.la_oracle_backward_def,
                   lib.la_oracle_backward_rec):
             f.restype = None
+        lib.la_oracle_decode.argtypes = [dp, dp, dp, dp, dp, dp, L, L, I, F, F]
+        lib.la_oracle_decode.restype = None
+        lib.la_oracle_grad_ab_def.argtypes = [dp, dp, dp, dp, dp, L, L, I, F, F, I]
+        lib.la_oracle_grad_ab_def.restype = None
         lib.la_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -158,3 +164,35 @@ def backward_rec(Q, K, V, O, G, dO, a, b, causal):
                                        _p(dQ), _p(dK), _p(dV),
                                        BH, N, D, float(a), float(b), int(bool(causal)))
     return dQ, dK, dV
+
+
+def decode_state_floats(D):
+    """Doubles per slice of the carried state: [S (D*D) | z (D) | p (D) | count (1)]."""
+    return D * D + 2 * D + 1
+
+
+def decode(Q, K, V, state, a, b):
+    """Incremental form (App. B.1): T new rows per slice, [..., T, D], appended to the
+    prefix summarised by ``state`` ([..., decode_state_floats(D)], updated in place; zeros
+    for an empty prefix).  Returns (O, G) of the new rows."""
+    (Q, K, V), shape, BH, T, D = _prep(Q, K, V)
+    if state.dtype != np.float64 or not state.flags.c_contiguous:
+        raise ValueError("state must be a C-contiguous float64 array")
+    if state.size != BH * decode_state_floats(D):
+        raise ValueError("state has the wrong size")
+    O = np.empty(shape, dtype=np.float64)
+    G = np.empty(shape[:-1], dtype=np.float64)
+    if BH * T * D:
+        _load().la_oracle_decode(_p(Q), _p(K), _p(V), _p(O), _p(G), _p(state), BH, T, D,
+                                 float(a), float(b))
+    return O, G
+
+
+def grad_ab_def(Q, K, V, dO, a, b, causal):
+    """(dL/da, dL/db) of L = sum(O * dO) by the pairwise definition, over all slices."""
+    (Q, K, V, dO), shape, BH, N, D = _prep(Q, K, V, dO)
+    out = np.zeros(2, dtype=np.float64)
+    if BH * N * D:
+        _load().la_oracle_grad_ab_def(_p(Q), _p(K), _p(V), _p(dO), _p(out), BH, N, D,
+                                      float(a), float(b), int(bool(causal)))
+    return float(out[0]), float(out[1])

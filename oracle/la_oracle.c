@@ -288,3 +288,77 @@ void la_oracle_backward_rec(const double *Q, const double *K, const double *V,
         free(S);
     }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Incremental (decode) form: the recurrence of App. B.1 (Table 3, row 2)    */
+/* with the state carried by the caller.  state = [S (D*D) | z (D) | p (D) | */
+/* cnt (1)] per slice, the sums of Eq. xy over every row seen so far (zeros   */
+/* for an empty prefix).  Each of the T new rows is added to the state, then  */
+/* read out: o_t = (a p + b S^T q_t) / g_t, g_t = a cnt + b q_t.z (Eq. fglast,*/
+/* div).  Always causal: a new row sees the prefix and itself.                */
+/* ------------------------------------------------------------------------ */
+void la_oracle_decode(const double *Q, const double *K, const double *V,
+                      double *O, double *G, double *state,
+                      long BH, long T, int D, double a, double b)
+{
+    const size_t SF = (size_t)D * D + 2 * (size_t)D + 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * T * D, *k = K + bh * T * D, *v = V + bh * T * D;
+        double *o = O + bh * T * D, *g = G + bh * T;
+        double *S = state + (size_t)bh * SF, *z = S + (size_t)D * D, *p = z + D, *cnt = p + D;
+        for (long t = 0; t < T; ++t) {
+            state_add_row(S, z, p, k + t * D, v + t * D, D);
+            *cnt += 1.0;
+            readout_row(S, z, p, *cnt, q + t * D, o + t * D, g + t, D, a, b);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Gradients of L = sum_ij o_ij Omega_ij with respect to the kernel's own     */
+/* coefficients (Sec. 2.2 allows a, b to be learnable), by the definition:    */
+/* with w_in = a + b s_in, s_in = q_i.k_n, dw/da = 1 and dw/db = s_in, and    */
+/* dL/dw_in = OmegaHat_i . v_n - delta_i as above,                            */
+/*   dL/da = sum_{i, n in A(i)} (OmegaHat_i . v_n - delta_i)                  */
+/*   dL/db = sum_{i, n in A(i)} (OmegaHat_i . v_n - delta_i) s_in             */
+/* dab[0] = dL/da, dab[1] = dL/db, summed over all slices.  O(N^2 D).         */
+/* ------------------------------------------------------------------------ */
+void la_oracle_grad_ab_def(const double *Q, const double *K, const double *V,
+                           const double *dO, double *dab,
+                           long BH, long N, int D, double a, double b, int causal)
+{
+    double da = 0.0, db = 0.0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : da, db)
+    for (long bh = 0; bh < BH; ++bh) {
+        const double *q = Q + bh * N * D, *k = K + bh * N * D, *v = V + bh * N * D;
+        const double *om = dO + bh * N * D;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(N + 2 * D));
+        double *oi = s + N, *oh = oi + D;
+        for (long i = 0; i < N; ++i) {
+            long last = causal ? i : N - 1;
+            double gi = 0.0;
+            for (int j = 0; j < D; ++j) oi[j] = 0.0;
+            for (long n = 0; n <= last; ++n) {
+                s[n] = dot(q + i * D, k + n * D, D);
+                double w = a + b * s[n];
+                gi += w;
+                for (int j = 0; j < D; ++j) oi[j] += w * v[n * D + j];
+            }
+            double delta = 0.0;
+            for (int j = 0; j < D; ++j) {
+                oi[j] /= gi;
+                oh[j] = om[i * D + j] / gi;
+                delta += oi[j] * oh[j];
+            }
+            for (long n = 0; n <= last; ++n) {
+                double c = dot(oh, v + n * D, D) - delta;
+                da += c;
+                db += c * s[n];
+            }
+        }
+        free(s);
+    }
+    dab[0] = da;
+    dab[1] = db;
+}

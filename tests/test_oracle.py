@@ -264,3 +264,74 @@ def test_a_zero_matches_cumsum_rnn_form(oracle_mod):
     for fwd in (oracle_mod.forward_def, oracle_mod.forward_rec):
         O, _ = fwd(Q, K, V, 0.0, 1.0, True)
         np.testing.assert_allclose(O, ref, rtol=1e-11)
+
+
+# --------------------------------------------------------------------------
+# incremental (decode) form with a carried state (App. B.1)
+# --------------------------------------------------------------------------
+def test_decode_hand_example(oracle_mod):
+    """The hand-evaluated causal example, one row per call with the state carried over."""
+    gold = _golden()
+    q = np.array([[1.0], [2.0]]); k = np.array([[3.0], [4.0]]); v = np.array([[5.0], [6.0]])
+    state = np.zeros(oracle_mod.decode_state_floats(1))
+    for t in range(2):
+        o, g = oracle_mod.decode(q[t:t + 1], k[t:t + 1], v[t:t + 1], state, 1.0, 0.5)
+        np.testing.assert_allclose(o[0, 0], gold[("causal", "O")][t], rtol=1e-14)
+        np.testing.assert_allclose(g[0], gold[("causal", "G")][t], rtol=1e-14)
+    # the state is [S | z | p | count] = [3*5 + 4*6 | 3 + 4 | 5 + 6 | 2]
+    np.testing.assert_allclose(state, [39.0, 7.0, 11.0, 2.0], rtol=1e-15)
+
+
+@pytest.mark.parametrize("steps", [[1] * 9, [4, 1, 3, 1], [9], [2, 7]])
+def test_decode_matches_definition_and_composes(oracle_mod, steps):
+    """Fed a sequence in pieces of any sizes, the incremental form reproduces the causal
+    definition row by row, and its final state is the plain sums over all rows."""
+    BH, D = 3, 5
+    N = sum(steps)
+    Q, K, V, _ = rand_inputs(BH, N, D, seed=71)
+    for a, b in ((1.0, 0.5), (2.0, -0.7)):
+        O_def, G_def = oracle_mod.forward_def(Q, K, V, a, b, True)
+        state = np.zeros((BH, oracle_mod.decode_state_floats(D)))
+        at = 0
+        for T in steps:
+            o, g = oracle_mod.decode(Q[:, at:at + T], K[:, at:at + T], V[:, at:at + T], state, a, b)
+            np.testing.assert_allclose(o, O_def[:, at:at + T], rtol=1e-11, atol=1e-14)
+            np.testing.assert_allclose(g, G_def[:, at:at + T], rtol=1e-12)
+            at += T
+        S = np.einsum("bnm,bnj->bmj", K, V).reshape(BH, D * D)
+        want = np.concatenate([S, K.sum(axis=1), V.sum(axis=1), np.full((BH, 1), float(N))], axis=1)
+        np.testing.assert_allclose(state, want, rtol=1e-12, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# gradients with respect to the kernel's coefficients a, b
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [True, False])
+def test_grad_ab(oracle_mod, causal):
+    BH, N, D = 2, 23, 6
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=83)
+    for a, b in ((1.0, 0.5), (2.0, -0.7), (1.5, 0.0)):
+        da, db = oracle_mod.grad_ab_def(Q, K, V, dO, a, b, causal)
+
+        def loss(a_, b_):
+            o, _ = oracle_mod.forward_def(Q, K, V, a_, b_, causal)
+            return float(np.sum(o * dO))
+
+        # central finite differences
+        h = 1e-6
+        np.testing.assert_allclose(da, (loss(a + h, b) - loss(a - h, b)) / (2 * h),
+                                   rtol=1e-6, atol=1e-8)
+        np.testing.assert_allclose(db, (loss(a, b + h) - loss(a, b - h)) / (2 * h),
+                                   rtol=1e-6, atol=1e-8)
+        # library autograd through the dense form
+        ta = torch.tensor(a, dtype=torch.float64, requires_grad=True)
+        tb = torch.tensor(b, dtype=torch.float64, requires_grad=True)
+        O_t, _ = dense_augmented(torch.tensor(Q), torch.tensor(K), torch.tensor(V), ta, tb, causal)
+        (O_t * torch.tensor(dO)).sum().backward()
+        np.testing.assert_allclose(da, ta.grad.item(), rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(db, tb.grad.item(), rtol=1e-9, atol=1e-12)
+        # O depends on (a, b) only through their ratio: a dL/da + b dL/db = 0, and the
+        # gradient of Q carries the same number: sum q.dq = b dL/db
+        assert abs(a * da + b * db) < 1e-9 * (abs(a * da) + abs(b * db)) + 1e-11
+        dq, _, _ = oracle_mod.backward_def(Q, K, V, dO, a, b, causal)
+        np.testing.assert_allclose(np.sum(Q * dq), b * db, rtol=1e-9, atol=1e-12)
