@@ -126,6 +126,40 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Incremental (decode) form: the recurrence of App. B.1 (Table 3, row 2: S_t =
+ * S_{t-1} + k_t v_t^T, z_t = z_{t-1} + k_t) for the kernel a + b x, i.e. Eq. xy /
+ * fglast with the running sums carried across calls instead of across chunks.
+ *
+ *   state: device memory, caller-owned, float32, la_decode_state_bytes(B, H, D)
+ *       bytes, 256-byte aligned; per (batch, head) slice [S (D*D, row r column j =
+ *       sum k_r v_j) | z (D) | p (D) | count (1)], padded to a multiple of 64
+ *       floats.  All zeros stands for an empty prefix (the caller clears it).
+ *   la_decode_step: appends T >= 1 rows per slice -- q, k, v, o are [B,H,T,D] of
+ *       `dt`, g is [B,H,T] float32 or NULL -- each row is added to the sums and
+ *       then read out (a row attends to the prefix and to itself), and the state
+ *       is updated in place.  D in {16, 32, 64, 128, 256}.  Calls that share a
+ *       state must not overlap in time.
+ *   la_decode_prefill: sets (accumulate = 0) or adds to (accumulate != 0) the
+ *       state the sums over the N rows of K, V [B,H,N,D] in one parallel pass:
+ *       the state after a prompt that was run through la_forward.  workspace as
+ *       for la_forward without the mask: la_workspace_bytes(B,H,N,D,dt,0,0).
+ *       D in {16, 32, 64, 128}.
+ * Error behaviour as for la_forward; a missing, misaligned or short state is
+ * LA_ERR_WORKSPACE.
+ */
+LA_API size_t la_decode_state_bytes(int B, int H, int D);
+
+LA_API la_status la_decode_step(const void *q, const void *k, const void *v,
+                     void *o, float *g, float *state, size_t state_bytes,
+                     int B, int H, int T, int D,
+                     float a, float b, la_dtype dt, void *hip_stream);
+
+LA_API la_status la_decode_prefill(const void *K, const void *V,
+                     float *state, size_t state_bytes,
+                     int B, int H, int N, int D, la_dtype dt, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * la_forward for callers that cannot allocate or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same computation and results as la_forward, with the workspace in a static

@@ -19,7 +19,8 @@ LA_MAX_TRACE = 8
 
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
-           "la_backward_saved", "la_debug_override", "la_forward_static")
+           "la_backward_saved", "la_debug_override", "la_forward_static", "la_decode_state_bytes",
+           "la_decode_step", "la_decode_prefill")
 
 
 class la_trace(ctypes.Structure):
@@ -75,6 +76,12 @@ def load_library():
     lib.la_backward_saved.argtypes = lib.la_backward.argtypes[:-1] + [vp, sz, vp, tp]
     lib.la_forward_static.restype = i
     lib.la_forward_static.argtypes = lib.la_forward.argtypes[:-3] + [vp]
+    lib.la_decode_state_bytes.restype = sz
+    lib.la_decode_state_bytes.argtypes = [i, i, i]
+    lib.la_decode_step.restype = i
+    lib.la_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, f, i, vp]
+    lib.la_decode_prefill.restype = i
+    lib.la_decode_prefill.argtypes = [vp, vp, vp, sz, i, i, i, i, i, i, vp, sz, vp]
     lib.la_debug_override.restype = None
     lib.la_debug_override.argtypes = [i, i]
     _lib = lib
@@ -250,3 +257,44 @@ def _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, str
         rc = lib.la_backward_traced(*head, _stream_ptr(stream, Q.device), tr)
     if rc != 0:
         raise LaError(rc, "la_backward_saved" if use_saved else "la_backward")
+
+
+def la_decode_state_bytes(B, H, D):
+    return int(load_library().la_decode_state_bytes(B, H, D))
+
+
+def la_decode_step(q, k, v, o, g, state, a, b, stream=None):
+    """la_decode_step of include/la.h: q, k, v, o [B, H, T, D]; g [B, H, T] float32 or None;
+    state: float32 device tensor of la_decode_state_bytes(B, H, D) bytes, updated in place."""
+    if q.dim() != 4:
+        raise ValueError("q must be [B, H, T, D]")
+    B, H, T, D = q.shape
+    _check_tensors(q, k, v, o, g, state)
+    if k.shape != q.shape or v.shape != q.shape or o.shape != q.shape:
+        raise ValueError("shape mismatch")
+    if not (k.dtype == v.dtype == o.dtype == q.dtype) or state.dtype != torch.float32:
+        raise TypeError("dtype mismatch")
+    if g is not None and (g.shape != q.shape[:3] or g.dtype != torch.float32):
+        raise ValueError("g must be [B, H, T] float32 (or None)")
+    rc = load_library().la_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(g), _ptr(state),
+                                       state.numel() * 4, B, H, T, D, float(a), float(b),
+                                       _dtype_code(q), _stream_ptr(stream, q.device))
+    if rc != 0:
+        raise LaError(rc, "la_decode_step")
+
+
+def la_decode_prefill(K, V, state, accumulate, workspace, stream=None):
+    """la_decode_prefill of include/la.h: K, V [B, H, N, D]."""
+    if K.dim() != 4:
+        raise ValueError("K must be [B, H, N, D]")
+    B, H, N, D = K.shape
+    _check_tensors(K, V, state, workspace)
+    if V.shape != K.shape or V.dtype != K.dtype or state.dtype != torch.float32:
+        raise ValueError("shape or dtype mismatch")
+    rc = load_library().la_decode_prefill(_ptr(K), _ptr(V), _ptr(state), state.numel() * 4, B, H,
+                                          N, D, _dtype_code(K), int(bool(accumulate)),
+                                          _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(),
+                                          _stream_ptr(stream, K.device))
+    if rc != 0:
+        raise LaError(rc, "la_decode_prefill")

@@ -317,6 +317,68 @@ la_status la_forward_static(const void *Q, const void *K, const void *V, void *O
                         false, nullptr, 0, hip_stream, nullptr);
 }
 
+size_t la_decode_state_bytes(int B, int H, int D)
+{
+    if (B < 1 || H < 1 || (double)B * H > 2147483647.0 / 4096.0) return 0;
+    if (!la::supported_d(D) && D != 256) return 0;
+    return (size_t)B * H * la::decode_state_floats(D) * 4;
+}
+
+la_status la_decode_step(const void *q, const void *k, const void *v, void *o, float *g,
+                         float *state, size_t state_bytes, int B, int H, int T, int D, float a,
+                         float b, la_dtype dt, void *hip_stream)
+{
+    if (B < 1 || H < 1 || T < 1 || D < 1 || (double)B * H > 2147483647.0 / 4096.0)
+        return LA_ERR_SHAPE;
+    if ((double)B * H * T * D >= 1099511627776.0) return LA_ERR_SHAPE;
+    if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_UNSUPPORTED;
+    if (!la::supported_d(D) && D != 256) return LA_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !o) return LA_ERR_NULL;
+    const void *ptrs[] = {q, k, v, o, g, state};
+    for (const void *p : ptrs)
+        if (!la::aligned16(p)) return LA_ERR_ALIGN;
+    const size_t need = la_decode_state_bytes(B, H, D);
+    if (!state || state_bytes < need || (((uintptr_t)state) & 255u)) return LA_ERR_WORKSPACE;
+    {
+        const size_t TT = (size_t)B * H * T, tb = TT * D * (dt == LA_F32 ? 4 : 2);
+        const la::Range ins[] = {{q, tb}, {k, tb}, {v, tb}};
+        const la::Range outs[] = {{o, tb}, {g, TT * 4}, {state, need}};
+        if (la::any_alias(ins, 3, outs, 3)) return LA_ERR_ALIAS;
+    }
+    if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;
+    return la::decode_step(q, k, v, o, g, state, B * H, T, D, a, b, dt, (hipStream_t)hip_stream);
+}
+
+la_status la_decode_prefill(const void *K, const void *V, float *state, size_t state_bytes, int B,
+                            int H, int N, int D, la_dtype dt, int accumulate, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    la_status s = la::check_shape(B, H, N, D, dt);
+    if (s != LA_OK) return s;
+    if (!K || !V) return LA_ERR_NULL;
+    if (!la::aligned16(K) || !la::aligned16(V)) return LA_ERR_ALIGN;
+    const size_t need = la_decode_state_bytes(B, H, D);
+    if (!state || state_bytes < need || (((uintptr_t)state) & 255u)) return LA_ERR_WORKSPACE;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, 0, 0);
+    if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
+    if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
+        return LA_ERR_WORKSPACE;
+    {
+        const size_t tb = (size_t)B * H * N * D * (dt == LA_F32 ? 4 : 2);
+        const la::Range ins[] = {{K, tb}, {V, tb}};
+        const la::Range outs[] = {{state, need}, {workspace, pl.total_bytes}};
+        if (la::any_alias(ins, 2, outs, 2)) return LA_ERR_ALIAS;
+    }
+    if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;
+    la::Problem pr{B * H, N, D, 1.f, 0.f, 0, dt};
+    hipStream_t st = (hipStream_t)hip_stream;
+    s = la::use_fast(pr, 0) ? la::fast_kv_totals(pr, pl, K, V, (float *)workspace, st)
+                            : la::generic_kv_totals(pr, pl, K, V, (float *)workspace, st);
+    if (s != LA_OK) return s;
+    return la::state_from_totals((const float *)workspace, state, B * H, D, pl.nseg, pl.slot_floats,
+                                 N, accumulate ? 1 : 0, st);
+}
+
 la_status la_forward_traced(const void *Q, const void *K, const void *V, void *O, float *G, int B,
                             int H, int N, int D, float a, float b, int causal, la_dtype dt,
                             void *workspace, size_t workspace_bytes, void *hip_stream,

@@ -140,6 +140,21 @@ la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const v
                        const void *V, void *O, float *G, float *ws, float *saved, hipStream_t st,
                        Tracer &tc);
 
+// Sums over the whole sequence, S = sum k v^T, z = sum k, p = sum v, left in slot 0 of every
+// slice as [S | z | p] (forward plan without the mask): phases 1 and 2 of the unmasked
+// forward pass on their own.
+la_status fast_kv_totals(const Problem &pr, const Plan &pl, const void *K, const void *V,
+                         float *ws, hipStream_t st);
+la_status generic_kv_totals(const Problem &pr, const Plan &pl, const void *K, const void *V,
+                            float *ws, hipStream_t st);
+
+// Incremental (decode) step (la_decode.hip).
+size_t decode_state_floats(int D);
+la_status decode_step(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
+                      int BH, int Tn, int D, float a, float b, la_dtype dt, hipStream_t st);
+la_status state_from_totals(const float *ws, float *state, int BH, int D, int nseg,
+                            size_t slot_floats, int N, int accumulate, hipStream_t st);
+
 // Generic (plain-ALU, any supported D) path.
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                           const void *V, void *O, float *G, float *ws, hipStream_t st,

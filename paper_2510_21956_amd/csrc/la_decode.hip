@@ -1,0 +1,163 @@
+// Incremental (decode) step: the recurrence of App. B.1 (Table 3, row 2) for the kernel
+// a + b x, with the running sums of Eq. xy carried across calls in a caller-owned state.
+//
+// State of one (batch, head) slice, float32: [S (D*D, S[r][j] = sum k_r v_j) | z (D) | p (D) |
+// count (1)], padded to a multiple of 64 floats.  A call appends T rows: each is added to the
+// sums, then read out, o_t = (a p + b S^T q_t) / g_t, g_t = a count + b q_t . z (Eq. fglast, div).
+//
+// One workgroup per slice keeps the whole state in registers for the T rows of the call (no
+// other workgroup touches that slice's state, so updating it in place is race-free): thread
+// t owns column j = t % D of the rows r = t / D + RG i.  The step is bound by reading and
+// writing the state once per call: 8 D^2 bytes per slice.
+#include "la_common.h"
+
+namespace la {
+namespace {
+
+template <int D>
+struct DC {
+    static constexpr int NT = D <= 128 ? 256 : 1024;  // threads per workgroup
+    static constexpr int RG = NT / D;                 // row groups: threads that share a column
+    static constexpr int RPT = D / RG;                // state rows per thread
+};
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m);
+    return x;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__((DC<D>::NT)) void k_decode(const T *__restrict__ Q,
+                                                       const T *__restrict__ K,
+                                                       const T *__restrict__ V, T *__restrict__ O,
+                                                       float *__restrict__ G,
+                                                       float *__restrict__ state, int Tn,
+                                                       size_t state_floats, float a, float b)
+{
+    constexpr int NT = DC<D>::NT, RG = DC<D>::RG, RPT = DC<D>::RPT;
+    __shared__ float qs[D], ks[D], vs[D], zs[D], part[RG][D], red[NT / 64], gsh;
+    const int bh = blockIdx.x, t = threadIdx.x, j = t % D, rg = t / D;
+    float *st = state + (size_t)bh * state_floats;
+    float S[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) S[i] = st[(size_t)(rg + RG * i) * D + j];
+    if (t < D) zs[t] = st[D * D + t];
+    float pj = st[D * D + D + j];  // every row group keeps its own copy of p[j]
+    float cnt = st[D * D + 2 * D];
+    const size_t base = (size_t)bh * Tn * D;
+    for (int tok = 0; tok < Tn; ++tok) {
+        __syncthreads();  // the previous row's reads of qs, ks, vs, part are done
+        if (t < D) {
+            const size_t e = base + (size_t)tok * D + t;
+            qs[t] = load_elem(Q, e);
+            const float kt = load_elem(K, e);
+            ks[t] = kt;
+            vs[t] = load_elem(V, e);
+            zs[t] += kt;  // the new row enters the sums before it is read out
+        }
+        cnt += 1.f;
+        __syncthreads();
+        // g = a count + b q . z
+        float s = 0.f;
+        for (int m = t; m < D; m += NT) s += qs[m] * zs[m];
+        s = wave_sum(s);
+        if (t % 64 == 0) red[t / 64] = s;
+        const float vj = vs[j];
+        pj += vj;
+        float f = 0.f;
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            const int r = rg + RG * i;
+            S[i] += ks[r] * vj;
+            f += S[i] * qs[r];
+        }
+        part[rg][j] = f;
+        __syncthreads();
+        if (t == 0) {
+            float qz = 0.f;
+            for (int wv = 0; wv < NT / 64; ++wv) qz += red[wv];
+            gsh = a * cnt + b * qz;
+        }
+        __syncthreads();
+        if (t < D) {
+            float lin = 0.f;
+#pragma unroll
+            for (int r = 0; r < RG; ++r) lin += part[r][t];
+            const float gv = gsh;
+            store_elem(O, base + (size_t)tok * D + t, (a * pj + b * lin) / gv);
+            if (t == 0 && G) G[(size_t)bh * Tn + tok] = gv;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) st[(size_t)(rg + RG * i) * D + j] = S[i];
+    __syncthreads();
+    if (t < D) {
+        st[D * D + t] = zs[t];
+        st[D * D + D + t] = pj;  // t < D is row group 0, column t
+    }
+    if (t == 0) st[D * D + 2 * D] = cnt;
+}
+
+// state (+)= [S | z | p] totals left in slot 0 of every slice by the forward sums, count (+)= N
+template <int DUMMY>
+__global__ __launch_bounds__(256) void k_state_from_totals(const float *__restrict__ ws,
+                                                           float *__restrict__ state, int D,
+                                                           int nseg, size_t slot_floats,
+                                                           size_t state_floats, int N,
+                                                           int accumulate)
+{
+    const int bh = blockIdx.x, len = D * D + 2 * D;
+    const float *src = ws + (size_t)bh * nseg * slot_floats;
+    float *dst = state + (size_t)bh * state_floats;
+    for (int e = blockIdx.y * 256 + threadIdx.x; e <= len; e += gridDim.y * 256) {
+        const float x = e < len ? src[e] : (float)N;
+        dst[e] = accumulate ? dst[e] + x : x;
+    }
+}
+
+template <typename T>
+la_status decode_by_d(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
+                      int BH, int Tn, int D, size_t sf, float a, float b, hipStream_t st)
+{
+    const T *q = (const T *)Q, *k = (const T *)K, *v = (const T *)V;
+    T *o = (T *)O;
+#define LA_DECODE_CASE(DD)                                                                       \
+    case DD:                                                                                     \
+        k_decode<T, DD><<<dim3(BH), dim3(DC<DD>::NT), 0, st>>>(q, k, v, o, G, state, Tn, sf, a, b); \
+        break;
+    switch (D) {
+        LA_DECODE_CASE(16)
+        LA_DECODE_CASE(32)
+        LA_DECODE_CASE(64)
+        LA_DECODE_CASE(128)
+        LA_DECODE_CASE(256)
+        default: return LA_ERR_UNSUPPORTED;
+    }
+#undef LA_DECODE_CASE
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+size_t decode_state_floats(int D) { return ((size_t)D * D + 2 * (size_t)D + 1 + 63) / 64 * 64; }
+
+la_status decode_step(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
+                      int BH, int Tn, int D, float a, float b, la_dtype dt, hipStream_t st)
+{
+    const size_t sf = decode_state_floats(D);
+    if (dt == LA_F32) return decode_by_d<float>(Q, K, V, O, G, state, BH, Tn, D, sf, a, b, st);
+    return decode_by_d<bf16_t>(Q, K, V, O, G, state, BH, Tn, D, sf, a, b, st);
+}
+
+la_status state_from_totals(const float *ws, float *state, int BH, int D, int nseg,
+                            size_t slot_floats, int N, int accumulate, hipStream_t st)
+{
+    const int len = D * D + 2 * D + 1;
+    k_state_from_totals<0><<<dim3(BH, (len + 255) / 256), dim3(256), 0, st>>>(
+        ws, state, D, nseg, slot_floats, decode_state_floats(D), N, accumulate);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+}  // namespace la

@@ -1494,7 +1494,31 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     return launch_status();
 }
 
+template <typename T, int D>
+la_status fast_totals(const Problem &pr, const Plan &pl, const void *Kv, const void *Vv, float *ws,
+                      hipStream_t st)
+{
+    constexpr int NT = FC<T, D>::NT;
+    kf_kv_state<T, D, false><<<dim3(pr.BH * pl.nseg), dim3(NT), 0, st>>>(
+        (const T *)Kv, (const T *)Vv, ws, pr.N, pl.nseg, pl.nseg, pl.map, pl.slot_floats, 0);
+    launch_scan_slots(ws, pr.BH, pl.nseg, pl.slot_floats, 0, D * D + 2 * D, 2, 0, pl.nseg - 1, st);
+    return launch_status();
+}
+
 }  // namespace
+
+la_status fast_kv_totals(const Problem &pr, const Plan &pl, const void *K, const void *V,
+                         float *ws, hipStream_t st)
+{
+    if (pr.dt == LA_F32) {
+        if (pr.D == 64) return fast_totals<float, 64>(pr, pl, K, V, ws, st);
+        if (pr.D == 128) return fast_totals<float, 128>(pr, pl, K, V, ws, st);
+    } else {
+        if (pr.D == 64) return fast_totals<__bf16, 64>(pr, pl, K, V, ws, st);
+        if (pr.D == 128) return fast_totals<__bf16, 128>(pr, pl, K, V, ws, st);
+    }
+    return LA_ERR_UNSUPPORTED;
+}
 
 bool fast_supported(const Problem &pr, int is_backward)
 {

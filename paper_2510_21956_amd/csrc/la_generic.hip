@@ -567,6 +567,33 @@ void launch_scan_slots(float *ws, int BH, int nseg, size_t slot_floats, int off,
                                                                     len, mode, lo, hi);
 }
 
+namespace {
+template <typename T>
+la_status totals_by_d(const Problem &pr, const Plan &pl, const void *Kv, const void *Vv, float *ws,
+                      hipStream_t st)
+{
+    const T *k = (const T *)Kv, *v = (const T *)Vv;
+    const dim3 grid(pr.BH * pl.nseg), block(NT);
+    switch (pr.D) {
+        case 16: k_fwd_state<T, 16><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
+        case 32: k_fwd_state<T, 32><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
+        case 64: k_fwd_state<T, 64><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
+        case 128: k_fwd_state<T, 128><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
+        default: return LA_ERR_UNSUPPORTED;
+    }
+    launch_scan_slots(ws, pr.BH, pl.nseg, pl.slot_floats, 0, pr.D * pr.D + 2 * pr.D, 2, 0,
+                      pl.nseg - 1, st);
+    return launch_status();
+}
+}  // namespace
+
+la_status generic_kv_totals(const Problem &pr, const Plan &pl, const void *K, const void *V,
+                            float *ws, hipStream_t st)
+{
+    if (pr.dt == LA_F32) return totals_by_d<float>(pr, pl, K, V, ws, st);
+    return totals_by_d<bf16_t>(pr, pl, K, V, ws, st);
+}
+
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                           const void *V, void *O, float *G, float *ws, hipStream_t st,
                           Tracer &tc)
