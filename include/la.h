@@ -78,7 +78,7 @@ LA_API const char *la_status_string(la_status s);
 /*
  * Bytes of device workspace la_forward (is_backward = 0) or la_backward
  * (is_backward = 1; is_backward = 2: la_backward called with O or G NULL, which
- * recomputes them) needs for this problem.  Returns 0 for invalid or
+ * recomputes them; is_backward = 3: la_backward_ab) needs for this problem.  Returns 0 for invalid or
  * unsupported arguments.  The workspace holds the per-segment running-sum
  * states (S = sum k v^T, z = sum k, p = sum v of Eq. xy; and the reverse sums
  * of Eq. endd for the backward pass) that let segments of one sequence run in
@@ -121,6 +121,27 @@ LA_API la_status la_forward(const void *Q, const void *K, const void *V,
 LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       const void *O, const float *G, const void *dO,
                       void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Gradients of sum(O * dO) with respect to the kernel's own coefficients, which
+ * Sec. 2.2 allows to be learnable.  With dL/dw_in = OmegaHat_i . v_n - delta_i
+ * (Eq. bound divided by b; OmegaHat = dO / g, delta_i = o_i . OmegaHat_i) and
+ * w_in = a + b q_i . k_n:
+ *     dL/db = sum_{i, n in A(i)} dL/dw_in (q_i . k_n) = sum_i q_i . dq_i / b,
+ *     dL/da = sum_{i, n in A(i)} dL/dw_in             = -(b / a) dL/db
+ * (O depends on a and b through their ratio only).  The call runs the ascending
+ * sweep of the backward pass (Eq. back1) once with unit b and reduces q . dq over
+ * all elements in a fixed order, so b = 0 is allowed; a = 0 is LA_ERR_UNSUPPORTED.
+ *   in : Q, K, V, O, dO, G as for la_backward (O, G required).
+ *   out: dab: device pointer to two floats, 8-byte aligned: dab[0] = dL/da,
+ *        dab[1] = dL/db, summed over every batch, head and row.
+ *   workspace: at least la_workspace_bytes(..., 3) bytes, 256-byte aligned.
+ */
+LA_API la_status la_backward_ab(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO, float *dab,
                       int B, int H, int N, int D,
                       float a, float b, int causal, la_dtype dt,
                       void *workspace, size_t workspace_bytes, void *hip_stream);

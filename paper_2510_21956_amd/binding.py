@@ -20,7 +20,7 @@ LA_MAX_TRACE = 8
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
            "la_backward_saved", "la_debug_override", "la_forward_static", "la_decode_state_bytes",
-           "la_decode_step", "la_decode_prefill")
+           "la_decode_step", "la_decode_prefill", "la_backward_ab")
 
 
 class la_trace(ctypes.Structure):
@@ -82,6 +82,8 @@ def load_library():
     lib.la_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, f, i, vp]
     lib.la_decode_prefill.restype = i
     lib.la_decode_prefill.argtypes = [vp, vp, vp, sz, i, i, i, i, i, i, vp, sz, vp]
+    lib.la_backward_ab.restype = i
+    lib.la_backward_ab.argtypes = [vp] * 7 + [i, i, i, i, f, f, i, i, vp, sz, vp]
     lib.la_debug_override.restype = None
     lib.la_debug_override.argtypes = [i, i]
     _lib = lib
@@ -298,3 +300,25 @@ def la_decode_prefill(K, V, state, accumulate, workspace, stream=None):
                                           _stream_ptr(stream, K.device))
     if rc != 0:
         raise LaError(rc, "la_decode_prefill")
+
+
+def la_backward_ab(Q, K, V, O, G, dO, dab, a, b, causal, workspace, stream=None):
+    """la_backward_ab of include/la.h; ``dab``: float32 device tensor of two elements."""
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, N, D]")
+    B, H, N, D = Q.shape
+    _check_tensors(Q, K, V, O, G, dO, dab, workspace)
+    for t in (K, V, O, dO):
+        if t.shape != Q.shape or t.dtype != Q.dtype:
+            raise ValueError("shape or dtype mismatch")
+    if G.shape != Q.shape[:3] or G.dtype != torch.float32:
+        raise ValueError("G must be [B, H, N] float32")
+    if dab.dtype != torch.float32 or dab.numel() < 2:
+        raise ValueError("dab must hold two float32")
+    rc = load_library().la_backward_ab(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(G), _ptr(dO),
+                                       _ptr(dab), B, H, N, D, float(a), float(b),
+                                       int(bool(causal)), _dtype_code(Q), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(),
+                                       _stream_ptr(stream, Q.device))
+    if rc != 0:
+        raise LaError(rc, "la_backward_ab")

@@ -131,6 +131,23 @@ static Recompute recompute_layout(const Plan &bwd, const Plan &fwd, size_t T, in
     return r;
 }
 
+// Workspace of la_backward_ab: the backward workspace, the partial sums of the final
+// reduction, then dQ for unit b (and, on the plain-ALU path, the dK and dV it cannot leave out).
+struct AbLayout {
+    size_t partials_off, dq_off, dk_off, dv_off, total_bytes;
+};
+static AbLayout ab_layout(const Plan &bwd, size_t T, int D, la_dtype dt, bool fast)
+{
+    const size_t tb = round_up(T * D * (dt == LA_F32 ? 4 : 2), 256);
+    AbLayout r;
+    r.partials_off = round_up(bwd.total_bytes, 256);
+    r.dq_off = r.partials_off + round_up((size_t)reduce_dot_partials() * 4, 256);
+    r.dk_off = r.dq_off + tb;
+    r.dv_off = r.dk_off + (fast ? 0 : tb);
+    r.total_bytes = r.dv_off + (fast ? 0 : tb);
+    return r;
+}
+
 }  // namespace la
 
 extern "C" {
@@ -166,6 +183,10 @@ size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal, i
     if (la::check_shape(B, H, N, D, dt) != LA_OK) return 0;
     const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, is_backward ? 1 : 0);
     if (!la::grid_ok(B, H, pl)) return 0;
+    if (is_backward == 3) {
+        la::Problem pr{B * H, N, D, 1.f, 1.f, causal ? 1 : 0, dt};
+        return la::ab_layout(pl, (size_t)B * H * N, D, dt, la::use_fast(pr, 1)).total_bytes;
+    }
     if (is_backward != 2) return pl.total_bytes;
     const la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
     return la::recompute_layout(pl, pf, (size_t)B * H * N, D, dt).total_bytes;
@@ -315,6 +336,51 @@ la_status la_forward_static(const void *Q, const void *K, const void *V, void *O
     // been written by this call's own kernels first
     return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, ws, LA_STATIC_SCRATCH_BYTES,
                         false, nullptr, 0, hip_stream, nullptr);
+}
+
+la_status la_backward_ab(const void *Q, const void *K, const void *V, const void *O,
+                         const float *G, const void *dO, float *dab, int B, int H, int N, int D,
+                         float a, float b, int causal, la_dtype dt, void *workspace,
+                         size_t workspace_bytes, void *hip_stream)
+{
+    la_status s = la::check_shape(B, H, N, D, dt);
+    if (s != LA_OK) return s;
+    if (!Q || !K || !V || !O || !G || !dO || !dab) return LA_ERR_NULL;
+    if (a == 0.f) return LA_ERR_UNSUPPORTED;
+    const void *ptrs[] = {Q, K, V, O, G, dO};
+    for (const void *p : ptrs)
+        if (!la::aligned16(p)) return LA_ERR_ALIGN;
+    if (((uintptr_t)dab) & 7u) return LA_ERR_ALIGN;
+    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 1);
+    if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
+    // the sweep below runs with b = 1: its scale is taken out again by the formula
+    la::Problem pr{B * H, N, D, a, 1.f, causal ? 1 : 0, dt};
+    const bool fast = la::use_fast(pr, 1);
+    const size_t T = (size_t)B * H * N;
+    const la::AbLayout lay = la::ab_layout(pl, T, D, dt, fast);
+    if (!workspace || workspace_bytes < lay.total_bytes || (((uintptr_t)workspace) & 255u))
+        return LA_ERR_WORKSPACE;
+    {
+        const size_t tb = T * D * (dt == LA_F32 ? 4 : 2);
+        const la::Range ins[] = {{Q, tb}, {K, tb}, {V, tb}, {O, tb}, {G, T * 4}, {dO, tb}};
+        const la::Range outs[] = {{dab, 8}, {workspace, lay.total_bytes}};
+        if (la::any_alias(ins, 6, outs, 2)) return LA_ERR_ALIAS;
+    }
+    if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *wsb = (char *)workspace;
+    void *dq1 = wsb + lay.dq_off;
+    if (fast) {
+        s = la::fast_backward_dq(pr, pl, Q, K, V, O, G, dO, dq1, (float *)workspace, st);
+    } else {
+        la::Tracer tc(nullptr, st);
+        s = la::generic_backward(pr, pl, Q, K, V, O, G, dO, dq1, wsb + lay.dk_off,
+                                 wsb + lay.dv_off, (float *)workspace, st, tc);
+    }
+    if (s != LA_OK) return s;
+    // sum q . dq(b = 1) = dL/db, and a dL/da + b dL/db = 0 (O depends on a, b through a / b only)
+    return la::reduce_dot(Q, dq1, T * D, dt, -b / a, 1.f, (float *)(wsb + lay.partials_off), dab,
+                          st);
 }
 
 size_t la_decode_state_bytes(int B, int H, int D)

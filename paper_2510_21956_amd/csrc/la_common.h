@@ -140,6 +140,16 @@ la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const v
                        const void *V, void *O, float *G, float *ws, float *saved, hipStream_t st,
                        Tracer &tc);
 
+// The ascending sweep of the backward pass alone: dQ for the coefficients in pr (matrix-core path).
+la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                           const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                           float *ws, hipStream_t st);
+// sum over all elements of X * Y (n elements of dt) -> out[0] = scale0 * sum, out[1] = scale1 * sum;
+// `partials` is scratch of at least reduce_dot_partials() floats.  Fixed summation order.
+int reduce_dot_partials();
+la_status reduce_dot(const void *X, const void *Y, size_t n, la_dtype dt, float scale0, float scale1,
+                     float *partials, float *out, hipStream_t st);
+
 // Sums over the whole sequence, S = sum k v^T, z = sum k, p = sum v, left in slot 0 of every
 // slice as [S | z | p] (forward plan without the mask): phases 1 and 2 of the unmasked
 // forward pass on their own.

@@ -117,6 +117,41 @@ __global__ __launch_bounds__(256) void k_state_from_totals(const float *__restri
     }
 }
 
+// Stage 1 of sum(X * Y): workgroup w sums a fixed contiguous share into partials[w].
+constexpr int kDotBlocks = 1024;
+template <typename T>
+__global__ __launch_bounds__(256) void k_dot_partial(const T *__restrict__ X,
+                                                     const T *__restrict__ Y, size_t n,
+                                                     float *__restrict__ partials)
+{
+    __shared__ float red[4];
+    const size_t per = (n + gridDim.x - 1) / gridDim.x;
+    const size_t lo = (size_t)blockIdx.x * per, hi = lo + per < n ? lo + per : n;
+    float s = 0.f;
+    for (size_t e = lo + threadIdx.x; e < hi; e += 256) s += load_elem(X, e) * load_elem(Y, e);
+    s = wave_sum(s);
+    if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+// Stage 2: one workgroup adds the partials in a fixed order and writes the two scaled results.
+__global__ __launch_bounds__(256) void k_dot_final(const float *__restrict__ partials, int np,
+                                                   float scale0, float scale1,
+                                                   float *__restrict__ out)
+{
+    __shared__ float red[4];
+    float s = 0.f;
+    for (int e = threadIdx.x; e < np; e += 256) s += partials[e];
+    s = wave_sum(s);
+    if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+        out[0] = scale0 * tot;
+        out[1] = scale1 * tot;
+    }
+}
+
 template <typename T>
 la_status decode_by_d(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
                       int BH, int Tn, int D, size_t sf, float a, float b, hipStream_t st)
@@ -140,6 +175,21 @@ la_status decode_by_d(const void *Q, const void *K, const void *V, void *O, floa
 }
 
 }  // namespace
+
+int reduce_dot_partials() { return kDotBlocks; }
+
+la_status reduce_dot(const void *X, const void *Y, size_t n, la_dtype dt, float scale0, float scale1,
+                     float *partials, float *out, hipStream_t st)
+{
+    if (dt == LA_F32)
+        k_dot_partial<float><<<dim3(kDotBlocks), dim3(256), 0, st>>>((const float *)X,
+                                                                     (const float *)Y, n, partials);
+    else
+        k_dot_partial<bf16_t><<<dim3(kDotBlocks), dim3(256), 0, st>>>((const bf16_t *)X,
+                                                                      (const bf16_t *)Y, n, partials);
+    k_dot_final<<<dim3(1), dim3(256), 0, st>>>(partials, kDotBlocks, scale0, scale1, out);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
 
 size_t decode_state_floats(int D) { return ((size_t)D * D + 2 * (size_t)D + 1 + 63) / 64 * 64; }
 

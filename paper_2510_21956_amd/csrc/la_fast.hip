@@ -1437,10 +1437,12 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     return launch_status();
 }
 
+// dq_only: stop after the ascending sweep (dQ and the per-row o . dO); the caller wants dQ alone.
 template <typename T, int D>
 la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
-                   void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc)
+                   void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc,
+                   bool dq_only = false)
 {
     typedef BwdSlot<D> SL;
     constexpr int NT = FC<T, D>::NT;
@@ -1472,6 +1474,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
                                                        sinit_floats, dprime, pr.N, nseg,
                                                        pl.map, pl.slot_floats, pr.b);
     tc.mark("bwd_dq");
+    if (dq_only) return launch_status();
     // reverse-running sums left by the ascending sweep
     if (pr.causal) {
         if (nseg > 1) {
@@ -1517,6 +1520,22 @@ la_status fast_kv_totals(const Problem &pr, const Plan &pl, const void *K, const
         if (pr.D == 64) return fast_totals<__bf16, 64>(pr, pl, K, V, ws, st);
         if (pr.D == 128) return fast_totals<__bf16, 128>(pr, pl, K, V, ws, st);
     }
+    return LA_ERR_UNSUPPORTED;
+}
+
+la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                           const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                           float *ws, hipStream_t st)
+{
+    Tracer tc(nullptr, st);
+    if (pr.dt == LA_F32 && pr.D == 64)
+        return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
+    if (pr.dt == LA_F32 && pr.D == 128)
+        return fast_bwd<float, 128>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
+    if (pr.dt == LA_BF16 && pr.D == 64)
+        return fast_bwd<__bf16, 64>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
+    if (pr.dt == LA_BF16 && pr.D == 128)
+        return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
     return LA_ERR_UNSUPPORTED;
 }
 
