@@ -13,6 +13,8 @@ Functions (paper passages in the C file's comments):
   forward_def_rows                -- definition at selected rows of one slice
   decode                          -- incremental form with a carried state (App. B.1)
   grad_ab_def                     -- dL/da, dL/db by the definition
+  normalise_rows / normalise_rows_backward -- the row normalisation of Sec. 3.3
+  forward_qknorm / backward_qknorm -- attention on row-normalised Q, K, gradients for the raw Q, K
 """
 import ctypes
 import hashlib
@@ -78,6 +80,10 @@ def _load():
         lib.la_oracle_decode.restype = None
         lib.la_oracle_grad_ab_def.argtypes = [dp, dp, dp, dp, dp, L, L, I, F, F, I]
         lib.la_oracle_grad_ab_def.restype = None
+        lib.la_oracle_normalise_rows.argtypes = [dp, dp, L, I]
+        lib.la_oracle_normalise_rows.restype = None
+        lib.la_oracle_normalise_rows_backward.argtypes = [dp, dp, dp, L, I]
+        lib.la_oracle_normalise_rows_backward.restype = None
         lib.la_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -196,3 +202,39 @@ def grad_ab_def(Q, K, V, dO, a, b, causal):
         _load().la_oracle_grad_ab_def(_p(Q), _p(K), _p(V), _p(dO), _p(out), BH, N, D,
                                       float(a), float(b), int(bool(causal)))
     return float(out[0]), float(out[1])
+
+
+def normalise_rows(X):
+    """xhat = x / ||x|| for every row of X [..., D] (Sec. 3.3)."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    out = np.empty_like(X)
+    D = X.shape[-1]
+    if X.size:
+        _load().la_oracle_normalise_rows(_p(X), _p(out), X.size // D, D)
+    return out
+
+
+def normalise_rows_backward(X, dXhat):
+    """Gradient with respect to X of a loss whose gradient with respect to xhat is dXhat."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    dXhat = np.ascontiguousarray(dXhat, dtype=np.float64)
+    if dXhat.shape != X.shape:
+        raise ValueError("shape mismatch")
+    out = np.empty_like(X)
+    D = X.shape[-1]
+    if X.size:
+        _load().la_oracle_normalise_rows_backward(_p(X), _p(dXhat), _p(out), X.size // D, D)
+    return out
+
+
+def forward_qknorm(Q, K, V, a, b, causal):
+    """Row-normalise Q and K (Sec. 3.3), then the running-sum forward pass.  Returns (O, G)."""
+    return forward_rec(normalise_rows(Q), normalise_rows(K), V, a, b, causal)
+
+
+def backward_qknorm(Q, K, V, O, G, dO, a, b, causal):
+    """Gradients with respect to the raw Q, K (and V) of attention on row-normalised Q, K,
+    from the stored set {Q, K, V, O, g}: the running-sum backward pass on the normalised
+    rows, then the backward of the normalisation."""
+    dQh, dKh, dV = backward_rec(normalise_rows(Q), normalise_rows(K), V, O, G, dO, a, b, causal)
+    return normalise_rows_backward(Q, dQh), normalise_rows_backward(K, dKh), dV

@@ -362,3 +362,37 @@ void la_oracle_grad_ab_def(const double *Q, const double *K, const double *V,
     dab[0] = da;
     dab[1] = db;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Row normalisation of Q and K before the attention (Sec. 3.3): every row    */
+/* x is replaced by xhat = x / ||x||_2.  Backward of that map for one row:    */
+/* with the gradient dxhat with respect to xhat,                              */
+/*   dx = (dxhat - xhat (xhat . dxhat)) / ||x||                               */
+/* (the Jacobian of x / ||x|| is (I - xhat xhat^T) / ||x||).                  */
+/* X, Y: [rows, D].                                                           */
+/* ------------------------------------------------------------------------ */
+void la_oracle_normalise_rows(const double *X, double *Xhat, long rows, int D)
+{
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+        const double *x = X + i * D;
+        double nrm = 0.0;
+        for (int m = 0; m < D; ++m) nrm += x[m] * x[m];
+        nrm = __builtin_sqrt(nrm);
+        for (int m = 0; m < D; ++m) Xhat[i * D + m] = x[m] / nrm;
+    }
+}
+
+void la_oracle_normalise_rows_backward(const double *X, const double *dXhat, double *dX,
+                                       long rows, int D)
+{
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+        const double *x = X + i * D, *dh = dXhat + i * D;
+        double nrm = 0.0, proj = 0.0;
+        for (int m = 0; m < D; ++m) nrm += x[m] * x[m];
+        nrm = __builtin_sqrt(nrm);
+        for (int m = 0; m < D; ++m) proj += (x[m] / nrm) * dh[m];
+        for (int m = 0; m < D; ++m) dX[i * D + m] = (dh[m] - (x[m] / nrm) * proj) / nrm;
+    }
+}

@@ -335,3 +335,61 @@ def test_grad_ab(oracle_mod, causal):
         assert abs(a * da + b * db) < 1e-9 * (abs(a * da) + abs(b * db)) + 1e-11
         dq, _, _ = oracle_mod.backward_def(Q, K, V, dO, a, b, causal)
         np.testing.assert_allclose(np.sum(Q * dq), b * db, rtol=1e-9, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# row normalisation of Q and K (Sec. 3.3) and its backward
+# --------------------------------------------------------------------------
+def test_normalise_rows(oracle_mod):
+    rng = np.random.default_rng(17)
+    X = rng.standard_normal((3, 11, 7)) * 3.0
+    Xh = oracle_mod.normalise_rows(X)
+    np.testing.assert_allclose(np.linalg.norm(Xh, axis=-1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(Xh, X / np.linalg.norm(X, axis=-1, keepdims=True), rtol=1e-14)
+    np.testing.assert_allclose(oracle_mod.normalise_rows(5.0 * X), Xh, rtol=1e-14)  # scale-free
+    dXh = rng.standard_normal(X.shape)
+    dX = oracle_mod.normalise_rows_backward(X, dXh)
+    # library autograd through torch's own normalisation
+    tx = torch.tensor(X, requires_grad=True)
+    (torch.nn.functional.normalize(tx, dim=-1) * torch.tensor(dXh)).sum().backward()
+    np.testing.assert_allclose(dX, tx.grad.numpy(), rtol=1e-11, atol=1e-14)
+    # xhat depends on the direction of x only: the gradient is orthogonal to x
+    np.testing.assert_allclose(np.sum(dX * X, axis=-1), 0.0, atol=1e-13)
+    # hand case: x = (3, 4), dxhat = (1, 0): dx = ((1, 0) - (0.6, 0.8) 0.6) / 5
+    np.testing.assert_allclose(
+        oracle_mod.normalise_rows_backward(np.array([[3.0, 4.0]]), np.array([[1.0, 0.0]])),
+        [[0.128, -0.096]], rtol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_qknorm_composition(oracle_mod, causal):
+    """Attention on normalised rows with gradients for the raw rows: finite differences and
+    library autograd through normalisation + dense form."""
+    BH, N, D = 2, 9, 4
+    a, b = 1.0, 0.5
+    Q, K, V, dO = rand_inputs(BH, N, D, seed=91, normalise=False)
+    O, G = oracle_mod.forward_qknorm(Q, K, V, a, b, causal)
+    dQ, dK, dV = oracle_mod.backward_qknorm(Q, K, V, O, G, dO, a, b, causal)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    nq = torch.nn.functional.normalize(tq, dim=-1)
+    nk = torch.nn.functional.normalize(tk, dim=-1)
+    O_t, G_t = dense_augmented(nq, nk, tv, a, b, causal)
+    (O_t * torch.tensor(dO)).sum().backward()
+    np.testing.assert_allclose(O, O_t.detach().numpy(), rtol=1e-11, atol=1e-14)
+    for x, t in ((dQ, tq), (dK, tk), (dV, tv)):
+        np.testing.assert_allclose(x, t.grad.numpy(), rtol=1e-9, atol=1e-13)
+
+    def loss(q, k, v):
+        o, _ = oracle_mod.forward_qknorm(q, k, v, a, b, causal)
+        return float(np.sum(o * dO))
+
+    h = 1e-6
+    rng = np.random.default_rng(3)
+    for t, grad in enumerate((dQ, dK)):
+        for _ in range(6):
+            idx = tuple(rng.integers(0, s) for s in Q.shape)
+            args_p, args_m = [Q.copy(), K.copy(), V], [Q.copy(), K.copy(), V]
+            args_p[t][idx] += h
+            args_m[t][idx] -= h
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
+            np.testing.assert_allclose(grad[idx], fd, rtol=1e-5, atol=1e-8)
