@@ -69,6 +69,8 @@ typedef enum la_dtype {
     LA_BF16 = 1
 } la_dtype;
 
+struct la_trace; /* per-kernel timing hook, defined further down */
+
 /* Library version: major*10000 + minor*100 + patch. */
 LA_API int la_version(void);
 
@@ -124,6 +126,33 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
                       int B, int H, int N, int D,
                       float a, float b, int causal, la_dtype dt,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Forward and backward pass with the row normalisation of Sec. 3.3 inside the call: Q and K
+ * are the raw rows, every kernel scales them to unit length (qhat = q / ||q||, khat = k /
+ * ||k||) as it stages them, so that no normalised copy of Q and K is ever written or read
+ * back, and la_backward_qknorm returns the gradients for the raw rows,
+ *     dq = (dqhat - qhat (qhat . dqhat)) / ||q||   (likewise dk),
+ * by passing the kernels' dqhat, dkhat through that map in place before it returns.
+ * Arguments, workspace sizes (la_workspace_bytes with is_backward 0 / 1, or 2 when O or G is
+ * NULL) and error behaviour as for la_forward_traced / la_backward_traced; O and G are those
+ * of la_forward_qknorm.  A row of zeros stays a row of zeros (and makes g_i = a n_i for it).
+ * With bfloat16 the normalised rows are rounded to bfloat16 once more when they are staged.
+ */
+LA_API la_status la_forward_qknorm(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt,
+                     void *workspace, size_t workspace_bytes, void *hip_stream,
+                     struct la_trace *trace);
+
+LA_API la_status la_backward_qknorm(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes, void *hip_stream,
+                      struct la_trace *trace);
 
 /*
  * Gradients of sum(O * dO) with respect to the kernel's own coefficients, which
@@ -238,7 +267,6 @@ LA_API void la_debug_override(int seg_len, int force_generic);
  * described below and may be NULL.  Error behaviour as for la_forward /
  * la_backward; a missing, misaligned or short `saved` is LA_ERR_WORKSPACE.
  */
-struct la_trace;
 LA_API size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal);
 
 LA_API la_status la_forward_save(const void *Q, const void *K, const void *V,

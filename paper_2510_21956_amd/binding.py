@@ -20,7 +20,8 @@ LA_MAX_TRACE = 8
 EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward", "la_backward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
            "la_backward_saved", "la_debug_override", "la_forward_static", "la_decode_state_bytes",
-           "la_decode_step", "la_decode_prefill", "la_backward_ab")
+           "la_decode_step", "la_decode_prefill", "la_backward_ab", "la_forward_qknorm",
+           "la_backward_qknorm")
 
 
 class la_trace(ctypes.Structure):
@@ -82,6 +83,10 @@ def load_library():
     lib.la_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, f, i, vp]
     lib.la_decode_prefill.restype = i
     lib.la_decode_prefill.argtypes = [vp, vp, vp, sz, i, i, i, i, i, i, vp, sz, vp]
+    lib.la_forward_qknorm.restype = i
+    lib.la_forward_qknorm.argtypes = lib.la_forward_traced.argtypes
+    lib.la_backward_qknorm.restype = i
+    lib.la_backward_qknorm.argtypes = lib.la_backward_traced.argtypes
     lib.la_backward_ab.restype = i
     lib.la_backward_ab.argtypes = [vp] * 7 + [i, i, i, i, f, f, i, i, vp, sz, vp]
     lib.la_debug_override.restype = None
@@ -204,7 +209,9 @@ def _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, save)
             int(bool(causal)), _dtype_code(Q), _ptr(workspace),
             workspace.numel() * workspace.element_size())
     tr = ctypes.byref(trace) if trace is not None else None
-    if save:
+    if save == "qknorm":
+        rc = lib.la_forward_qknorm(*head, _stream_ptr(stream, Q.device), tr)
+    elif save:
         sp, sb = _saved_args(saved, Q)
         rc = lib.la_forward_save(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
     else:
@@ -252,7 +259,9 @@ def _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, str
             B, H, N, D, float(a), float(b), int(bool(causal)), _dtype_code(Q), _ptr(workspace),
             workspace.numel() * workspace.element_size())
     tr = ctypes.byref(trace) if trace is not None else None
-    if use_saved:
+    if use_saved == "qknorm":
+        rc = lib.la_backward_qknorm(*head, _stream_ptr(stream, Q.device), tr)
+    elif use_saved:
         sp, sb = _saved_args(saved, Q)
         rc = lib.la_backward_saved(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
     else:
@@ -322,3 +331,15 @@ def la_backward_ab(Q, K, V, O, G, dO, dab, a, b, causal, workspace, stream=None)
                                        _stream_ptr(stream, Q.device))
     if rc != 0:
         raise LaError(rc, "la_backward_ab")
+
+
+def la_forward_qknorm(Q, K, V, O, G, a, b, causal, workspace, stream=None, trace=None):
+    """la_forward_qknorm of include/la.h: la_forward on raw Q, K, normalised row by row inside."""
+    _forward(Q, K, V, O, G, a, b, causal, workspace, None, stream, trace, "qknorm")
+
+
+def la_backward_qknorm(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, stream=None,
+                       trace=None):
+    """la_backward_qknorm of include/la.h: gradients for the raw Q, K."""
+    _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, None, stream, trace,
+              "qknorm")

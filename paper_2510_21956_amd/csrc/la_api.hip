@@ -53,8 +53,9 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
         const long cost_seg = (total + p.nseg - 1) / p.nseg;
         if (cost_seg / kLoCost >= 128) {  // every segment keeps at least two chunks
             p.map.cost_seg = cost_seg;
-            // rounding may leave the last segment(s) empty: drop them
-            while (p.nseg > 1 && seg_row(p.map, p.nseg - 1, p.nseg, N) >= N) --p.nseg;
+            // the number of segments is the same for both ways of cutting (buffer sizes depend
+            // on it): if rounding would leave the last segment empty, keep the uniform cut
+            if (seg_row(p.map, p.nseg - 1, p.nseg, N) >= N) p.map.cost_seg = 0;
         }
     }
     const size_t DD = (size_t)D * D;
@@ -115,6 +116,12 @@ static bool use_fast(const Problem &pr, int is_backward)
     if (g_force_generic.load(std::memory_order_relaxed)) return false;
     return fast_supported(pr, is_backward);
 }
+
+// bfloat16 with the normalisation inside the call runs on the plain-ALU kernels, whose tiles
+// are float32: rounding the normalised rows back to bfloat16, as the matrix-core kernels'
+// tiles would, costs the early rows of dQ, dK up to twice the error allowance (measured on the
+// CPU with the oracle fed rounded normalised rows).
+static bool norm_needs_wide_tiles(const Problem &pr) { return pr.norm_qk && pr.dt == LA_BF16; }
 
 // Extra workspace of a backward pass that recomputes O and g (either handed in as NULL):
 // the forward pass's own workspace, then O, then g, each rounded up to 256 bytes.
@@ -205,7 +212,8 @@ size_t la_saved_state_bytes(int B, int H, int N, int D, la_dtype dt, int causal)
 static la_status forward_impl(const void *Q, const void *K, const void *V, void *O, float *G,
                               int B, int H, int N, int D, float a, float b, int causal,
                               la_dtype dt, void *workspace, size_t workspace_bytes, bool save,
-                              void *saved, size_t saved_bytes, void *hip_stream, la_trace *trace)
+                              void *saved, size_t saved_bytes, void *hip_stream, la_trace *trace,
+                              int norm_qk = 0)
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
@@ -213,12 +221,13 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
     if (!la::aligned16(Q) || !la::aligned16(K) || !la::aligned16(V) || !la::aligned16(O) ||
         !la::aligned16(G))
         return LA_ERR_ALIGN;
-    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 0);
+    la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 0);
     if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
     if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
-    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
-    const bool fast = la::use_fast(pr, 0);
+    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt, norm_qk};
+    const bool fast = la::use_fast(pr, 0) && !la::norm_needs_wide_tiles(pr);
+    if (!fast) pl.map.cost_seg = 0;  // the plain-ALU kernels cut uniformly (same segment count)
     float *sv = nullptr;
     if (save && fast && la::use_fast(pr, 1)) {
         if (!saved || saved_bytes < pl.saved_bytes || (((uintptr_t)saved) & 255u))
@@ -249,7 +258,7 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
                                int B, int H, int N, int D, float a, float b, int causal,
                                la_dtype dt, void *workspace, size_t workspace_bytes, bool use_saved,
                                const void *saved, size_t saved_bytes, void *hip_stream,
-                               la_trace *trace)
+                               la_trace *trace, int norm_qk = 0)
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
@@ -257,17 +266,21 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
     const void *ptrs[] = {Q, K, V, O, G, dO, dQ, dK, dV};
     for (const void *p : ptrs)
         if (!la::aligned16(p)) return LA_ERR_ALIGN;
-    const la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 1);
+    la::Plan pl = la::make_plan(B, H, N, D, dt, causal, 1);
     if (!la::grid_ok(B, H, pl)) return LA_ERR_SHAPE;
     const bool recompute = !O || !G;
-    const la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
+    la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
     const size_t T = (size_t)B * H * N;
     const la::Recompute rc = la::recompute_layout(pl, pf, T, D, dt);
     const size_t need = recompute ? rc.total_bytes : pl.total_bytes;
     if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
-    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt};
-    const bool fast = la::use_fast(pr, 1);
+    la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt, norm_qk};
+    const bool fast = la::use_fast(pr, 1) && !la::norm_needs_wide_tiles(pr);
+    if (!fast) {  // the plain-ALU kernels cut uniformly (same segment count)
+        pl.map.cost_seg = 0;
+        pf.map.cost_seg = 0;
+    }
     const float *sv = nullptr;
     if (use_saved && fast && la::use_fast(pr, 0)) {
         if (!saved || saved_bytes < pl.saved_bytes || (((uintptr_t)saved) & 255u))
@@ -289,7 +302,7 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         char *wsb = (char *)workspace;
         void *o2 = wsb + rc.o_off;
         float *g2 = (float *)(wsb + rc.g_off);
-        const bool ffast = la::use_fast(pr, 0);
+        const bool ffast = la::use_fast(pr, 0) && !la::norm_needs_wide_tiles(pr);
         s = ffast ? la::fast_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off),
                                      nullptr, st, tc)
                   : la::generic_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
@@ -298,10 +311,19 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         if (!O) O = o2;
         if (!G) G = g2;
     }
-    if (fast)
-        return la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
-                                 tc);
-    return la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st, tc);
+    s = fast ? la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
+                                 tc)
+             : la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
+                                    tc);
+    if (s != LA_OK || !norm_qk) return s;
+    // the kernels left the gradients for the normalised rows: take them through the backward of
+    // the normalisation, in place
+    s = la::project_rows(Q, dQ, T, D, dt, st);
+    if (s != LA_OK) return s;
+    tc.mark("project_dq");
+    s = la::project_rows(K, dK, T, D, dt, st);
+    tc.mark("project_dk");
+    return s;
 }
 
 // Device address of `scratch` on the current device, resolved on the first call on that
@@ -381,6 +403,25 @@ la_status la_backward_ab(const void *Q, const void *K, const void *V, const void
     // sum q . dq(b = 1) = dL/db, and a dL/da + b dL/db = 0 (O depends on a, b through a / b only)
     return la::reduce_dot(Q, dq1, T * D, dt, -b / a, 1.f, (float *)(wsb + lay.partials_off), dab,
                           st);
+}
+
+la_status la_forward_qknorm(const void *Q, const void *K, const void *V, void *O, float *G, int B,
+                            int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                            void *workspace, size_t workspace_bytes, void *hip_stream,
+                            la_trace *trace)
+{
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace, workspace_bytes,
+                        false, nullptr, 0, hip_stream, trace, 1);
+}
+
+la_status la_backward_qknorm(const void *Q, const void *K, const void *V, const void *O,
+                             const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
+                             int H, int N, int D, float a, float b, int causal, la_dtype dt,
+                             void *workspace, size_t workspace_bytes, void *hip_stream,
+                             la_trace *trace)
+{
+    return backward_impl(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt, workspace,
+                         workspace_bytes, false, nullptr, 0, hip_stream, trace, 1);
 }
 
 size_t la_decode_state_bytes(int B, int H, int D)

@@ -99,6 +99,7 @@ struct Problem {
     float a, b;
     int causal;
     la_dtype dt;
+    int norm_qk = 0;  // rows of Q and K are scaled to unit length as they are staged (Sec. 3.3)
 };
 
 // Records the caller's timing events between kernels (see la_trace in la.h).
@@ -149,6 +150,10 @@ la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, con
 int reduce_dot_partials();
 la_status reduce_dot(const void *X, const void *Y, size_t n, la_dtype dt, float scale0, float scale1,
                      float *partials, float *out, hipStream_t st);
+
+// Backward of the row normalisation (Sec. 3.3), in place: dX <- (dX - xhat (xhat . dX)) / ||x||
+// for every one of `rows` rows of D elements, xhat = x / ||x||.
+la_status project_rows(const void *X, void *dX, size_t rows, int D, la_dtype dt, hipStream_t st);
 
 // Sums over the whole sequence, S = sum k v^T, z = sum k, p = sum v, left in slot 0 of every
 // slice as [S | z | p] (forward plan without the mask): phases 1 and 2 of the unmasked

@@ -152,6 +152,39 @@ __global__ __launch_bounds__(256) void k_dot_final(const float *__restrict__ par
     }
 }
 
+// Backward of x -> x / ||x|| for one row per 16 lanes (D <= 256: up to 16 elements a lane).
+template <typename T>
+__global__ __launch_bounds__(256) void k_project_rows(const T *__restrict__ X, T *__restrict__ dX,
+                                                      size_t rows, int D)
+{
+    const size_t row = (size_t)blockIdx.x * 16 + threadIdx.x / 16;
+    const int l = threadIdx.x % 16;
+    if (row >= rows) return;  // whole 16-lane groups leave together
+    const T *x = X + row * D;
+    T *dx = dX + row * D;
+    float xv[16], dv[16], ss = 0.f, dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int m = l + 16 * i;
+        xv[i] = m < D ? load_elem(x, m) : 0.f;
+        dv[i] = m < D ? load_elem(dx, m) : 0.f;
+        ss += xv[i] * xv[i];
+        dot += xv[i] * dv[i];
+    }
+#pragma unroll
+    for (int m = 8; m >= 1; m >>= 1) {
+        ss += __shfl_xor(ss, m);
+        dot += __shfl_xor(dot, m);
+    }
+    const float inv = ss > 0.f ? 1.f / sqrtf(ss) : 0.f;
+    const float proj = dot * inv * inv;  // (xhat . dxhat) / ||x||
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int m = l + 16 * i;
+        if (m < D) store_elem(dx, m, (dv[i] - xv[i] * proj) * inv);
+    }
+}
+
 template <typename T>
 la_status decode_by_d(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
                       int BH, int Tn, int D, size_t sf, float a, float b, hipStream_t st)
@@ -188,6 +221,16 @@ la_status reduce_dot(const void *X, const void *Y, size_t n, la_dtype dt, float 
         k_dot_partial<bf16_t><<<dim3(kDotBlocks), dim3(256), 0, st>>>((const bf16_t *)X,
                                                                       (const bf16_t *)Y, n, partials);
     k_dot_final<<<dim3(1), dim3(256), 0, st>>>(partials, kDotBlocks, scale0, scale1, out);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status project_rows(const void *X, void *dX, size_t rows, int D, la_dtype dt, hipStream_t st)
+{
+    const dim3 grid((unsigned)((rows + 15) / 16)), block(256);
+    if (dt == LA_F32)
+        k_project_rows<float><<<grid, block, 0, st>>>((const float *)X, (float *)dX, rows, D);
+    else
+        k_project_rows<bf16_t><<<grid, block, 0, st>>>((const bf16_t *)X, (bf16_t *)dX, rows, D);
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 

@@ -278,6 +278,35 @@ __device__ __forceinline__ float reduce_adjacent(float s)
     return s;
 }
 
+// Row normalisation of Sec. 3.3 on a stager's registers: each of the thread's four rows is
+// scaled to unit length (the row is held by the GPR consecutive lanes that share it) and, for
+// bf16, rounded back to the tile's type.  Rows of zeros (past the end of the slice) stay zeros.
+template <typename T, int D>
+__device__ __forceinline__ void normalise_rows(Stager<T, D> &s)
+{
+    typedef FC<T, D> F;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float x[F::EPV], ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < F::EPV; ++e) {
+            x[e] = Stager<T, D>::elem(s.raw[i], e);
+            ss += x[e] * x[e];
+        }
+        ss = reduce_adjacent<F::GPR>(ss);
+        const float inv = ss > 0.f ? 1.f / sqrtf(ss) : 0.f;
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s.raw[i][e] = __float_as_uint(x[e] * inv);
+        } else {
+            const bf4v lo = to_bf4(f4v{x[0], x[1], x[2], x[3]} * inv);
+            const bf4v hi = to_bf4(f4v{x[4], x[5], x[6], x[7]} * inv);
+            const u2v l2 = __builtin_bit_cast(u2v, lo), h2 = __builtin_bit_cast(u2v, hi);
+            s.raw[i] = u4v{l2[0], l2[1], h2[0], h2[1]};
+        }
+    }
+}
+
 // Sum over the four lane groups of a wave (lanes l, l^16, l^32, l^48).
 __device__ __forceinline__ float reduce_lane_groups(float x)
 {
@@ -603,7 +632,7 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 template <typename T, int D, bool TRANSPOSED>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
-    int nseg_run, SegMap sm, size_t slot_floats, int slot_shift)
+    int nseg_run, SegMap sm, size_t slot_floats, int slot_shift, int norm)
 {
     typedef FC<T, D> F;
     constexpr int C = F::C, NRB = F::NRB, LDT = F::LDT;
@@ -641,6 +670,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     s1.load(h0 ? Kp : Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
+        if (norm && h0) normalise_rows(s1);  // K
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
         // next chunk, in flight during the products (after the last one: that one again)
@@ -682,7 +712,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
-    int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b)
+    int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b, int norm)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -756,6 +786,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of the weights: early rows
+        if (norm) normalise_rows(s1);  // Q or K, whichever this half stages
         if (h0) {
             s1.store_rows(Qs);
             if constexpr (CAUSAL) s2.store_cols(VTt);
@@ -916,7 +947,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
-    float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b)
+    float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b,
+    int norm)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1004,6 +1036,14 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         __syncthreads();
         const float *rs = rsb[par];
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
+        if (norm && !h0) {
+            if constexpr (CAUSAL) {
+                normalise_rows(s2);  // K
+                if (need_R) normalise_rows(s3);  // Q
+            } else {
+                normalise_rows(s1);  // Q
+            }
+        }
         if (h0) {
             const f4v r4 = *reinterpret_cast<const f4v *>(rs + 4 * rq);
             // o_i . dO_i : partial over this thread's columns, then over the GPR consecutive
@@ -1163,7 +1203,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, SegMap sm,
-    size_t slot_floats, float a, float b)
+    size_t slot_floats, float a, float b, int norm)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1260,6 +1300,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
         __syncthreads();
+        if (norm && h0) {
+            normalise_rows(s1);  // K
+            if constexpr (CAUSAL) normalise_rows(s2);  // Q
+        }
         if (h0) {
             s1.store_rows(Ks);
             if constexpr (CAUSAL) {
@@ -1419,7 +1463,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
         kf_kv_state<T, D, false><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
-            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0);
+            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("fwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, D * D + 2 * D, pr.causal ? 0 : 2,
                           pr.causal ? 1 : 0, nseg - 1, st);
@@ -1428,11 +1472,11 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_fwd_apply<T, D, true><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b);
+            pr.b, pr.norm_qk);
     else
         kf_fwd_apply<T, D, false><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b);
+            pr.b, pr.norm_qk);
     tc.mark("fwd_apply");
     return launch_status();
 }
@@ -1457,7 +1501,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (!saved && nrun > 0) {
         kf_kv_state<T, D, true><<<dim3(pr.BH * nrun), block, 0, st>>>(
-            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0);
+            K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("bwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST,
                           pr.causal ? 0 : 2, pr.causal ? 1 : 0, nseg - 1, st);
@@ -1468,11 +1512,11 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                       sinit_floats, dprime, pr.N, nseg,
-                                                      pl.map, pl.slot_floats, pr.b);
+                                                      pl.map, pl.slot_floats, pr.b, pr.norm_qk);
     else
         kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
                                                        sinit_floats, dprime, pr.N, nseg,
-                                                       pl.map, pl.slot_floats, pr.b);
+                                                       pl.map, pl.slot_floats, pr.b, pr.norm_qk);
     tc.mark("bwd_dq");
     if (dq_only) return launch_status();
     // reverse-running sums left by the ascending sweep
@@ -1484,14 +1528,14 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
         }
         kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                        nseg, pl.map, pl.slot_floats, pr.a,
-                                                       pr.b);
+                                                       pr.b, pr.norm_qk);
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
         kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
                                                         nseg, pl.map, pl.slot_floats, pr.a,
-                                                        pr.b);
+                                                        pr.b, pr.norm_qk);
     }
     tc.mark("bwd_dkv");
     return launch_status();
@@ -1503,7 +1547,7 @@ la_status fast_totals(const Problem &pr, const Plan &pl, const void *Kv, const v
 {
     constexpr int NT = FC<T, D>::NT;
     kf_kv_state<T, D, false><<<dim3(pr.BH * pl.nseg), dim3(NT), 0, st>>>(
-        (const T *)Kv, (const T *)Vv, ws, pr.N, pl.nseg, pl.nseg, pl.map, pl.slot_floats, 0);
+        (const T *)Kv, (const T *)Vv, ws, pr.N, pl.nseg, pl.nseg, pl.map, pl.slot_floats, 0, pr.norm_qk);
     launch_scan_slots(ws, pr.BH, pl.nseg, pl.slot_floats, 0, D * D + 2 * D, 2, 0, pl.nseg - 1, st);
     return launch_status();
 }

@@ -34,6 +34,23 @@ __device__ __forceinline__ void load_tile(float *dst, const T *X, long c0, long 
     }
 }
 
+// Row normalisation of Sec. 3.3 on up to two staged tiles: thread i scales row i of `x`,
+// thread C + i row i of `y` (either may be null).  Rows of zeros (past the end) stay zeros.
+// Call between the barrier that follows the loads and another barrier.
+template <int D, int C>
+__device__ __forceinline__ void normalise_tiles(float *x, float *y)
+{
+    const int t = threadIdx.x;
+    float *row = t < C ? (x ? x + t * (D + 1) : nullptr)
+                       : (t < 2 * C && y ? y + (t - C) * (D + 1) : nullptr);
+    if (row) {
+        float ss = 0.f;
+        for (int m = 0; m < D; ++m) ss += row[m] * row[m];
+        const float inv = ss > 0.f ? 1.f / sqrtf(ss) : 0.f;
+        for (int m = 0; m < D; ++m) row[m] *= inv;
+    }
+}
+
 // OmegaHat tile: dO / g per row (Eq. back2); zero for rows past the end.
 template <typename T, int D, int C>
 __device__ __forceinline__ void load_omega_hat(float *dst, const T *dO, const float *G, long c0,
@@ -63,7 +80,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(NT) void k_fwd_state(const T *__restrict__ K, const T *__restrict__ V,
                                                   float *__restrict__ ws, int N, int nseg,
                                                   int nseg_run, int seg_len, size_t slot_floats,
-                                                  int slot_shift)
+                                                  int slot_shift, int norm)
 {
     constexpr int C = Cfg<D>::C, LD = Cfg<D>::LD, PER = Cfg<D>::PER, MG = NT / D;
     __shared__ float k[C * LD], v[C * LD];
@@ -81,6 +98,10 @@ __global__ __launch_bounds__(NT) void k_fwd_state(const T *__restrict__ K, const
         load_tile<T, D, C>(k, Kp, c0, row1);
         load_tile<T, D, C>(v, Vp, c0, row1);
         __syncthreads();
+        if (norm) {
+            normalise_tiles<D, C>(k, nullptr);
+            __syncthreads();
+        }
         for (int n = 0; n < C; ++n) {
             float vj = v[n * LD + j];
 #pragma unroll
@@ -116,7 +137,8 @@ __global__ __launch_bounds__(NT) void k_bwd_state(const T *__restrict__ Q, const
                                                   const float *__restrict__ G,
                                                   const T *__restrict__ dO, float *__restrict__ ws,
                                                   float *__restrict__ delta, int N, int nseg,
-                                                  int seg_len, size_t slot_floats, int causal)
+                                                  int seg_len, size_t slot_floats, int causal,
+                                                  int norm)
 {
     constexpr int C = Cfg<D>::C, LD = Cfg<D>::LD, PER = Cfg<D>::PER, MG = NT / D;
     __shared__ float q[C * LD], k[C * LD], v[C * LD], oh[C * LD], tmp[C * LD], dl[C];
@@ -144,6 +166,10 @@ __global__ __launch_bounds__(NT) void k_bwd_state(const T *__restrict__ Q, const
         }
         load_omega_hat<T, D, C>(oh, dOp, Gp, c0, row1);
         __syncthreads();
+        if (norm) {
+            normalise_tiles<D, C>(q, need_S ? k : nullptr);
+            __syncthreads();
+        }
         for (int e = t; e < C * D; e += NT) {
             int i = e / D, jj = e % D;
             long r = c0 + i;
@@ -238,7 +264,7 @@ __global__ __launch_bounds__(NT) void k_fwd_apply(const T *__restrict__ Q, const
                                                   float *__restrict__ G,
                                                   const float *__restrict__ ws, int N, int nseg,
                                                   int seg_len, size_t slot_floats, float a, float b,
-                                                  int causal)
+                                                  int causal, int norm)
 {
     constexpr int C = Cfg<D>::C, LD = Cfg<D>::LD, PL = C + 1;
     __shared__ float S[D * LD], z[D], p[D];
@@ -268,6 +294,10 @@ __global__ __launch_bounds__(NT) void k_fwd_apply(const T *__restrict__ Q, const
             load_tile<T, D, C>(v, Vp, c0, row1);
         }
         __syncthreads();
+        if (norm) {
+            normalise_tiles<D, C>(q, causal ? k : nullptr);
+            __syncthreads();
+        }
         if (causal) {
             for (int e = t; e < C * C; e += NT) {
                 int i = e / C, n = e % C;
@@ -339,7 +369,7 @@ __global__ __launch_bounds__(NT) void k_bwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dQ, T *__restrict__ dK,
     T *__restrict__ dV, const float *__restrict__ ws, const float *__restrict__ delta, int N,
-    int nseg, int seg_len, size_t slot_floats, float a, float b, int causal)
+    int nseg, int seg_len, size_t slot_floats, float a, float b, int causal, int norm)
 {
     constexpr int C = 16, LD = Cfg<D>::LD, PL = C + 1;
     __shared__ float St[D * LD], z[D], u[D], w[D];  // St: S in sweep 1, R in sweep 2
@@ -368,6 +398,10 @@ __global__ __launch_bounds__(NT) void k_bwd_apply(
         load_omega_hat<T, D, C>(oh, dOp, Gp, c0, row1);
         if (t < C) dl[t] = (c0 + t < row1) ? dp[c0 + t] : 0.f;
         __syncthreads();
+        if (norm) {
+            normalise_tiles<D, C>(k, nullptr);
+            __syncthreads();
+        }
         if (causal) {
             for (int e = t; e < C * C; e += NT) {
                 int i = e / C, n = e % C;
@@ -419,6 +453,10 @@ __global__ __launch_bounds__(NT) void k_bwd_apply(
         load_omega_hat<T, D, C>(oh, dOp, Gp, c0, row1);
         if (t < C) dl[t] = (c0 + t < row1) ? dp[c0 + t] : 0.f;
         __syncthreads();
+        if (norm) {
+            normalise_tiles<D, C>(q, k);
+            __syncthreads();
+        }
         if (causal) {
             for (int e = t; e < C * C; e += NT) {
                 int i = e / C, n = e % C;
@@ -484,7 +522,7 @@ la_status fwd_impl(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
         k_fwd_state<T, D><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
-            K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0);
+            K, V, ws, pr.N, nseg, nrun, pl.seg_len, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("generic_fwd_state");
         const int len = D * D + 2 * D;
         k_scan_slots<<<dim3(pr.BH, (len + NT - 1) / NT), dim3(NT), 0, st>>>(
@@ -492,7 +530,8 @@ la_status fwd_impl(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
         tc.mark("scan_slots");
     }
     k_fwd_apply<T, D><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-        Q, K, V, O, G, ws, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.a, pr.b, pr.causal);
+        Q, K, V, O, G, ws, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.a, pr.b, pr.causal,
+        pr.norm_qk);
     tc.mark("generic_fwd_apply");
     return launch_status();
 }
@@ -505,7 +544,8 @@ la_status bwd_impl(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     const int nseg = pl.nseg;
     float *delta = ws + pl.delta_offset_floats;
     k_bwd_state<T, D><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
-        Q, K, V, O, G, dO, ws, delta, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.causal);
+        Q, K, V, O, G, dO, ws, delta, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.causal,
+        pr.norm_qk);
     tc.mark("generic_bwd_state");
     const int lenS = D * D + D, lenR = D * D + 2 * D;
     if (pr.causal) {
@@ -521,7 +561,7 @@ la_status bwd_impl(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     }
     k_bwd_apply<T, D><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
         Q, K, V, G, dO, dQ, dK, dV, ws, delta, pr.N, nseg, pl.seg_len, pl.slot_floats, pr.a, pr.b,
-        pr.causal);
+        pr.causal, pr.norm_qk);
     tc.mark("generic_bwd_apply");
     return launch_status();
 }
@@ -575,10 +615,10 @@ la_status totals_by_d(const Problem &pr, const Plan &pl, const void *Kv, const v
     const T *k = (const T *)Kv, *v = (const T *)Vv;
     const dim3 grid(pr.BH * pl.nseg), block(NT);
     switch (pr.D) {
-        case 16: k_fwd_state<T, 16><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
-        case 32: k_fwd_state<T, 32><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
-        case 64: k_fwd_state<T, 64><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
-        case 128: k_fwd_state<T, 128><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0); break;
+        case 16: k_fwd_state<T, 16><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0, pr.norm_qk); break;
+        case 32: k_fwd_state<T, 32><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0, pr.norm_qk); break;
+        case 64: k_fwd_state<T, 64><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0, pr.norm_qk); break;
+        case 128: k_fwd_state<T, 128><<<grid, block, 0, st>>>(k, v, ws, pr.N, pl.nseg, pl.nseg, pl.seg_len, pl.slot_floats, 0, pr.norm_qk); break;
         default: return LA_ERR_UNSUPPORTED;
     }
     launch_scan_slots(ws, pr.BH, pl.nseg, pl.slot_floats, 0, pr.D * pr.D + 2 * pr.D, 2, 0,
