@@ -16,7 +16,7 @@ static std::atomic<int> g_force_generic{0};
 
 static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
-static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128; }
+static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128 || D == 256; }
 
 // Segment length.  The masked apply kernels keep one (D = 128) or two (fp32, D = 64)
 // workgroups resident per compute unit (the unmasked ones, which hold no tiles of K and
@@ -30,7 +30,7 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     Plan p;
     const long BH = (long)B * H;
     const int min_len = (D >= 128) ? 512 : 256;
-    const long resident = !causal ? 4 : (dt == LA_F32 && D <= 64) ? 2 : 1;
+    const long resident = D == 256 ? 1 : !causal ? 4 : (dt == LA_F32 && D <= 64) ? 2 : 1;
     const long target = 256 * resident;
     long want = (target + BH / 2) / BH;  // nearest number of segments per slice
     long max_by_len = N / min_len;
@@ -192,7 +192,8 @@ size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal, i
     if (!la::grid_ok(B, H, pl)) return 0;
     if (is_backward == 3) {
         la::Problem pr{B * H, N, D, 1.f, 1.f, causal ? 1 : 0, dt};
-        return la::ab_layout(pl, (size_t)B * H * N, D, dt, la::use_fast(pr, 1)).total_bytes;
+        return la::ab_layout(pl, (size_t)B * H * N, D, dt, la::use_fast(pr, 1) || D == 256)
+            .total_bytes;
     }
     if (is_backward != 2) return pl.total_bytes;
     const la::Plan pf = la::make_plan(B, H, N, D, dt, causal, 0);
@@ -217,6 +218,7 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
+    if (norm_qk && D == 256) return LA_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !O) return LA_ERR_NULL;
     if (!la::aligned16(Q) || !la::aligned16(K) || !la::aligned16(V) || !la::aligned16(O) ||
         !la::aligned16(G))
@@ -247,6 +249,9 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
     if (fast)
         return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace, sv,
                                 (hipStream_t)hip_stream, tc);
+    if (D == 256)
+        return la::wide_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
+                                (hipStream_t)hip_stream, tc);
     return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
                                (hipStream_t)hip_stream, tc);
 }
@@ -262,6 +267,7 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
+    if (norm_qk && D == 256) return LA_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return LA_ERR_NULL;
     const void *ptrs[] = {Q, K, V, O, G, dO, dQ, dK, dV};
     for (const void *p : ptrs)
@@ -305,16 +311,20 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         const bool ffast = la::use_fast(pr, 0) && !la::norm_needs_wide_tiles(pr);
         s = ffast ? la::fast_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off),
                                      nullptr, st, tc)
-                  : la::generic_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
-                                        tc);
+            : D == 256
+                ? la::wide_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st, tc)
+                : la::generic_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
+                                      tc);
         if (s != LA_OK) return s;
         if (!O) O = o2;
         if (!G) G = g2;
     }
     s = fast ? la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
                                  tc)
-             : la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
-                                    tc);
+        : D == 256
+            ? la::wide_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st, tc)
+            : la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
+                                   tc);
     if (s != LA_OK || !norm_qk) return s;
     // the kernels left the gradients for the normalised rows: take them through the backward of
     // the normalisation, in place
@@ -379,7 +389,7 @@ la_status la_backward_ab(const void *Q, const void *K, const void *V, const void
     la::Problem pr{B * H, N, D, a, 1.f, causal ? 1 : 0, dt};
     const bool fast = la::use_fast(pr, 1);
     const size_t T = (size_t)B * H * N;
-    const la::AbLayout lay = la::ab_layout(pl, T, D, dt, fast);
+    const la::AbLayout lay = la::ab_layout(pl, T, D, dt, fast || D == 256);
     if (!workspace || workspace_bytes < lay.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     {
@@ -394,6 +404,10 @@ la_status la_backward_ab(const void *Q, const void *K, const void *V, const void
     void *dq1 = wsb + lay.dq_off;
     if (fast) {
         s = la::fast_backward_dq(pr, pl, Q, K, V, O, G, dO, dq1, (float *)workspace, st);
+    } else if (D == 256) {
+        la::Tracer tc(nullptr, st);
+        s = la::wide_backward(pr, pl, Q, K, V, O, G, dO, dq1, nullptr, nullptr, (float *)workspace,
+                              st, tc);
     } else {
         la::Tracer tc(nullptr, st);
         s = la::generic_backward(pr, pl, Q, K, V, O, G, dO, dq1, wsb + lay.dk_off,
@@ -427,7 +441,7 @@ la_status la_backward_qknorm(const void *Q, const void *K, const void *V, const 
 size_t la_decode_state_bytes(int B, int H, int D)
 {
     if (B < 1 || H < 1 || (double)B * H > 2147483647.0 / 4096.0) return 0;
-    if (!la::supported_d(D) && D != 256) return 0;
+    if (!la::supported_d(D)) return 0;
     return (size_t)B * H * la::decode_state_floats(D) * 4;
 }
 
@@ -439,7 +453,7 @@ la_status la_decode_step(const void *q, const void *k, const void *v, void *o, f
         return LA_ERR_SHAPE;
     if ((double)B * H * T * D >= 1099511627776.0) return LA_ERR_SHAPE;
     if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_UNSUPPORTED;
-    if (!la::supported_d(D) && D != 256) return LA_ERR_UNSUPPORTED;
+    if (!la::supported_d(D)) return LA_ERR_UNSUPPORTED;
     if (!q || !k || !v || !o) return LA_ERR_NULL;
     const void *ptrs[] = {q, k, v, o, g, state};
     for (const void *p : ptrs)
@@ -462,6 +476,7 @@ la_status la_decode_prefill(const void *K, const void *V, float *state, size_t s
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
+    if (D == 256) return LA_ERR_UNSUPPORTED;
     if (!K || !V) return LA_ERR_NULL;
     if (!la::aligned16(K) || !la::aligned16(V)) return LA_ERR_ALIGN;
     const size_t need = la_decode_state_bytes(B, H, D);

@@ -170,6 +170,14 @@ la_status decode_step(const void *Q, const void *K, const void *V, void *O, floa
 la_status state_from_totals(const float *ws, float *state, int BH, int D, int nseg,
                             size_t slot_floats, int N, int accumulate, hipStream_t st);
 
+// Head size 256 (la_wide.hip): token-serial kernels with the state in registers.
+// wide_backward with dK == nullptr runs the ascending sweep (dQ) only.
+la_status wide_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                       const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
+la_status wide_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                        const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                        void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
+
 // Generic (plain-ALU, any supported D) path.
 la_status generic_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                           const void *V, void *O, float *G, float *ws, hipStream_t st,

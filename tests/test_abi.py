@@ -46,6 +46,7 @@ def test_workspace_bytes(lib):
     assert la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 1) > \
         la.la_workspace_bytes(4, 16, 4096, 64, la.LA_F32, 1, 0)
     assert la.la_workspace_bytes(4, 16, 4096, 48, la.LA_F32, 1, 0) == 0      # unsupported D
+    assert la.la_workspace_bytes(4, 16, 4096, 256, la.LA_F32, 1, 1) > 0
     assert la.la_workspace_bytes(0, 16, 4096, 64, la.LA_F32, 1, 0) == 0      # bad shape
     assert la.la_workspace_bytes(1, 1, 1, 64, 7, 1, 0) == 0                  # bad dtype
     # size limits: B*H*N*D < 2^40 elements, B*H < 2^31 / 4096

@@ -19,7 +19,7 @@ def la():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("D", [16, 32, 64, 128])
+@pytest.mark.parametrize("D", [16, 32, 64, 128, 256])
 def test_grad_ab(oracle_mod, la, D, dtype):
     """Short forced segments (several segments, ragged tail); b = 0 included: the sweep runs
     with unit b, so the gradient with respect to b exists there as well.

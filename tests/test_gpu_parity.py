@@ -85,6 +85,8 @@ SMALL = [
     # matrix-core path at its edges: a single row, one short chunk, one row past a chunk,
     # exactly one chunk, one row past a 64-row segment boundary
     (1, 1, 1, 64), (1, 1, 31, 64), (1, 2, 33, 128), (1, 1, 64, 64), (3, 1, 65, 64), (1, 1, 1, 128),
+    # head size 256 (token-serial kernels)
+    (1, 1, 1, 256), (1, 2, 70, 256), (2, 1, 300, 256),
 ]
 
 
@@ -116,7 +118,7 @@ COEFS = [(2.0, -0.7), (0.5, 0.0), (1.0, 0.9), (1.0, 1.0)]
 
 @pytest.mark.parametrize("ab", COEFS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("D", [32, 64, 128])
+@pytest.mark.parametrize("D", [32, 64, 128, 256])
 def test_other_coefficients(oracle_mod, la, knobs, D, dtype, ab):
     knobs(64, 0)
     a, b = ab
@@ -211,7 +213,8 @@ PAPER = [("paper_causal_f32_B4_H16_N1000_D128", [0, 21, 63]),
          ("paper_causal_f32_B4_H16_N10000_D128", [0, 40]),
          ("paper_causal_f32_B4_H16_N4096_D32", [0, 50]),
          ("paper_causal_f32_B4_H16_N4096_D64", [7]),
-         ("paper_causal_f32_B4_H16_N4096_D128", [63])]
+         ("paper_causal_f32_B4_H16_N4096_D128", [63]),
+         ("paper_causal_f32_B4_H16_N4096_D256", [17])]
 
 
 @pytest.mark.parametrize("name,slices", PAPER)
