@@ -8,7 +8,7 @@
 // phases as the other paths: per-segment sums, scan over the segments, apply.
 //
 // All four sweeps are one kernel.  With a state M[x][y] (thread t owns column y = t % D of
-// the rows x = t / D + RG i), two vectors and three per-row operands A[x], B[y], C[x]:
+// the D / RG consecutive rows x = (t / D) D / RG + i), two vectors and three per-row operands A[x], B[y], C[x]:
 //     update    M[x][y] += A[x] B[y],  yvec[y] += wB B[y],  xvec[x] += wA A[x]
 //     readout   lin[y] = sum_x M[x][y] C[x]
 //   forward  (ascending)   A = k, B = v, C = q        M = S,   yvec = p, xvec = z
@@ -37,10 +37,28 @@ __device__ __forceinline__ float wsum(float x)
     return x;
 }
 
+// Four consecutive elements of a row as floats.
+__device__ __forceinline__ void load4(const float *p, float (&x)[4])
+{
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+}
+__device__ __forceinline__ void load4(const bf16_t *p, float (&x)[4])
+{
+    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+
 // State slot: [M (D*D, row x column y) | yvec (D) | xvec (D)].
 // pass 0: sums of this segment's rows -> slot `seg + slot_shift`;  pass 1: apply.
 // load_t: the slot holds the matrix transposed and the wanted vector in its xvec part (dK
 // starts from the sums the dV-shaped phase 1 left).
+//
+// Rows are staged WCH = 16 at a time: wave w of the sixteen fetches row w of the group (one
+// 4-element vector a lane), so that the memory latency is paid once per group, not once per
+// row; row factors (1/g, delta) are applied as the group is written to LDS, and o . dO of a
+// row is a reduction inside its wave.
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(WNT) void k_wide(const T *__restrict__ XA, const T *__restrict__ XB,
                                               const T *__restrict__ XC, const T *__restrict__ Oin,
@@ -51,12 +69,18 @@ __global__ __launch_bounds__(WNT) void k_wide(const T *__restrict__ XA, const T 
                                               int slot_shift, float a, float b, int causal,
                                               int pass, int load_t)
 {
-    constexpr int RG = WNT / D, RPT = D / RG;
+    // a workgroup owns YC = D / 2 columns of the state (the two halves of a (slice, segment)
+    // are neighbouring workgroups): 32 state floats a thread instead of 64, which is what
+    // lets the state stay in registers next to everything else
+    constexpr int YC = D / 2, RG = WNT / YC, RPT = D / RG, WCH = WNT / 64;
+    static_assert(D == 4 * 64, "one wave stages one row, four elements a lane");
     constexpr bool DESC = MODE == W_DK || MODE == W_DV;
     constexpr bool OMEGA_A = MODE == W_DK, OMEGA_B = MODE == W_DV, OMEGA_C = MODE == W_DQ;
-    __shared__ float As[D], Bs[D], Cs[D], xv[D], part[RG][D], red[WNT / 64], sc[2];
-    const int bh = blockIdx.x / nseg_run, seg = seg0 + blockIdx.x % nseg_run;
-    const int t = threadIdx.x, y = t % D, rg = t / D;
+    __shared__ __align__(16) float Ach[WCH][D], Bch[WCH][D], Cch[WCH][D];
+    __shared__ float xv[D], part[2][RG][YC], red[WNT / 64], dlt[WCH], qz;
+    const int half = blockIdx.x % 2, sblk = blockIdx.x / 2;
+    const int bh = sblk / nseg_run, seg = seg0 + sblk % nseg_run;
+    const int t = threadIdx.x, yl = t % YC, y = half * YC + yl, rg = t / YC, wv = t / 64, l = t % 64;
     const size_t base = (size_t)bh * N * D;
     const long row0 = (long)seg * seg_len;
     const long row1 = (row0 + seg_len < N) ? row0 + seg_len : N;
@@ -73,7 +97,7 @@ __global__ __launch_bounds__(WNT) void k_wide(const T *__restrict__ XA, const T 
         const float *slot = ws + ((size_t)bh * nseg + (causal ? seg : 0)) * slot_floats + slot_off;
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
-            const int x = rg + RG * i;
+            const int x = rg * RPT + i;
             M[i] = load_t ? slot[(size_t)y * D + x] : slot[(size_t)x * D + y];
         }
         yvec = slot[D * D + (load_t ? D : 0) + y];
@@ -81,90 +105,137 @@ __global__ __launch_bounds__(WNT) void k_wide(const T *__restrict__ XA, const T 
     }
     float cnt = causal ? (float)row0 : (float)N;  // rows summed so far (forward pass)
 
-    for (long k = 0; k < row1 - row0; ++k) {
-        const long i = DESC ? row1 - 1 - k : row0 + k;
-        __syncthreads();  // the previous row's reads are done
-        float gi = 1.f, dpi = 0.f;
-        if (MODE != W_FWD) gi = Gin[(size_t)bh * N + i];
-        if (MODE == W_DK || MODE == W_DV) dpi = dprime[(size_t)bh * N + i];
-        float prod = 0.f;  // forward: q . z term;  dQ: o . dO term
-        if (t < D) {
-            const size_t e = base + (size_t)i * D + t;
-            const float av = load_elem(XA, e) * (OMEGA_A ? 1.f / gi : 1.f);
-            const float bv = load_elem(XB, e) * (OMEGA_B ? 1.f / gi : 1.f);
-            const float cv = load_elem(XC, e) * (OMEGA_C ? 1.f / gi : 1.f);
-            As[t] = av;
-            Bs[t] = bv;
-            Cs[t] = cv;
-            if (MODE == W_FWD) {
-                if (update) xv[t] += av;  // z
-                prod = cv * xv[t];
-            } else if (MODE == W_DQ) {
-                // C = dO / g: o . dO = g (o . OmegaHat)
-                prod = pass == 1 ? load_elem(Oin, e) * cv * gi : 0.f;
-            } else if (MODE == W_DV) {
-                if (update) xv[t] += (dpi / gi) * av;  // u, kept for the dK sweep's start
+    // group g of the sweep covers rows [lo, lo + WCH) of the segment, lo counted from the
+    // sweep's starting end; wave wv stages the row it will be walked as number wv
+    const long nrows = row1 - row0, ngroups = (nrows + WCH - 1) / WCH;
+    float fa[4], fb[4], fc[4], fo[4], fg = 1.f, fd = 0.f;
+    auto fetch = [&](long grp) {
+        const long k = grp * WCH + wv;  // position in the sweep
+        const bool ok = k < nrows;
+        const long i = ok ? (DESC ? row1 - 1 - k : row0 + k) : row0;  // any valid row if not ok
+        const size_t e = base + (size_t)i * D + 4 * l;
+        load4(XA + e, fa);
+        load4(XB + e, fb);
+        load4(XC + e, fc);
+        if (MODE == W_DQ && pass == 1) load4(Oin + e, fo);
+        if (MODE != W_FWD) fg = Gin[(size_t)bh * N + i];
+        if (MODE == W_DK || MODE == W_DV) fd = dprime[(size_t)bh * N + i];
+    };
+    int pb = 0;
+    for (long grp = 0; grp < ngroups; ++grp) {
+        __syncthreads();  // the previous group's rows are done with the staged tiles
+        // (the group is fetched here and not a group ahead: values held across the walk below
+        // would push the state out of the register file, and the exposed latency is paid once
+        // per sixteen rows)
+        fetch(grp);
+        {
+            const float rg_ = 1.f / fg;
+            float dl = fd * rg_;  // delta = dprime / g
+            if (MODE == W_DQ && pass == 1) {
+                float s = (fo[0] * fc[0] + fo[1] * fc[1]) + (fo[2] * fc[2] + fo[3] * fc[3]);
+                s = wsum(s);  // o . dO of this wave's row
+                const long k = grp * WCH + wv;
+                if (l == 0 && k < nrows && half == 0) dprime[(size_t)bh * N + row0 + k] = s;
+                dl = s * rg_;
             }
+            if (l == 0) dlt[wv] = dl;
+            const float sa = OMEGA_A ? rg_ : 1.f, sb = OMEGA_B ? rg_ : 1.f, scl = OMEGA_C ? rg_ : 1.f;
+            *reinterpret_cast<float4 *>(&Ach[wv][4 * l]) =
+                make_float4(fa[0] * sa, fa[1] * sa, fa[2] * sa, fa[3] * sa);
+            *reinterpret_cast<float4 *>(&Bch[wv][4 * l]) =
+                make_float4(fb[0] * sb, fb[1] * sb, fb[2] * sb, fb[3] * sb);
+            *reinterpret_cast<float4 *>(&Cch[wv][4 * l]) =
+                make_float4(fc[0] * scl, fc[1] * scl, fc[2] * scl, fc[3] * scl);
         }
-        if (MODE == W_FWD || MODE == W_DQ) {
-            prod = wsum(prod);
-            if (t % 64 == 0) red[t / 64] = prod;
-        }
-        cnt += update ? 1.f : 0.f;
         __syncthreads();
-        if ((MODE == W_FWD || MODE == W_DQ) && t == 0) {
-            float s = 0.f;
-            for (int wv = 0; wv < D / 64; ++wv) s += red[wv];
-            sc[0] = s;
-            if (MODE == W_DQ && pass == 1) dprime[(size_t)bh * N + i] = s;
-        }
-        const float by = Bs[y];
-        if (update) {
-            const float wB = MODE == W_DK ? dpi / gi : 1.f;
-            yvec += wB * by;
-        }
-        float lin = 0.f;
-#pragma unroll
-        for (int r0 = 0; r0 < RPT; r0 += 8) {
-            // eight rows at a time: keeps the operands in flight (not all 2 RPT of them) in
-            // registers next to the RPT of the state
-#pragma unroll
-            for (int r = r0; r < r0 + 8; ++r) {
-                const int x = rg + RG * r;
-                if (update) M[r] += As[x] * by;
-                lin += M[r] * Cs[x];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (pass == 1) part[rg][y] = lin;
-        __syncthreads();
-        if (pass == 1 && t < D) {
-            float l = 0.f;
-#pragma unroll
-            for (int r = 0; r < RG; ++r) l += part[r][t];
-            const size_t e = base + (size_t)i * D + t;
+        const long left = nrows - grp * WCH;
+        const int nr = left < WCH ? (int)left : WCH;
+        for (int r = 0; r < nr; ++r) {
+            const long k = grp * WCH + r;
+            const long i = DESC ? row1 - 1 - k : row0 + k;
+            const float *As = Ach[r], *Bs = Bch[r], *Cs = Cch[r];
+            const float dl = dlt[r];
             if (MODE == W_FWD) {
-                const float gv = a * cnt + b * sc[0];
-                store_elem(out, e, (a * yvec + b * l) / gv);
-                if (t == 0 && Gout) Gout[(size_t)bh * N + i] = gv;
-            } else if (MODE == W_DQ) {
-                store_elem(out, e, b * (l - (sc[0] / gi) * yvec));
-            } else if (MODE == W_DK) {
-                store_elem(out, e, b * (l - yvec));
-            } else {
-                store_elem(out, e, a * yvec + b * l);
+                // z takes the row in, then q . z (a reduction over the first D threads)
+                float prod = 0.f;
+                if (t < D) {
+                    if (update) xv[t] += As[t];
+                    prod = Cs[t] * xv[t];
+                }
+                if (pass == 1) {
+                    prod = wsum(prod);
+                    if (l == 0) red[wv] = prod;
+                    __syncthreads();
+                    if (t == 0) {
+                        float s = 0.f;
+                        for (int u = 0; u < D / 64; ++u) s += red[u];
+                        qz = s;
+                    }
+                }
             }
+            cnt += update ? 1.f : 0.f;
+            const float by = Bs[y];
+            if (update) yvec += (MODE == W_DK ? dl : 1.f) * by;
+            if (MODE == W_DV && update && t < D) xv[t] += dl * As[t];  // u, for the dK sweep's start
+            if (pass == 0) {
+                // phase 1 only sums: no readout, and nothing to wait for between rows
+#pragma unroll
+                for (int q = 0; q < RPT; q += 4) {
+                    const float4 a4 = *reinterpret_cast<const float4 *>(As + rg * RPT + q);
+                    M[q] += a4.x * by;
+                    M[q + 1] += a4.y * by;
+                    M[q + 2] += a4.z * by;
+                    M[q + 3] += a4.w * by;
+                }
+                continue;
+            }
+            float lin = 0.f;
+#pragma unroll
+            for (int q = 0; q < RPT; q += 4) {
+                // the thread's rows are consecutive: operands come four to an LDS read, the
+                // same address in every lane of the wave
+                const float4 a4 = *reinterpret_cast<const float4 *>(As + rg * RPT + q);
+                const float4 c4 = *reinterpret_cast<const float4 *>(Cs + rg * RPT + q);
+                if (update) {
+                    M[q] += a4.x * by;
+                    M[q + 1] += a4.y * by;
+                    M[q + 2] += a4.z * by;
+                    M[q + 3] += a4.w * by;
+                }
+                lin += (M[q] * c4.x + M[q + 1] * c4.y) + (M[q + 2] * c4.z + M[q + 3] * c4.w);
+                // at most two steps' operands in flight: more would push the state out of the
+                // register file
+                if (q % 8 == 4) __builtin_amdgcn_sched_barrier(0);
+            }
+            if (pass == 1) part[pb][rg][yl] = lin;
+            __syncthreads();
+            if (pass == 1 && t < YC) {  // row group 0: column y = half * YC + t
+                float lsum = 0.f;
+#pragma unroll
+                for (int u = 0; u < RG; ++u) lsum += part[pb][u][t];
+                const size_t e = base + (size_t)i * D + y;
+                if (MODE == W_FWD) {
+                    const float gv = a * cnt + b * qz;
+                    store_elem(out, e, (a * yvec + b * lsum) / gv);
+                    if (t == 0 && half == 0 && Gout) Gout[(size_t)bh * N + i] = gv;
+                } else if (MODE == W_DQ) {
+                    store_elem(out, e, b * (lsum - dl * yvec));
+                } else if (MODE == W_DK) {
+                    store_elem(out, e, b * (lsum - yvec));
+                } else {
+                    store_elem(out, e, a * yvec + b * lsum);
+                }
+            }
+            pb ^= 1;  // the next row writes the other buffer while this one is still read
         }
     }
     if (pass == 0) {
         float *slot = ws + ((size_t)bh * nseg + seg + slot_shift) * slot_floats + slot_off;
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) slot[(size_t)(rg + RG * i) * D + y] = M[i];
+        for (int i = 0; i < RPT; ++i) slot[(size_t)(rg * RPT + i) * D + y] = M[i];
         __syncthreads();
-        if (t < D) {
-            slot[D * D + t] = yvec;  // t < D is row group 0, column t
-            slot[D * D + D + t] = xv[t];
-        }
+        if (t < YC) slot[D * D + y] = yvec;  // row group 0
+        if (t < D && half == 0) slot[D * D + D + t] = xv[t];
     }
 }
 
@@ -178,7 +249,7 @@ la_status wide_fwd(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     const int nseg = pl.nseg, len = D * D + 2 * D;
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
-        k_wide<T, D, W_FWD><<<dim3(pr.BH * nrun), dim3(WNT), 0, st>>>(
+        k_wide<T, D, W_FWD><<<dim3(2 * pr.BH * nrun), dim3(WNT), 0, st>>>(
             K, V, Q, nullptr, nullptr, nullptr, nullptr, nullptr, ws, pr.N, nseg, nrun, 0, pl.seg_len,
             pl.slot_floats, 0, pr.causal ? 1 : 0, pr.a, pr.b, pr.causal, 0, 0);
         tc.mark("wide_fwd_state");
@@ -186,7 +257,7 @@ la_status wide_fwd(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
                           pr.causal ? 1 : 0, nseg - 1, st);
         tc.mark("scan_slots");
     }
-    k_wide<T, D, W_FWD><<<dim3(pr.BH * nseg), dim3(WNT), 0, st>>>(
+    k_wide<T, D, W_FWD><<<dim3(2 * pr.BH * nseg), dim3(WNT), 0, st>>>(
         K, V, Q, nullptr, nullptr, nullptr, O, G, ws, pr.N, nseg, nseg, 0, pl.seg_len,
         pl.slot_floats, 0, 0, pr.a, pr.b, pr.causal, 1, 0);
     tc.mark("wide_fwd_apply");
@@ -204,10 +275,10 @@ la_status wide_bwd(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     const int roff = (len + 63) / 64 * 64;  // the reverse-running sums follow in the same slot
     float *dprime = ws + pl.delta_offset_floats;
     const int nrun = pr.causal ? nseg - 1 : nseg;
-    const dim3 grid(pr.BH * nseg), block(WNT);
+    const dim3 grid(2 * pr.BH * nseg), block(WNT);
     // forward-running sums S^T, z before every segment
     if (nrun > 0) {
-        k_wide<T, D, W_DQ><<<dim3(pr.BH * nrun), block, 0, st>>>(
+        k_wide<T, D, W_DQ><<<dim3(2 * pr.BH * nrun), block, 0, st>>>(
             V, K, dO, O, G, dprime, nullptr, nullptr, ws, pr.N, nseg, nrun, 0, pl.seg_len,
             pl.slot_floats, 0, pr.causal ? 1 : 0, pr.a, pr.b, pr.causal, 0, 0);
         tc.mark("wide_bwd_state");
@@ -222,7 +293,7 @@ la_status wide_bwd(const Problem &pr, const Plan &pl, const T *Q, const T *K, co
     if (!dK) return wstatus();
     // reverse-running sums R, w, u after every segment (dV-shaped); dK reads them transposed
     if (nrun > 0) {
-        k_wide<T, D, W_DV><<<dim3(pr.BH * nrun), block, 0, st>>>(
+        k_wide<T, D, W_DV><<<dim3(2 * pr.BH * nrun), block, 0, st>>>(
             Q, dO, K, nullptr, G, dprime, nullptr, nullptr, ws, pr.N, nseg, nrun, pr.causal ? 1 : 0,
             pl.seg_len, pl.slot_floats, roff, pr.causal ? -1 : 0, pr.a, pr.b, pr.causal, 0, 0);
         tc.mark("wide_bwd_rstate");
