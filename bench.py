@@ -122,6 +122,10 @@ def main():
                     help="time la_forward + la_backward (no hand-over of running sums)")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the entry points beyond la_forward / la_backward (decode "
+                         "step, normalisation inside the call, coefficient gradients, head size "
+                         "256) and add them under the key 'extras'")
     ap.add_argument("--seg-len", type=int, default=0,
                     help="force the rows per segment (la_debug_override; 0: the library's plan)")
     ap.add_argument("--cpu-slices", type=int, default=64)
@@ -175,9 +179,69 @@ def main():
                 "dominant_kernel_frac": r["roofline"]["frac"] if r["roofline"] else None,
                 "kernels_ms": r["kernels_ms"], "steps": r["steps"], "dtype": r["dtype"]}
         out["all_configs"] = rows
+    if args.extras:
+        out["extras"] = extras(torch, wl, la)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_slices)
     print(json.dumps(out))
+
+
+def extras(torch, wl, la):
+    """Timings of the other entry points on synthetic inputs of the benchmark's recipe."""
+    def timed(fn, reps, warm=5):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    res = {}
+    # decode: one new token per slice, state carried in place
+    B, H, D = 8, 16, 128
+    x = {n: torch.randn((B, H, 1, D), device="cuda").to(torch.bfloat16) for n in "qkv"}
+    o = torch.empty_like(x["q"])
+    g = torch.empty((B, H, 1), device="cuda")
+    st = torch.zeros(la.la_decode_state_bytes(B, H, D) // 4, device="cuda")
+    ms = timed(lambda: la.la_decode_step(x["q"], x["k"], x["v"], o, g, st, 1.0, 0.5), 200)
+    res["decode_step_bf16_B8_H16_D128_T1"] = {
+        "us_per_step": ms * 1e3, "tokens_per_s": B / (ms * 1e-3),
+        "state_GBs": 2 * st.numel() * 4 / (ms * 1e-3) / 1e9}
+    # normalisation inside the call, coefficient gradients: the headline shape, raw Q and K
+    cfg = wl.CONFIGS[1]
+    t = make_device_inputs(cfg, torch, 1)[0]
+    t["Q"] = (t["Q"] * 3.0).contiguous()
+    t["K"] = (t["K"] * 0.25).contiguous()
+    dt = la.LA_F32
+    args6 = (cfg.B, cfg.H, cfg.N, cfg.D, dt, cfg.causal)
+    wsf = torch.empty(la.la_workspace_bytes(*args6, 0), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(la.la_workspace_bytes(*args6, 3), dtype=torch.uint8, device="cuda")
+
+    def qknorm_step():
+        la.la_forward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b, cfg.causal, wsf)
+        la.la_backward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
+                              t["dV"], cfg.a, cfg.b, cfg.causal, wsb)
+    res["qknorm_fwd_bwd_" + cfg.name] = {"ms_per_step": timed(qknorm_step, 30)}
+    dab = torch.zeros(2, device="cuda")
+    res["backward_ab_" + cfg.name] = {"ms": timed(
+        lambda: la.la_backward_ab(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], dab, cfg.a,
+                                  cfg.b, cfg.causal, wsb), 30)}
+    del t, wsf, wsb
+    torch.cuda.empty_cache()
+    # head size 256: the top of the paper's head-size sweep
+    c = wl.find_workload("paper_causal_f32_B4_H16_N4096_D256")
+    t = make_device_inputs(c, torch, 1)[0]
+    a6 = (c.B, c.H, c.N, c.D, dt, c.causal)
+    wsf = torch.empty(la.la_workspace_bytes(*a6, 0), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(la.la_workspace_bytes(*a6, 1), dtype=torch.uint8, device="cuda")
+    fwd = timed(lambda: la.la_forward(t["Q"], t["K"], t["V"], t["O"], t["G"], c.a, c.b, c.causal,
+                                      wsf), 5, 2)
+    bwd = timed(lambda: la.la_backward(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
+                                       t["dK"], t["dV"], c.a, c.b, c.causal, wsb), 5, 2)
+    res[c.name] = {"forward_ms": fwd, "backward_ms": bwd}
+    return res
 
 
 def source_digest():
