@@ -71,7 +71,21 @@ struct FC {
     // row d (fp32: 4-element column groups; bf16: the 8-element units above, over the whole
     // row) are stored XOR-swizzled by swz(d); readers apply the same swizzle.
     static constexpr int SWM = C / 8;  // swizzle values: 0 .. SWM-1
-    static __device__ __forceinline__ int swz(int d) { return (d / (2 * EPV)) % SWM; }
+    // A wave's 16-byte LDS reads are served in four passes of 16 lanes, and a pass is not 16
+    // consecutive lanes: it takes lanes {0-3, 12-15, 20-23, 24-27}, the next one {4-11, 16-19,
+    // 28-31}, then the same two sets plus 32.  In a fragment read lane 16g + c takes unit g of
+    // row c, so a pass mixes unit g of rows 0-3 and 12-15 with unit g+1 of rows 4-11, which
+    // collide when rows are an odd number of units apart.  Rows 4-11 of every 16 therefore
+    // hold the units of each k-tile exchanged in pairs (unit index ^ 1): every pass then reads
+    // one unit position of 16 different rows, which the odd stride spreads over all banks.
+    static __device__ __forceinline__ int flip(int row) { return ((row >> 2) ^ (row >> 3)) & 1; }
+    // The swizzle of row d of a transposed tile, pair exchange included.  (fp32: the exchange
+    // replaces bit 3 of d by bit 2 in the low swizzle bit; the stores stay free of conflicts.)
+    static __device__ __forceinline__ int swz(int d)
+    {
+        if constexpr (B16) return ((d / (2 * EPV)) % SWM) ^ flip(d);
+        else return ((d / (2 * EPV)) % SWM) ^ ((d >> 3) & 1) ^ flip(d);
+    }
     // For row d = r0 + c with r0 a multiple of 16 and c < 16: swz(d) = swz(r0) ^ swz(c).
     static_assert(16 % (2 * EPV) == 0, "a 16-row block covers whole swizzle steps");
     // Offset inside row d of a transposed tile of the 4-element group of chunk rows 4q .. 4q+3.
@@ -148,15 +162,15 @@ struct Stager {
     __device__ __forceinline__ void store_rows(T *rm) const
     {
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
+        const int fr = F::flip(4 * rq);  // the same for the quad's four rows
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            T *dst = rm + (4 * rq + i) * F::LDR + dg * F::EPV;
+            T *row = rm + (4 * rq + i) * F::LDR;
             if constexpr (sizeof(T) == 4) {
-                *reinterpret_cast<u4v *>(dst) = raw[i];
+                *reinterpret_cast<u4v *>(row + (dg ^ fr) * F::EPV) = raw[i];
             } else {  // the two 4-element groups of the unit go to their permuted places
-                T *row = rm + (4 * rq + i) * F::LDR;
-                *reinterpret_cast<u2v *>(row + F::grp_pos(2 * dg)) = u2v{raw[i][0], raw[i][1]};
-                *reinterpret_cast<u2v *>(row + F::grp_pos(2 * dg + 1)) = u2v{raw[i][2], raw[i][3]};
+                *reinterpret_cast<u2v *>(row + F::grp_pos((2 * dg) ^ fr)) = u2v{raw[i][0], raw[i][1]};
+                *reinterpret_cast<u2v *>(row + F::grp_pos((2 * dg + 1) ^ fr)) = u2v{raw[i][2], raw[i][3]};
             }
         }
     }
@@ -178,7 +192,7 @@ struct Stager {
                 const uint32_t r0 = raw[0][wd], r1 = raw[1][wd], r2 = raw[2][wd], r3 = raw[3][wd];
                 const u2v lo = {(r0 & 0xffffu) | (r1 << 16), (r2 & 0xffffu) | (r3 << 16)};
                 const u2v hi = {(r0 >> 16) | (r1 & 0xffff0000u), (r2 >> 16) | (r3 & 0xffff0000u)};
-                const int cg = F::tr_pos(rq, dg * 8);  // the same for all 8 rows of the unit
+                const int cg = F::tr_pos(rq, dg * 8 + 2 * wd);  // the same for both rows
                 *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd) * F::LDT + cg) = lo;
                 *reinterpret_cast<u2v *>(tr + (dg * 8 + 2 * wd + 1) * F::LDT + cg) = hi;
             }
@@ -448,14 +462,16 @@ __device__ __forceinline__ void state_product(Blk (&acc)[NM], const Blk (&col)[D
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDR = F::LDR;
     typedef Ys<M, NM> B;
-    int lane0 = c * LDR;  // opaque to the compiler, see outer_update
+    // row c, and in it the place of the lane group's unit (opaque to the compiler, see
+    // outer_update)
+    int lane0 = c * LDR + F::EPV * (g ^ F::flip(c));
     asm volatile("" : "+v"(lane0));
     pipeline<D / KT, DEPTH>(
         D / KT,
         [&](int kt) {
             B b;
 #pragma unroll
-            for (int m = 0; m < NM; ++m) b.y[m] = M::load(ys + m * 16 * LDR + lane0 + kt * KT, g);
+            for (int m = 0; m < NM; ++m) b.y[m] = M::load(ys + m * 16 * LDR + lane0 + kt * KT, 0);
             return b;
         },
         [&](int kt, const B &b) {
@@ -481,15 +497,15 @@ __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, con
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int KT = F::KT, LDR = F::LDR, STEPS = D / KT, BATCH = STEPS < 4 ? STEPS : 4;
-    int lane0 = c * LDR;  // opaque to the compiler, see outer_update
+    int lane0 = c * LDR + F::EPV * (g ^ F::flip(c));  // see state_product
     asm volatile("" : "+v"(lane0));
 #pragma unroll
     for (int k0 = 0; k0 < STEPS; k0 += BATCH) {
         typename M::Frag x[BATCH], y[BATCH];
 #pragma unroll
         for (int k = 0; k < BATCH; ++k) {
-            x[k] = M::load(xs + xr * LDR + lane0 + (k0 + k) * KT, g);
-            y[k] = M::load(ys + yr * LDR + lane0 + (k0 + k) * KT, g);
+            x[k] = M::load(xs + xr * LDR + lane0 + (k0 + k) * KT, 0);
+            y[k] = M::load(ys + yr * LDR + lane0 + (k0 + k) * KT, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -512,6 +528,9 @@ __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, in
     typedef XsYs<M, NXP, NYP> B;
     int lane0 = c * LDT;  // opaque to the compiler, see outer_update
     asm volatile("" : "+v"(lane0));
+    // row c of the weight tile, and in it the place of the lane group's unit
+    int laney = c * LDT + F::EPV * (g ^ F::flip(c));
+    asm volatile("" : "+v"(laney));
     pipeline<C / KT>(
         kt1 - kt0,
         [&](int s) {
@@ -521,7 +540,7 @@ __device__ __forceinline__ void chunk_product(Blk &acc, const T *xt, int xps, in
                 b.x[p] = M::load_off(xt + p * xps + xr * LDT + lane0, kt0 + s, xo);
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
-                b.y[p] = M::load(yt + p * yps + (yr + c) * LDT + (kt0 + s) * KT, g);
+                b.y[p] = M::load(yt + p * yps + yr * LDT + laney + (kt0 + s) * KT, 0);
             return b;
         },
         [&](int, const B &b) {
@@ -548,6 +567,9 @@ __device__ __forceinline__ void chunk_products_lower(Blk (&acc)[NBL], int ib0, c
     typedef XsYs<M, 1, NYP> B;
     int lane0 = c * LDT;  // opaque to the compiler, see outer_update
     asm volatile("" : "+v"(lane0));
+    // row c of the weight tile, and in it the place of the lane group's unit
+    int laney = c * LDT + F::EPV * (g ^ F::flip(c));
+    asm volatile("" : "+v"(laney));
     auto kts = [&](int m) { return ((ib0 + m + 1) * 16 + KT - 1) / KT; };
     int steps = 0;
 #pragma unroll
@@ -568,7 +590,7 @@ __device__ __forceinline__ void chunk_products_lower(Blk (&acc)[NBL], int ib0, c
             b.x[0] = M::load_off(xt + xr * LDT + lane0, kt, xo);
 #pragma unroll
             for (int p = 0; p < NYP; ++p)
-                b.y[p] = M::load(yt + p * yps + (ib0 + m) * 16 * LDT + lane0 + kt * KT, g);
+                b.y[p] = M::load(yt + p * yps + (ib0 + m) * 16 * LDT + laney + kt * KT, 0);
             return b;
         },
         [&](int s, const B &b) {
@@ -594,7 +616,8 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
     typedef Mma<T, 16> M;
     typedef typename Vec4<T>::type V4;
     const f4v x = {vals[0], vals[1], vals[2], vals[3]};
-    T *dst = tile + (col0 + c) * FC<T, D>::LDT + FC<T, D>::grp_pos(row0 / 4 + g);
+    T *dst = tile + (col0 + c) * FC<T, D>::LDT +
+             FC<T, D>::grp_pos((row0 / 4 + g) ^ FC<T, D>::flip(c));
     const V4 vh = pack4(x, T());
     *reinterpret_cast<V4 *>(dst) = vh;
     if constexpr (M::PLANES == 2) {
@@ -606,21 +629,29 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
 // of block row c.  Neighbouring lanes would write to different rows, which the memory
 // pipeline cannot merge, so the values are first exchanged between lanes (no memory
 // involved): afterwards lane l holds row l / 4, column quad l % 4, and four neighbouring
-// lanes write one contiguous run of a row.  Rows at or beyond `rows_valid` are skipped.
+// lanes write one contiguous run of a row.  The block is addressed through a buffer
+// descriptor that covers its first `rows_valid` rows (at most 16, possibly none): stores
+// to rows beyond them are dropped by the address check, without a branch, and the lane's
+// address is one 32-bit offset that does not change from block to block.
 template <typename T>
 __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_valid, int l,
                                             float x0, float x1, float x2, float x3)
 {
     const int src = 16 * (l % 4) + l / 4;  // lane that holds (row l/4, column quad l%4)
     const int row = l / 4, cq = l % 4;
+    const int nrows = rows_valid < 0 ? 0 : (rows_valid > 16 ? 16 : rows_valid);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        base, 0, nrows * ld * (int)sizeof(T), kBufferFlags);
+    const int off = (row * ld + col0 + 4 * cq) * (int)sizeof(T);
     if constexpr (sizeof(T) == 4) {
-        f4v v = {__shfl(x0, src), __shfl(x1, src), __shfl(x2, src), __shfl(x3, src)};
-        if (row < rows_valid) *reinterpret_cast<f4v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
+        const u4v v = {__float_as_uint(__shfl(x0, src)), __float_as_uint(__shfl(x1, src)),
+                       __float_as_uint(__shfl(x2, src)), __float_as_uint(__shfl(x3, src))};
+        __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, off, 0, 0);
     } else {
         bf4v p = to_bf4(f4v{x0, x1, x2, x3});
         u2v u = *reinterpret_cast<u2v *>(&p);
-        u2v v = {(unsigned)__shfl((int)u[0], src), (unsigned)__shfl((int)u[1], src)};
-        if (row < rows_valid) *reinterpret_cast<u2v *>(base + (size_t)row * ld + col0 + 4 * cq) = v;
+        const u2v v = {(unsigned)__shfl((int)u[0], src), (unsigned)__shfl((int)u[1], src)};
+        __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, off, 0, 0);
     }
 }
 
@@ -842,11 +873,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             typedef typename Vec4<T>::type V4;
             constexpr int PARTS = NT / C, PER = D / PARTS;  // threads per row, elements per thread
             const int i = t / PARTS, part = t % PARTS;
+            const int fz = F::flip(i) * F::EPV;  // row i holds its units exchanged in pairs
             float s = 0.f;
 #pragma unroll
             for (int d = 0; d < PER; d += 4) {
                 V4 qv = *reinterpret_cast<const V4 *>(Qs + i * LDR + part * PER + d);
-                f4v zv = *reinterpret_cast<const f4v *>(zs + part * PER + d);
+                f4v zv = *reinterpret_cast<const f4v *>(zs + ((part * PER + d) ^ fz));
                 s += (to_float(qv[0]) * zv[0] + to_float(qv[1]) * zv[1]) +
                      (to_float(qv[2]) * zv[2] + to_float(qv[3]) * zv[3]);
             }
@@ -880,7 +912,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             if (l < C) {
                 const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 ginv[w][l] = 1.f / gv;
-                if (w == 0 && G && c0 + l < row1) Gp[c0 + l] = gv;
+                // (32-bit row arithmetic: a segment is far shorter than 2^31 rows)
+                if (w == 0 && G && l < (int)(row1 - c0)) (Gp + c0)[l] = gv;
             }
             __builtin_amdgcn_wave_barrier();
             if constexpr (CAUSAL) {
@@ -1027,7 +1060,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     };
     // 1/g of the chunk starting at c0 (whose g values have been fetched) into buffer `par`
     auto post_factors = [&](long c0, int par) {
-        if (t < C) rsb[par][t] = (c0 + t < row1) ? __builtin_amdgcn_rcpf(g_next) : 0.f;
+        if (t < C) rsb[par][t] = (t < (int)(row1 - c0)) ? __builtin_amdgcn_rcpf(g_next) : 0.f;
     };
     fetch(row0);
     post_factors(row0, 0);
@@ -1059,7 +1092,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                     const int r = 4 * rq + i;
                     dl[r] = s;
                     dls[r] = s * r4[i];
-                    if (c0 + r < row1) dp[c0 + r] = s;
+                    if (r < (int)(row1 - c0)) (dp + c0)[r] = s;
                 }
             }
             s1.store_rows(dOs);
@@ -1284,7 +1317,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // row factors of the chunk starting at c0 (already fetched) into buffer `par`
     auto post_factors = [&](long c0, int par) {
         if (CAUSAL && t < C) {
-            const bool ok = c0 + t < row1;
+            const bool ok = t < (int)(row1 - c0);
             const float r = ok ? __builtin_amdgcn_rcpf(g_next) : 0.f, d = ok ? d_next : 0.f;
             float *f = fac + par * 3 * C;
             f[t] = r;
