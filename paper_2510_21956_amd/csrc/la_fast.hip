@@ -135,6 +135,13 @@ struct Stager {
     // patched after loading, makes the compiler wait for the data on the spot.  A half
     // with no tensor of its own for a stager requests the other half's: the same lines at
     // the same time, so no extra memory traffic.
+    //
+    // Rows [I0, I1) of the thread's four: the memory pipeline of a CU takes in about one
+    // 16-byte-per-lane load per 50 clocks and queues some thirty of them; a workgroup that
+    // asks for a whole chunk at once (64 to 100 loads) leaves its later waves standing at the
+    // issue of their loads for a fifth of the chunk's time.  The kernels therefore request the
+    // next chunk two rows per thread at a time, at points spread over the current chunk's work.
+    template <int I0 = 0, int I1 = 4>
     __device__ __forceinline__ void load(const T *X, long c0, int N)
     {
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
@@ -143,7 +150,7 @@ struct Stager {
             const_cast<T *>(X + (size_t)c0 * D), 0, (int)(rows * D * sizeof(T)), kBufferFlags);
         const int off = (4 * rq * D + dg * F::EPV) * (int)sizeof(T);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = I0; i < I1; ++i)
             raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + i * D * (int)sizeof(T), 0, 0);
     }
 
@@ -513,6 +520,42 @@ __device__ __forceinline__ void block_product(Blk &acc, const T *xs, int xr, con
     }
 }
 
+// Two such blocks at once: all fragments of both are requested together and the MFMAs
+// alternate between the two accumulators.  A block on its own is a chain of dependent steps
+// (LDS round trip, MFMAs into one accumulator, element-wise map, stores); two of them
+// interleaved take little longer than one.
+template <typename T, int D>
+__device__ __forceinline__ void block_product2(Blk &acc0, const T *xs0, int xr0, const T *ys0,
+                                               int yr0, Blk &acc1, const T *xs1, int xr1,
+                                               const T *ys1, int yr1, int c, int g)
+{
+    typedef FC<T, D> F;
+    typedef Mma<T, 16> M;
+    constexpr int KT = F::KT, LDR = F::LDR, STEPS = D / KT, BATCH = STEPS < 4 ? STEPS : 4;
+    int lane0 = c * LDR + F::EPV * (g ^ F::flip(c));  // see state_product
+    asm volatile("" : "+v"(lane0));
+#pragma unroll
+    for (int k0 = 0; k0 < STEPS; k0 += BATCH) {
+        typename M::Frag x0[BATCH], y0[BATCH], x1[BATCH], y1[BATCH];
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            x0[k] = M::load(xs0 + xr0 * LDR + lane0 + (k0 + k) * KT, 0);
+            y0[k] = M::load(ys0 + yr0 * LDR + lane0 + (k0 + k) * KT, 0);
+        }
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            x1[k] = M::load(xs1 + xr1 * LDR + lane0 + (k0 + k) * KT, 0);
+            y1[k] = M::load(ys1 + yr1 * LDR + lane0 + (k0 + k) * KT, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            M::mma(acc0, x0[k], y0[k]);
+            M::mma(acc1, x1[k], y1[k]);
+        }
+    }
+}
+
 // acc += X_rows(xr)[k-tiles kt0..kt1) . Y_rows(yr)^T over chunk rows, where X is a
 // (swizzled) transposed tile with NXP planes (plane stride xps) and Y a weight tile with
 // NYP planes (plane stride yps), both with leading dimension LDT.  Products of two second
@@ -826,39 +869,63 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             s1.store_cols(KTt);
         }
         __syncthreads();
-        // next chunk, in flight meanwhile (after the last one: that one again)
-        s1.load(p1, min(c0 + C, c_last), N);
-        if constexpr (CAUSAL) s2.load(Vp, min(c0 + C, c_last), N);
+        // next chunk, in flight meanwhile (after the last one: that one again), requested in
+        // four parts spread over this chunk's work
+        // (the unmasked kernel is bound by memory and asks for everything at once)
+        const long cn = min(c0 + C, c_last);
+        if constexpr (CAUSAL) s1.template load<0, 2>(p1, cn, N);
+        else s1.load(p1, cn, N);
 
         // ---- phase A: weight blocks P = tril(a + b Q K^T), q.z, column sums ----
         if constexpr (CAUSAL) {
-            // the NB(NB+1)/2 blocks on or below the diagonal, dealt round-robin to the waves
-#pragma unroll 1
-            for (int pidx = w; pidx < NB * (NB + 1) / 2; pidx += NW) {
-                int ib = 0, nb = pidx;
+            // the NB(NB+1)/2 blocks on or below the diagonal, dealt round-robin to the waves;
+            // a wave with two blocks to do works on both at once
+            constexpr int NBLK = NB * (NB + 1) / 2;
+            auto block_of = [](int pidx, int &ib, int &nb) {
+                ib = 0;
+                nb = pidx;
                 while (nb > ib) nb -= ++ib;
-                {
-                    Blk pa;  // rows n (block nb), columns i (block ib)
-                    pa.zero();
-                    block_product<T, D>(pa, Ks, nb * 16, Qs, ib * 16, c, g);
-                    float vals[4], rs = 0.f;
+            };
+            // pa: rows n (block nb), columns i (block ib)
+            auto finish = [&](const Blk &pa, int ib, int nb) {
+                float vals[4], rs = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float x = a + b * pa.get(e);
-                        if (nb == ib && 4 * g + e > c) x = 0.f;
-                        vals[e] = x;
-                        rs += x;
-                    }
-                    store_weight_block<T, D>(Ps, PSZ, ib * 16, nb * 16, c, g, vals, lo_on);
-                    if (KT > 16 && nb == ib && ib % 2 == 0) {
-                        // the k-tile of the products below also covers the next block: zeros
-                        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-                        store_weight_block<T, D>(Ps, PSZ, ib * 16, (nb + 1) * 16, c, g, zero, lo_on);
-                    }
-                    rs = reduce_lane_groups(rs);
-                    if (g == 0) psum[nb][ib * 16 + c] = rs;
+                for (int e = 0; e < 4; ++e) {
+                    float x = a + b * pa.get(e);
+                    if (nb == ib && 4 * g + e > c) x = 0.f;
+                    vals[e] = x;
+                    rs += x;
+                }
+                store_weight_block<T, D>(Ps, PSZ, ib * 16, nb * 16, c, g, vals, lo_on);
+                if (KT > 16 && nb == ib && ib % 2 == 0) {
+                    // the k-tile of the products below also covers the next block: zeros
+                    const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+                    store_weight_block<T, D>(Ps, PSZ, ib * 16, (nb + 1) * 16, c, g, zero, lo_on);
+                }
+                rs = reduce_lane_groups(rs);
+                if (g == 0) psum[nb][ib * 16 + c] = rs;
+            };
+#pragma unroll 1
+            for (int pidx = w; pidx < NBLK; pidx += 2 * NW) {
+                int ib, nb;
+                block_of(pidx, ib, nb);
+                Blk pa;
+                pa.zero();
+                if (pidx + NW < NBLK) {
+                    int ib1, nb1;
+                    block_of(pidx + NW, ib1, nb1);
+                    Blk pa1;
+                    pa1.zero();
+                    block_product2<T, D>(pa, Ks, nb * 16, Qs, ib * 16, pa1, Ks, nb1 * 16, Qs,
+                                         ib1 * 16, c, g);
+                    finish(pa, ib, nb);
+                    finish(pa1, ib1, nb1);
+                } else {
+                    block_product<T, D>(pa, Ks, nb * 16, Qs, ib * 16, c, g);
+                    finish(pa, ib, nb);
                 }
             }
+            s1.template load<2, 4>(p1, cn, N);
             if constexpr (!F::MS) {
 #pragma unroll
                 for (int part = 0; part < VJ::PER; ++part) {
@@ -886,9 +953,20 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             for (int m = 1; m < PARTS; m <<= 1) s += __shfl_xor(s, m);
             if (part == 0) qzs[i] = s;
         }
+        // The product with the state needs nothing of phase A: it runs before the barrier, so
+        // that on every SIMD the wave that is done with its weight blocks first feeds the
+        // matrix pipe while the other one still works through its blocks in the vector ALU.
+        Blk facc[NB];  // rows j = 16w + 4g + e, columns i
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
+        if (lo_on) state_product<T, D, NB>(facc, st, Qs, c, g);
+        else state_product<T, D, NB, 1>(facc, st, Qs, c, g);
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) facc[ib].v *= b;  // b S^T Q^T, before the block products
+        if constexpr (CAUSAL) s2.template load<0, 2>(Vp, cn, N);
         __syncthreads();
 
-        // ---- phase B: denominators; per row block b S^T Q^T + V^T P^T, normalise, store ----
+        // ---- phase B: denominators; per row block V^T P^T on top, normalise, store ----
         {
             // the row's q.z and block row sums: requested now, used after the state product
             float qz = 0.f, ps = 0.f;
@@ -902,13 +980,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                     }
                 }
             }
-            Blk facc[NB];  // rows j = 16w + 4g + e, columns i
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) facc[ib].zero();
-            if (lo_on) state_product<T, D, NB>(facc, st, Qs, c, g);
-            else state_product<T, D, NB, 1>(facc, st, Qs, c, g);
-#pragma unroll
-            for (int ib = 0; ib < NB; ++ib) facc[ib].v *= b;  // b S^T Q^T, before the block products
             if (l < C) {
                 const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 ginv[w][l] = 1.f / gv;
@@ -933,6 +1004,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                                (facc[ib].get(3) + p4[3]) * gi[ib]);
         }
         if constexpr (CAUSAL) {
+            s2.template load<2, 4>(Vp, cn, N);
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
             if constexpr (!F::MS) {
                 pacc.v += *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
@@ -1052,11 +1124,39 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     float g_next;  // g of row t % C of the chunk being fetched
     const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
+    // Part k of the request for the chunk at c0 (see Stager::load): six parts with the mask,
+    // four without; g comes with the first, it is needed before the chunk ends.
+    // The unmasked kernel is bound by memory and asks for everything with part 0.
+    auto fetch_part = [&](long c0, auto part) {
+        constexpr int k = decltype(part)::value;
+        if constexpr (!CAUSAL) {
+            if constexpr (k == 0) {
+                g_next = load_row_float(Gp, c0, N, t % C);
+                s1.load(p1, c0, N);
+                s2.load(p2, c0, N);
+            }
+        } else if constexpr (k == 0) {
+            g_next = load_row_float(Gp, c0, N, t % C);
+            s1.template load<0, 2>(p1, c0, N);
+        } else if constexpr (k == 1) {
+            s1.template load<2, 4>(p1, c0, N);
+        } else if constexpr (k == 2) {
+            s2.template load<0, 2>(p2, c0, N);
+        } else if constexpr (k == 3) {
+            s2.template load<2, 4>(p2, c0, N);
+        } else if constexpr (k == 4) {
+            s3.template load<0, 2>(Qp, c0, N);
+        } else if constexpr (k == 5) {
+            s3.template load<2, 4>(Qp, c0, N);
+        }
+    };
     auto fetch = [&](long c0) {
-        s1.load(p1, c0, N);
-        s2.load(p2, c0, N);
-        if constexpr (CAUSAL) s3.load(Qp, c0, N);
-        g_next = load_row_float(Gp, c0, N, t % C);
+        fetch_part(c0, std::integral_constant<int, 0>());
+        fetch_part(c0, std::integral_constant<int, 1>());
+        fetch_part(c0, std::integral_constant<int, 2>());
+        fetch_part(c0, std::integral_constant<int, 3>());
+        fetch_part(c0, std::integral_constant<int, 4>());
+        fetch_part(c0, std::integral_constant<int, 5>());
     };
     // 1/g of the chunk starting at c0 (whose g values have been fetched) into buffer `par`
     auto post_factors = [&](long c0, int par) {
@@ -1106,7 +1206,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             s1.store_cols(QTt);
         }
         __syncthreads();
-        fetch(min(c0 + C, c_last));  // next chunk, in flight meanwhile (at the end: the last again)
+        // next chunk, in flight meanwhile (at the end: the last again), requested in parts
+        const long cn = min(c0 + C, c_last);
+        fetch_part(cn, std::integral_constant<int, 0>());
 
         // ---- phase A: weight blocks Cm' (rows n, columns i), column sums of K ----
         if constexpr (CAUSAL) {
@@ -1141,6 +1243,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                         csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
             }
         }
+        fetch_part(cn, std::integral_constant<int, 1>());
         if constexpr (!F::MS) {
             if (need_R) {
                 // this chunk's share of w = sum OmegaHat and u = sum delta q
@@ -1184,17 +1287,21 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                                f * (acc[ii].get(2) - di[ii] * z4[2]),
                                f * (acc[ii].get(3) - di[ii] * z4[3]));
             }
+            if (i0 == 0) fetch_part(cn, std::integral_constant<int, 2>());
         }
+        fetch_part(cn, std::integral_constant<int, 3>());
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, VTt, 0, KTt, 0, w, c, g, ql, wo, vz);
             if constexpr (!F::MS) zacc.v += *reinterpret_cast<const f4v *>(csk + w * 16 + 4 * g);
         }
+        fetch_part(cn, std::integral_constant<int, 4>());
         if (need_R) {
             constexpr int GRP = (sizeof(T) == 4 && D == 64) ? 4 : 2;
             vr.wplanes = lo_on ? 2 : 1;
             if (lo_on) outer_update<T, D, GRP, 1, PP>(accR, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vr);
             else outer_update<T, D, GRP, 1, 1>(accR, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vr);
         }
+        fetch_part(cn, std::integral_constant<int, 5>());
         par ^= 1;
         post_factors(c0 + C, par);
     }
@@ -1267,7 +1374,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
-    const bool h0 = w < F::NW / 2;  // first or second staging half
+    // staging halves: the waves that came first on their SIMDs (0 .. NW/2-1) run ahead of the
+    // others in every phase, so they take the heavier set of tiles ("half 1" below)
+    const bool h0 = w >= F::NW / 2;
     // swizzle of transposed tiles: lane part, and this wave's own 16 rows resolved
     const SwzLane ql = Mma<T, 16>::swz_lane(g, F::swz(c));
     const SwzOff wo = Mma<T, 16>::swz_offsets(g, F::swz(c), F::swz(w * 16));
@@ -1306,13 +1415,30 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     Stager<T, D> s1, s2;
     const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
     float g_next = 1.f, d_next = 0.f;  // g, dprime of row t % C of the chunk being fetched
-    auto fetch = [&](long c0) {
-        s1.load(p1, c0, N);
-        if constexpr (CAUSAL) {
-            s2.load(p2, c0, N);
+    // Part k of the request for the chunk at c0 (see Stager::load); the row factors come
+    // with the first, they are needed before the chunk ends.  The unmasked kernel is bound
+    // by memory and asks for everything with part 0.
+    auto fetch_part = [&](long c0, auto part) {
+        constexpr int k = decltype(part)::value;
+        if constexpr (!CAUSAL) {
+            if constexpr (k == 0) s1.load(p1, c0, N);
+        } else if constexpr (k == 0) {
             g_next = load_row_float(Gp, c0, N, t % C);
             d_next = load_row_float(dp, c0, N, t % C);
+            s1.template load<0, 2>(p1, c0, N);
+        } else if constexpr (k == 1) {
+            s1.template load<2, 4>(p1, c0, N);
+        } else if constexpr (CAUSAL && k == 2) {
+            s2.template load<0, 2>(p2, c0, N);
+        } else if constexpr (CAUSAL && k == 3) {
+            s2.template load<2, 4>(p2, c0, N);
         }
+    };
+    auto fetch = [&](long c0) {
+        fetch_part(c0, std::integral_constant<int, 0>());
+        fetch_part(c0, std::integral_constant<int, 1>());
+        fetch_part(c0, std::integral_constant<int, 2>());
+        fetch_part(c0, std::integral_constant<int, 3>());
     };
     // row factors of the chunk starting at c0 (already fetched) into buffer `par`
     auto post_factors = [&](long c0, int par) {
@@ -1352,8 +1478,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         }
         __syncthreads();
         // next chunk of the descending sweep, in flight meanwhile (after the first chunk of
-        // the segment: that one again)
-        fetch(ci > 0 ? c0 - C : c0);
+        // the segment: that one again), requested in parts
+        const long cn = ci > 0 ? c0 - C : c0;
+        fetch_part(cn, std::integral_constant<int, 0>());
 
         // ---- phase A: weight blocks Cm and W (rows i, columns n), column sums ----
         if constexpr (CAUSAL) {
@@ -1366,8 +1493,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                     Blk pc, pw;
                     pc.zero();
                     pw.zero();
-                    block_product<T, D>(pc, dOs, ib * 16, Vs, nb * 16, c, g);
-                    block_product<T, D>(pw, Qs, ib * 16, Ks, nb * 16, c, g);
+                    if constexpr (F::B16) {
+                        block_product2<T, D>(pc, dOs, ib * 16, Vs, nb * 16, pw, Qs, ib * 16, Ks,
+                                             nb * 16, c, g);
+                    } else {  // fp32: the matrix pipe is the limit, and the registers are needed
+                        block_product<T, D>(pc, dOs, ib * 16, Vs, nb * 16, c, g);
+                        block_product<T, D>(pw, Qs, ib * 16, Ks, nb * 16, c, g);
+                    }
                     const f4v r4 = *reinterpret_cast<const f4v *>(rs + ib * 16 + 4 * g);
                     const f4v d4 = *reinterpret_cast<const f4v *>(dl + ib * 16 + 4 * g);
                     float vc[4], vw[4];
@@ -1395,21 +1527,26 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                     if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
                 }
             }
-            __syncthreads();
         }
+        fetch_part(cn, std::integral_constant<int, 1>());
+        // The first product with the state needs nothing of phase A: it runs before the
+        // barrier, so that on every SIMD the wave that is done with its weight blocks first
+        // feeds the matrix pipe while the other one still works in the vector ALU.
+        constexpr int NPB = NB;
+        constexpr int n0 = 0;
+        Blk ak[NPB];
+#pragma unroll
+        for (int m = 0; m < NPB; ++m) ak[m].zero();
+        if (lo_on) state_product<T, D, NPB>(ak, Rb, Vs, c, g);
+        else state_product<T, D, NPB, 1>(ak, Rb, Vs, c, g);
+        fetch_part(cn, std::integral_constant<int, 2>());
+        if constexpr (CAUSAL) __syncthreads();
         const f4v u4 = uacc.v, w4 = a * wacc.v;
 
         // ---- phase B: per row block (rows r resp. j, columns n): R^T V^T + Q^T Cm, R K^T +
         //      OmegaHat^T W; store ----
-        constexpr int NPB = NB;
-#pragma unroll 1
-        for (int n0 = 0; n0 < NB; n0 += NPB) {
+        {
             {
-                Blk ak[NPB];
-#pragma unroll
-                for (int m = 0; m < NPB; ++m) ak[m].zero();
-                if (lo_on) state_product<T, D, NPB>(ak, Rb, Vs + n0 * 16 * LDR, c, g);
-                else state_product<T, D, NPB, 1>(ak, Rb, Vs + n0 * 16 * LDR, c, g);
 #pragma unroll
                 for (int m = 0; m < NPB; ++m) {
                     const int nb = n0 + m;
@@ -1427,6 +1564,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                                    b * (ak[m].get(3) - u4[3]));
                 }
             }
+            fetch_part(cn, std::integral_constant<int, 3>());
             {
                 Blk av[NPB];
 #pragma unroll

@@ -5,7 +5,7 @@
 // on two LDS tiles whose rows hold the contraction index contiguously, or with
 // one operand taken straight from an accumulator block of an earlier product.
 //
-// Block size BS (16 or 32) is the MFMA output tile edge; a 64-lane wave is
+// Block size BS = 16 is the MFMA output tile edge; a 64-lane wave is
 // NG = 64 / BS lane groups of BS lanes.  Lane (c = lane % BS, g = lane / BS):
 //   * as an operand, supplies row c of X (or Y) and, per k-tile, the contraction
 //     indices  4g..4g+3  (fp32) or  4g..4g+3 and KT/2+4g..KT/2+4g+3  (bf16);
@@ -25,7 +25,6 @@
 namespace la {
 
 typedef float f4v __attribute__((ext_vector_type(4)));
-typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf4v __attribute__((ext_vector_type(4)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef float f2v __attribute__((ext_vector_type(2)));
@@ -44,24 +43,6 @@ __device__ __forceinline__ f4v bf4_to_float(bf4v x) { return __builtin_convertve
 // ---- accumulator blocks -----------------------------------------------------
 template <int BS>
 struct Acc;
-
-template <>
-struct Acc<32> {
-    f16v v;
-    static constexpr int GROUPS = 4;  // groups of four registers
-    __device__ __forceinline__ void zero()
-    {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = 0.f;
-    }
-    __device__ __forceinline__ f4v group(int q) const
-    {
-        f4v r = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-        return r;
-    }
-    __device__ __forceinline__ float get(int i) const { return v[i]; }
-    __device__ __forceinline__ void set(int i, float x) { v[i] = x; }
-};
 
 template <>
 struct Acc<16> {
@@ -90,6 +71,7 @@ struct Mma;
 
 template <int BS>
 struct Mma<float, BS> {
+    static_assert(BS == 16, "16 x 16 output tiles");
     static constexpr int NG = 64 / BS;
     static constexpr int KT = 4 * NG;   // contraction indices per k-tile
     static constexpr int GPT = 1;       // accumulator groups per k-tile when used as operand
@@ -135,10 +117,7 @@ struct Mma<float, BS> {
     {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            if constexpr (BS == 32)
-                c.v = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], c.v, 0, 0, 0);
-            else
-                c.v = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], c.v, 0, 0, 0);
+            c.v = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], c.v, 0, 0, 0);
         }
     }
     // The intermediate (possibly split) is the X operand: c += a * b.
@@ -156,6 +135,7 @@ struct Mma<float, BS> {
 
 template <int BS>
 struct Mma<__bf16, BS> {
+    static_assert(BS == 16, "16 x 16 output tiles");
     static constexpr int NG = 64 / BS;
     static constexpr int KT = 8 * NG;
     static constexpr int GPT = 2;
@@ -225,10 +205,7 @@ struct Mma<__bf16, BS> {
     static __device__ __forceinline__ Frag lo_of(const Frag2 &f) { return f.lo; }
     static __device__ __forceinline__ void mma(Acc<BS> &c, Frag a, Frag b)
     {
-        if constexpr (BS == 32)
-            c.v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c.v, 0, 0, 0);
-        else
-            c.v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c.v, 0, 0, 0);
+        c.v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c.v, 0, 0, 0);
     }
     static __device__ __forceinline__ void mma2x(Acc<BS> &c, const Frag2 &a, Frag b)
     {
