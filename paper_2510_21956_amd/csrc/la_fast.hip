@@ -953,6 +953,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             for (int m = 1; m < PARTS; m <<= 1) s += __shfl_xor(s, m);
             if (part == 0) qzs[i] = s;
         }
+        if constexpr (CAUSAL) s2.template load<0, 2>(Vp, cn, N);
         // The product with the state needs nothing of phase A: it runs before the barrier, so
         // that on every SIMD the wave that is done with its weight blocks first feeds the
         // matrix pipe while the other one still works through its blocks in the vector ALU.
@@ -963,7 +964,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
         else state_product<T, D, NB, 1>(facc, st, Qs, c, g);
 #pragma unroll
         for (int ib = 0; ib < NB; ++ib) facc[ib].v *= b;  // b S^T Q^T, before the block products
-        if constexpr (CAUSAL) s2.template load<0, 2>(Vp, cn, N);
+        if constexpr (CAUSAL) s2.template load<2, 4>(Vp, cn, N);
         __syncthreads();
 
         // ---- phase B: denominators; per row block V^T P^T on top, normalise, store ----
@@ -1004,7 +1005,6 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                                (facc[ib].get(3) + p4[3]) * gi[ib]);
         }
         if constexpr (CAUSAL) {
-            s2.template load<2, 4>(Vp, cn, N);
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
             if constexpr (!F::MS) {
                 pacc.v += *reinterpret_cast<const f4v *>(csv + w * 16 + 4 * g);
