@@ -327,6 +327,17 @@ def measure(cfg, args, steps, warmup, torch, wl, la):
                                  t["dK"], t["dV"], cfg.a, cfg.b, cfg.causal, wsb, saved, None,
                                  trb)
 
+    # event handles for the per-kernel durations measured after the timed loops
+    reps = max(5, min(steps, 50))
+    traces = []
+    for i in range(reps):
+        evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
+        trf, trb = la.la_trace(), la.la_trace()
+        trf.events = ctypes.cast(evf.handles, ctypes.POINTER(ctypes.c_void_p))
+        trb.events = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p))
+        trf.capacity = trb.capacity = la.LA_MAX_TRACE + 1
+        traces.append((trf, evf, trb, evb))
+
     def timed(n):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -357,19 +368,9 @@ def measure(cfg, args, steps, warmup, torch, wl, la):
 
     # Per-kernel durations: the same steps again, back to back and straight after the timed
     # loop (so at the same clocks), with the library recording HIP events between its kernels
-    # on the stream it launches on.  Every repetition has event handles of its own; nothing
-    # waits until all of them are enqueued.
-    reps = max(5, min(steps, 50))
-    traces = []
-    for i in range(reps):
-        evf, evb = HipEvents(la.LA_MAX_TRACE + 1), HipEvents(la.LA_MAX_TRACE + 1)
-        trf, trb = la.la_trace(), la.la_trace()
-        trf.events = ctypes.cast(evf.handles, ctypes.POINTER(ctypes.c_void_p))
-        trb.events = ctypes.cast(evb.handles, ctypes.POINTER(ctypes.c_void_p))
-        trf.capacity = trb.capacity = la.LA_MAX_TRACE + 1
-        traces.append((trf, evf, trb, evb))
-    for i in range(min(5, warmup)):  # handle creation took a while: back to speed first
-        step(sets[i % n_sets])
+    # on the stream it launches on.  Every repetition has event handles of its own (created
+    # before the timed loops: the device must not sit idle in between); nothing waits until
+    # all of them are enqueued.
     for i, (trf, evf, trb, evb) in enumerate(traces):
         step(sets[i % n_sets], trf, trb)
     torch.cuda.synchronize()
