@@ -1028,6 +1028,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
 // Fast-path backward slot: [S^T (D*D) | z (D) | R (D*D) | u (D) | w (D) | R^T (D*D)], all
 // unscaled sums: S = sum k v^T, z = sum k, R = sum q OmegaHat^T, u = sum delta q,
 // w = sum OmegaHat (Eq. endd without the factors a, b).
+// The descending sweep of fp32 at D = 64 with the mask keeps R once (see kf_bwd_dkv): the
+// R^T part of the slot is then neither written nor scanned.
+template <typename T, int D, bool CAUSAL>
+constexpr bool kSingleR = CAUSAL && sizeof(T) == 4 && D == 64;
+
 template <int D>
 struct BwdSlot {
     static constexpr int ST = 0, Z = D * D, R = D * D + D, U = 2 * D * D + D, W = 2 * D * D + 2 * D,
@@ -1313,7 +1318,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             for (int i = 0; i < 4; ++i) {
                 const int r = rb * 16 + 4 * g + i, j = w * 16 + c;
                 out[SL::R + r * D + j] = accR[rb].get(i);
-                out[SL::RT + j * D + r] = accR[rb].get(i);
+                if constexpr (!kSingleR<T, D, CAUSAL>) out[SL::RT + j * D + r] = accR[rb].get(i);
             }
         if constexpr (F::MS) {
             if (c == 0) {
@@ -1354,7 +1359,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // One LDS block laid out by hand, small arrays first: addresses are then a lane offset
     // plus a constant the instruction can carry, instead of one base register per array.
     constexpr int RM = C * LDR;  // elements of a row-major tile
-    constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ);
+    // fp32 at D = 64 with the mask: the matrix pipe is the limit, and keeping R in both
+    // orientations costs a second rank-C update per chunk (a fifth of the kernel's MFMA
+    // work).  Here R is kept once, in the accumulators as rows r x columns j, and a copy of
+    // it sits in LDS as a row-major tile [r][j]: dK = V R^T contracts over j, which runs
+    // along that tile's rows, so the product takes both operands from LDS.  The copy is
+    // rewritten after every update (16 four-byte stores per lane); its 17 KB are what still
+    // fits next to the other tiles with two workgroups per CU.
+    constexpr bool RL = kSingleR<T, D, CAUSAL>;
+    constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ) + (RL ? D * LDR : 0);
     constexpr int NCS = F::MS ? 0 : 2 * D;  // vector-ALU sums: u and w of the chunk
     __shared__ __align__(16) unsigned char lds[(6 * C + NCS) * 4 + NELEM * sizeof(T)];
     // 1/g, dprime, delta of the chunk's rows: two buffers of [3][C], the next chunk's being
@@ -1365,6 +1378,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     T *CmT = reinterpret_cast<T *>(fac + 6 * C + NCS), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
+    T *Rs = dOs + TS * RM;  // [D][LDR], only if RL
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * D;
@@ -1391,8 +1405,23 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         for (int i = 0; i < 4; ++i) {
             const int row = rb * 16 + 4 * g + i, col = w * 16 + c;
             Ra[rb].set(i, zero_init ? 0.f : slot[SL::R + row * D + col]);
-            Rb[rb].set(i, zero_init ? 0.f : slot[SL::RT + row * D + col]);
+            Rb[rb].set(i, (zero_init || RL) ? 0.f : slot[SL::RT + row * D + col]);
         }
+    // R to its LDS tile: element (r = 16 rb + 4 g + e, j = 16 w + c), with the pair exchange of
+    // the row (FC::flip; it depends on g only).  The 16 lanes of a group cover 64 consecutive
+    // bytes of a row and the two groups of a 32-lane store pass are 16 banks apart.
+    auto publish_R = [&]() {
+        if constexpr (RL) {
+            const int fg = F::flip(4 * g);
+            float *dst = reinterpret_cast<float *>(Rs) + 4 * g * LDR + 16 * w +
+                         4 * ((c / 4) ^ fg) + c % 4;
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[(16 * rb + e) * LDR] = Ra[rb].get(e);
+        }
+    };
+    publish_R();  // read after the two barriers at the top of the first chunk
     // u[16w + 4g + e] = sum delta q and w[16w + 4g + e] = sum OmegaHat, kept up by the rank-C
     // updates (B = Q weighted by delta; B = OmegaHat)
     Blk uacc, wacc;
@@ -1537,8 +1566,14 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         Blk ak[NPB];
 #pragma unroll
         for (int m = 0; m < NPB; ++m) ak[m].zero();
-        if (lo_on) state_product<T, D, NPB>(ak, Rb, Vs, c, g);
-        else state_product<T, D, NPB, 1>(ak, Rb, Vs, c, g);
+        if constexpr (RL) {
+            static_assert(!RL || NPB == 2, "two row blocks per chunk");
+            block_product2<T, D>(ak[0], Rs, w * 16, Vs, 0, ak[1], Rs, w * 16, Vs, 16, c, g);
+        } else if (lo_on) {
+            state_product<T, D, NPB>(ak, Rb, Vs, c, g);
+        } else {
+            state_product<T, D, NPB, 1>(ak, Rb, Vs, c, g);
+        }
         fetch_part(cn, std::integral_constant<int, 2>());
         if constexpr (CAUSAL) __syncthreads();
         const f4v u4 = uacc.v, w4 = a * wacc.v;
@@ -1605,7 +1640,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                 outer_update<T, D, 2, PP, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
             } else {
                 outer_update<T, D, 2, 1, 1>(Ra, QTt, 0, OHt, TSZ, w, c, g, ql, wo, vw_);
-                outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
+                if constexpr (!RL) outer_update<T, D, 2, 1, 1>(Rb, OHt, TSZ, QTt, 0, w, c, g, ql, wo, vu_);
+                // every wave read the copy before the phase barrier of this chunk; the next
+                // read is behind the two barriers at the top of the next chunk
+                publish_R();
             }
             if constexpr (!F::MS) {
                 uacc.v += *reinterpret_cast<const f4v *>(csu + w * 16 + 4 * g);
@@ -1693,8 +1731,8 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     // reverse-running sums left by the ascending sweep
     if (pr.causal) {
         if (nseg > 1) {
-            launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 1, 0,
-                              nseg - 2, st);
+            launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R,
+                              (kSingleR<T, D, true> ? SL::RT : SL::END) - SL::R, 1, 0, nseg - 2, st);
             tc.mark("scan_slots_rev");
         }
         kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
