@@ -1341,7 +1341,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 //   dV_c = tril(W)^T OmegaHat_c + a 1 w^T + b K_c R,  W_in = a + b q_i . k_n
 //   then R += Q_c^T OmegaHat_c, u += sum delta q, w += sum OmegaHat.
 // R is held twice: rows r x columns j for dV (contraction over r) and rows j x
-// columns r for dK (contraction over j).
+// columns r for dK (contraction over j); fp32 at D = 64 holds it once and takes the
+// second orientation from a copy in LDS (RL below).
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
