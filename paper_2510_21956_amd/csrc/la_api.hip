@@ -66,7 +66,34 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
                                 : round_up(slots, 64) * 4;
     p.saved_floats = round_up(DD + D, 64);
     p.saved_bytes = (size_t)BH * p.nseg * p.saved_floats * 4;
+    // fp32 at D = 256 runs as passes of the D = 128 kernels (split_forward / split_backward):
+    // their workspace, plus one float per token-head in the forward pass
+    if (D == 256 && dt == LA_F32) {
+        const Plan h = make_plan(B, H, N, 128, dt, causal, is_backward);
+        const size_t need = h.total_bytes + (is_backward ? 0 : round_up((size_t)BH * N, 64) * 4);
+        if (need > p.total_bytes) p.total_bytes = need;
+    }
     return p;
+}
+
+// Forward and backward pass at D = 256: fp32 on the matrix-core kernels of D = 128, column
+// block by column block; bf16 on the token-serial kernels.
+static la_status forward_256(const Problem &pr, const Plan &pl, int B, int H, const void *Q,
+                             const void *K, const void *V, void *O, float *G, float *ws,
+                             hipStream_t st, Tracer &tc)
+{
+    if (pr.dt != LA_F32) return wide_forward(pr, pl, Q, K, V, O, G, ws, st, tc);
+    const Plan h = make_plan(B, H, pr.N, 128, pr.dt, pr.causal, 0);
+    return split_forward(pr, h, Q, K, V, O, G, ws, st, tc);
+}
+static la_status backward_256(const Problem &pr, const Plan &pl, int B, int H, const void *Q,
+                              const void *K, const void *V, const void *O, const float *G,
+                              const void *dO, void *dQ, void *dK, void *dV, float *ws,
+                              hipStream_t st, Tracer &tc)
+{
+    if (pr.dt != LA_F32) return wide_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+    const Plan h = make_plan(B, H, pr.N, 128, pr.dt, pr.causal, 1);
+    return split_backward(pr, h, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
 }
 
 static la_status check_shape(int B, int H, int N, int D, la_dtype dt)
@@ -250,8 +277,8 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
         return la::fast_forward(pr, pl, Q, K, V, O, G, (float *)workspace, sv,
                                 (hipStream_t)hip_stream, tc);
     if (D == 256)
-        return la::wide_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
-                                (hipStream_t)hip_stream, tc);
+        return la::forward_256(pr, pl, B, H, Q, K, V, O, G, (float *)workspace,
+                               (hipStream_t)hip_stream, tc);
     return la::generic_forward(pr, pl, Q, K, V, O, G, (float *)workspace,
                                (hipStream_t)hip_stream, tc);
 }
@@ -312,7 +339,8 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         s = ffast ? la::fast_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off),
                                      nullptr, st, tc)
             : D == 256
-                ? la::wide_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st, tc)
+                ? la::forward_256(pr, pf, B, H, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
+                                  tc)
                 : la::generic_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off), st,
                                       tc);
         if (s != LA_OK) return s;
@@ -322,7 +350,8 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
     s = fast ? la::fast_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, sv, st,
                                  tc)
         : D == 256
-            ? la::wide_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st, tc)
+            ? la::backward_256(pr, pl, B, H, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
+                               tc)
             : la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
                                    tc);
     if (s != LA_OK || !norm_qk) return s;

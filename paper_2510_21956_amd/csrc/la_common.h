@@ -171,6 +171,13 @@ la_status state_from_totals(const float *ws, float *state, int BH, int D, int ns
                             size_t slot_floats, int N, int accumulate, hipStream_t st);
 
 // Head size 256 (la_wide.hip): token-serial kernels with the state in registers.
+// Head size 256 in fp32 as passes of the D = 128 matrix-core kernels over column blocks of
+// the 256-wide rows; `pl` is the plan of the D = 128 problem (la_fast.hip).
+la_status split_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                        const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
+la_status split_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                         const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                         void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
 // wide_backward with dK == nullptr runs the ascending sweep (dQ) only.
 la_status wide_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                        const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);

@@ -119,7 +119,10 @@ struct FC {
 // 4*rq .. 4*rq+3, rq = row_quad(th), so that it can write the transposed tile with
 // 4-element vectors along the row index.
 // ---------------------------------------------------------------------------
-template <typename T, int D>
+// LD is the distance between consecutive rows of the tensors in memory, in elements: D for
+// the dense [N, D] slices of the library's own layout, more when a call works on a block of
+// columns of wider rows.
+template <typename T, int D, int LD = D>
 struct Stager {
     typedef FC<T, D> F;
     static constexpr int C = F::C;
@@ -147,11 +150,12 @@ struct Stager {
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
         const long rows = (N - c0 < C) ? N - c0 : C;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<T *>(X + (size_t)c0 * D), 0, (int)(rows * D * sizeof(T)), kBufferFlags);
-        const int off = (4 * rq * D + dg * F::EPV) * (int)sizeof(T);
+            const_cast<T *>(X + (size_t)c0 * LD), 0, (int)(((rows - 1) * LD + D) * sizeof(T)),
+            kBufferFlags);
+        const int off = (4 * rq * LD + dg * F::EPV) * (int)sizeof(T);
 #pragma unroll
         for (int i = I0; i < I1; ++i)
-            raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + i * D * (int)sizeof(T), 0, 0);
+            raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + i * LD * (int)sizeof(T), 0, 0);
     }
 
     // Element e of unit u as a float.
@@ -302,8 +306,8 @@ __device__ __forceinline__ float reduce_adjacent(float s)
 // Row normalisation of Sec. 3.3 on a stager's registers: each of the thread's four rows is
 // scaled to unit length (the row is held by the GPR consecutive lanes that share it) and, for
 // bf16, rounded back to the tile's type.  Rows of zeros (past the end of the slice) stay zeros.
-template <typename T, int D>
-__device__ __forceinline__ void normalise_rows(Stager<T, D> &s)
+template <typename T, int D, int LD>
+__device__ __forceinline__ void normalise_rows(Stager<T, D, LD> &s)
 {
     typedef FC<T, D> F;
 #pragma unroll
@@ -676,9 +680,13 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
 // descriptor that covers its first `rows_valid` rows (at most 16, possibly none): stores
 // to rows beyond them are dropped by the address check, without a branch, and the lane's
 // address is one 32-bit offset that does not change from block to block.
+// acc = 1 adds what the block holds already, acc = 2 adds it times old_scale[row] (fp32 only):
+// the calls that work on a block of columns of wider rows build their results up over several
+// launches.
 template <typename T>
 __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_valid, int l,
-                                            float x0, float x1, float x2, float x3)
+                                            float x0, float x1, float x2, float x3, int acc = 0,
+                                            const float *old_scale = nullptr)
 {
     const int src = 16 * (l % 4) + l / 4;  // lane that holds (row l/4, column quad l%4)
     const int row = l / 4, cq = l % 4;
@@ -687,8 +695,15 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
         base, 0, nrows * ld * (int)sizeof(T), kBufferFlags);
     const int off = (row * ld + col0 + 4 * cq) * (int)sizeof(T);
     if constexpr (sizeof(T) == 4) {
-        const u4v v = {__float_as_uint(__shfl(x0, src)), __float_as_uint(__shfl(x1, src)),
-                       __float_as_uint(__shfl(x2, src)), __float_as_uint(__shfl(x3, src))};
+        f4v y = {__shfl(x0, src), __shfl(x1, src), __shfl(x2, src), __shfl(x3, src)};
+        if (acc) {
+            const u4v o = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+            const float sc = acc == 2 ? old_scale[row] : 1.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] += sc * __uint_as_float(o[e]);
+        }
+        const u4v v = {__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]),
+                       __float_as_uint(y[3])};
         __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, off, 0, 0);
     } else {
         bf4v p = to_bf4(f4v{x0, x1, x2, x3});
@@ -703,7 +718,7 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 // factors), written to state slot `seg + slot_shift` as [S | z | p].  The
 // backward pass takes the TRANSPOSED variant, [S^T | z], for its ascending sweep.
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool TRANSPOSED>
+template <typename T, int D, bool TRANSPOSED, int LD = D>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
     int nseg_run, SegMap sm, size_t slot_floats, int slot_shift, int norm)
@@ -713,7 +728,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     __shared__ __align__(16) T KTt[D * LDT];
     __shared__ __align__(16) T VTt[D * LDT];
     const int bh = blockIdx.x / nseg_run, seg = blockIdx.x % nseg_run;
-    const T *Kp = K + (size_t)bh * N * D, *Vp = V + (size_t)bh * N * D;
+    const T *Kp = K + (size_t)bh * N * LD, *Vp = V + (size_t)bh * N * LD;
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
@@ -739,7 +754,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     }
     float vec = 0.f;  // vector-ALU sums: t < D: p[t];  D <= t < 2D: z[t-D]
 
-    Stager<T, D> s1;  // half 0: K, half 1: V
+    Stager<T, D, LD> s1;  // half 0: K, half 1: V
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     s1.load(h0 ? Kp : Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
@@ -782,11 +797,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
 //   f = tril(a + b Q_c K_c^T) V_c + a 1 p^T + b Q_c S ;  g = rowsum(tril) + a n + b Q_c z
 //   then S += K_c^T V_c, z += sum k, p += sum v
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool CAUSAL>
+// With LD != D the call works on D columns of rows LD wide and is one of several launches
+// that build O up (fp32 only):  xflags & XF_RAW: leave the numerator f undivided in O and the
+// launch's own share of g in G;  xflags & XF_ACC: add the f that O holds already and the share
+// of g in Gin before dividing.
+constexpr int XF_RAW = 1, XF_ACC = 2;
+template <typename T, int D, bool CAUSAL, int LD = D>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
-    int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b, int norm)
+    int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b, int norm,
+    int xflags, const float *__restrict__ Gin)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -803,7 +824,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     __shared__ __align__(16) float csv[F::MS ? 4 : D], csk[F::MS ? 4 : D];  // vector-ALU sums
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
-    const size_t base = (size_t)bh * N * D;
+    const size_t base = (size_t)bh * N * LD;
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base;
     T *Op = O + base;
     float *Gp = G + (size_t)bh * N;
@@ -852,7 +873,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     }
 
     // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
-    Stager<T, D> s1, s2;
+    Stager<T, D, LD> s1, s2;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     const T *p1 = (h0 || !CAUSAL) ? Qp : Kp;
     s1.load(p1, row0, N);
@@ -982,10 +1003,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
                 }
             }
             if (l < C) {
-                const float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
-                ginv[w][l] = 1.f / gv;
+                float gv = b * qz + a * (CAUSAL ? (float)c0 : (float)N) + ps;
                 // (32-bit row arithmetic: a segment is far shorter than 2^31 rows)
-                if (w == 0 && G && l < (int)(row1 - c0)) (Gp + c0)[l] = gv;
+                const bool valid = l < (int)(row1 - c0);
+                if constexpr (LD != D) {
+                    if ((xflags & XF_ACC) && valid) gv += (Gin + (size_t)bh * N + c0)[l];
+                    ginv[w][l] = (xflags & XF_RAW) ? 1.f : 1.f / gv;
+                } else {
+                    ginv[w][l] = 1.f / gv;
+                }
+                if (w == 0 && G && valid) (Gp + c0)[l] = gv;
             }
             __builtin_amdgcn_wave_barrier();
             if constexpr (CAUSAL) {
@@ -998,11 +1025,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             const f4v p4 = a * pacc.v;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib)
-                store_block<T>(Op + (size_t)(c0 + ib * 16) * D, D, w * 16,
+                store_block<T>(Op + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
                                (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi[ib],
                                (facc[ib].get(1) + p4[1]) * gi[ib],
                                (facc[ib].get(2) + p4[2]) * gi[ib],
-                               (facc[ib].get(3) + p4[3]) * gi[ib]);
+                               (facc[ib].get(3) + p4[3]) * gi[ib],
+                               (LD != D && (xflags & XF_ACC)) ? 2 : 0, &ginv[w][ib * 16]);
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
@@ -1052,13 +1080,14 @@ struct BwdSlot {
 // (Eq. endd without the factors), which it leaves in the slot of the segment
 // that will start from them.
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool CAUSAL>
+// With LD != D (see kf_fwd_apply): xflags & 1 adds the results to what dQ holds already.
+template <typename T, int D, bool CAUSAL, int LD = D>
 __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4) ? 2 : 3)) void kf_bwd_dq(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
     T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
     float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b,
-    int norm)
+    int norm, int xflags)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1078,7 +1107,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
-    const size_t base = (size_t)bh * N * D;
+    const size_t base = (size_t)bh * N * LD;
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
     T *dQp = dQ + base;
     const float *Gp = G + (size_t)bh * N;
@@ -1125,7 +1154,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 
     // staging: half 0: dO (rows, scaled columns) and O (for dprime);
     //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
-    Stager<T, D> s1, s2, s3;
+    Stager<T, D, LD> s1, s2, s3;
     float g_next;  // g of row t % C of the chunk being fetched
     const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
@@ -1286,11 +1315,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
                 const float f = b * sc[ii];
-                store_block<T>(dQp + (size_t)(c0 + ib * 16) * D, D, w * 16,
+                store_block<T>(dQp + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
                                (int)(row1 - c0) - ib * 16, l, f * (acc[ii].get(0) - di[ii] * z4[0]),
                                f * (acc[ii].get(1) - di[ii] * z4[1]),
                                f * (acc[ii].get(2) - di[ii] * z4[2]),
-                               f * (acc[ii].get(3) - di[ii] * z4[3]));
+                               f * (acc[ii].get(3) - di[ii] * z4[3]),
+                               (LD != D && (xflags & 1)) ? 1 : 0);
             }
             if (i0 == 0) fetch_part(cn, std::integral_constant<int, 2>());
         }
@@ -1344,12 +1374,13 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 // columns r for dK (contraction over j); fp32 at D = 64 holds it once and takes the
 // second orientation from a copy in LDS (RL below).
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool CAUSAL>
+// With LD != D (see kf_fwd_apply): xflags & 2 adds to what dK holds already, xflags & 4 to dV.
+template <typename T, int D, bool CAUSAL, int LD = D>
 __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
     const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, SegMap sm,
-    size_t slot_floats, float a, float b, int norm)
+    size_t slot_floats, float a, float b, int norm, int xflags)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1382,7 +1413,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     T *Rs = dOs + TS * RM;  // [D][LDR], only if RL
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
-    const size_t base = (size_t)bh * N * D;
+    const size_t base = (size_t)bh * N * LD;
     const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *dOp = dO + base;
     T *dKp = dK + base, *dVp = dV + base;
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
@@ -1442,7 +1473,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // columns) and the row factors; unmasked: K and V only
     const long nchunks = (row1 - row0 + C - 1) / C;
     const int dg = (t % F::HT) % F::GPR, rq = F::row_quad(t % F::HT);  // staging unit and row quad
-    Stager<T, D> s1, s2;
+    Stager<T, D, LD> s1, s2;
     const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
     float g_next = 1.f, d_next = 0.f;  // g, dprime of row t % C of the chunk being fetched
     // Part k of the request for the chunk at c0 (see Stager::load); the row factors come
@@ -1594,10 +1625,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                             chunk_product<T, D, 1, 1>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                     }
-                    store_block<T>(dKp + (size_t)(c0 + nb * 16) * D, D, w * 16,
+                    store_block<T>(dKp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
                                    b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
-                                   b * (ak[m].get(3) - u4[3]));
+                                   b * (ak[m].get(3) - u4[3]),
+                                   (LD != D && (xflags & 2)) ? 1 : 0);
                 }
             }
             fetch_part(cn, std::integral_constant<int, 3>());
@@ -1625,9 +1657,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                         }
                     }
-                    store_block<T>(dVp + (size_t)(c0 + nb * 16) * D, D, w * 16,
+                    store_block<T>(dVp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
-                                   av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3]);
+                                   av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3],
+                                   (LD != D && (xflags & 4)) ? 1 : 0);
                 }
             }
         }
@@ -1661,10 +1694,10 @@ inline la_status launch_status()
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
-template <typename T, int D>
+template <typename T, int D, int LD = D>
 la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, void *Ov, float *G, float *ws, float *saved, hipStream_t st,
-                   Tracer &tc)
+                   Tracer &tc, int xflags = 0, const float *Gin = nullptr)
 {
     constexpr int NT = FC<T, D>::NT;
     const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv;
@@ -1672,7 +1705,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const int nseg = pl.nseg;
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
-        kf_kv_state<T, D, false><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
+        kf_kv_state<T, D, false, LD><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("fwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, D * D + 2 * D, pr.causal ? 0 : 2,
@@ -1680,23 +1713,23 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
         tc.mark("scan_slots");
     }
     if (pr.causal)
-        kf_fwd_apply<T, D, true><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
+        kf_fwd_apply<T, D, true, LD><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, pr.norm_qk);
+            pr.b, pr.norm_qk, xflags, Gin);
     else
-        kf_fwd_apply<T, D, false><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
+        kf_fwd_apply<T, D, false, LD><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, pr.norm_qk);
+            pr.b, pr.norm_qk, xflags, Gin);
     tc.mark("fwd_apply");
     return launch_status();
 }
 
 // dq_only: stop after the ascending sweep (dQ and the per-row o . dO); the caller wants dQ alone.
-template <typename T, int D>
+template <typename T, int D, int LD = D>
 la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
                    void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc,
-                   bool dq_only = false)
+                   bool dq_only = false, int xflags = 0)
 {
     typedef BwdSlot<D> SL;
     constexpr int NT = FC<T, D>::NT;
@@ -1710,7 +1743,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     // per-segment sums (none needed from a masked pass's last segment) and a scan here
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (!saved && nrun > 0) {
-        kf_kv_state<T, D, true><<<dim3(pr.BH * nrun), block, 0, st>>>(
+        kf_kv_state<T, D, true, LD><<<dim3(pr.BH * nrun), block, 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("bwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST,
@@ -1720,13 +1753,13 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const float *sinit = saved ? saved : ws;
     const size_t sinit_floats = saved ? pl.saved_floats : pl.slot_floats;
     if (pr.causal)
-        kf_bwd_dq<T, D, true><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
-                                                      sinit_floats, dprime, pr.N, nseg,
-                                                      pl.map, pl.slot_floats, pr.b, pr.norm_qk);
+        kf_bwd_dq<T, D, true, LD><<<grid, block, 0, st>>>(
+            Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
+            pl.slot_floats, pr.b, pr.norm_qk, xflags);
     else
-        kf_bwd_dq<T, D, false><<<grid, block, 0, st>>>(Q, K, V, O, G, dO, dQ, ws, sinit,
-                                                       sinit_floats, dprime, pr.N, nseg,
-                                                       pl.map, pl.slot_floats, pr.b, pr.norm_qk);
+        kf_bwd_dq<T, D, false, LD><<<grid, block, 0, st>>>(
+            Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
+            pl.slot_floats, pr.b, pr.norm_qk, xflags);
     tc.mark("bwd_dq");
     if (dq_only) return launch_status();
     // reverse-running sums left by the ascending sweep
@@ -1736,16 +1769,16 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
                               (kSingleR<T, D, true> ? SL::RT : SL::END) - SL::R, 1, 0, nseg - 2, st);
             tc.mark("scan_slots_rev");
         }
-        kf_bwd_dkv<T, D, true><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
-                                                       nseg, pl.map, pl.slot_floats, pr.a,
-                                                       pr.b, pr.norm_qk);
+        kf_bwd_dkv<T, D, true, LD><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
+                                                           pr.N, nseg, pl.map, pl.slot_floats,
+                                                           pr.a, pr.b, pr.norm_qk, xflags);
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
-        kf_bwd_dkv<T, D, false><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime, pr.N,
-                                                        nseg, pl.map, pl.slot_floats, pr.a,
-                                                        pr.b, pr.norm_qk);
+        kf_bwd_dkv<T, D, false, LD><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
+                                                            pr.N, nseg, pl.map, pl.slot_floats,
+                                                            pr.a, pr.b, pr.norm_qk, xflags);
     }
     tc.mark("bwd_dkv");
     return launch_status();
@@ -1791,6 +1824,64 @@ la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, con
     if (pr.dt == LA_BF16 && pr.D == 128)
         return fast_bwd<__bf16, 128>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
     return LA_ERR_UNSUPPORTED;
+}
+
+// Head size 256 in fp32 on the D = 128 kernels.  With q = [q1 q2], k = [k1 k2] (halves of
+// 128) the weight a + b q.k is (a + b q1.k1) + (0 + b q2.k2), and with v = [v1 v2] every sum
+// of Sec. 3.1 / 3.2 splits into blocks: the numerator of output half j is the sum over i of
+// the numerators of the D = 128 problems (q_i, k_i, v_j) with coefficients (a, b) for i = 1
+// and (0, b) for i = 2, g is the sum of their denominators, and likewise
+//   dq_i = sum_j dq(q_i, k_i, v_j; o_j, dO_j, g),   dk_i = sum_j dk(...),   dv_j = sum_i dv(...)
+// where the blocks (o_j, dO_j) and the full g stand for the stored set of the block problem
+// (delta = o . OmegaHat splits over j as well).  Four passes of the D = 128 kernels over column
+// blocks of the 256-wide rows, each adding to what the previous ones left in the outputs.
+// `pl` is the plan of the D = 128 problem; the forward pass keeps the first pass's share of g
+// in B*H*N floats behind that plan's workspace.
+la_status split_forward(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
+                        const void *Vv, void *Ov, float *G, float *ws, hipStream_t st, Tracer &tc)
+{
+    const float *Q = (const float *)Qv, *K = (const float *)Kv, *V = (const float *)Vv;
+    float *O = (float *)Ov;
+    float *gpart = ws + pl.total_bytes / sizeof(float);
+    Problem p = pr;
+    p.D = 128;
+    Tracer quiet(nullptr, st);  // the caller's trace gets one mark per pass, not per kernel
+    for (int j = 0; j < 2; ++j) {
+        p.a = pr.a;
+        la_status s = fast_fwd<float, 128, 256>(p, pl, Q, K, V + 128 * j, O + 128 * j, gpart, ws,
+                                                nullptr, st, quiet, XF_RAW, nullptr);
+        if (s != LA_OK) return s;
+        tc.mark("fwd_block_pass");
+        p.a = 0.f;
+        s = fast_fwd<float, 128, 256>(p, pl, Q + 128, K + 128, V + 128 * j, O + 128 * j,
+                                      j == 1 ? G : nullptr, ws, nullptr, st, quiet, XF_ACC, gpart);
+        if (s != LA_OK) return s;
+        tc.mark("fwd_block_pass");
+    }
+    return LA_OK;
+}
+
+la_status split_backward(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
+                         const void *Vv, const void *Ov, const float *G, const void *dOv,
+                         void *dQv, void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
+{
+    const float *Q = (const float *)Qv, *K = (const float *)Kv, *V = (const float *)Vv,
+                *O = (const float *)Ov, *dO = (const float *)dOv;
+    float *dQ = (float *)dQv, *dK = (float *)dKv, *dV = (float *)dVv;
+    Problem p = pr;
+    p.D = 128;
+    Tracer quiet(nullptr, st);  // the caller's trace gets one mark per pass, not per kernel
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            p.a = i == 0 ? pr.a : 0.f;
+            const int xflags = (j == 1 ? 1 | 2 : 0) | (i == 1 ? 4 : 0);
+            const la_status s = fast_bwd<float, 128, 256>(
+                p, pl, Q + 128 * i, K + 128 * i, V + 128 * j, O + 128 * j, G, dO + 128 * j,
+                dQ + 128 * i, dK + 128 * i, dV + 128 * j, ws, nullptr, st, quiet, false, xflags);
+            if (s != LA_OK) return s;
+            tc.mark("bwd_block_pass");
+        }
+    return LA_OK;
 }
 
 bool fast_supported(const Problem &pr, int is_backward)

@@ -149,7 +149,8 @@ def test_optional_saved_set(la, knobs):
     The recomputation runs the same kernels on the same plan, so gradients must equal the
     chained run's bit for bit."""
     for (B, H, N, D, dtype, seg) in ((2, 2, 700, 64, "f32", 0), (1, 2, 333, 128, "bf16", 64),
-                                     (1, 2, 100, 32, "f32", 0)):
+                                     (1, 2, 100, 32, "f32", 0), (1, 2, 200, 256, "f32", 64),
+                                     (1, 1, 130, 256, "bf16", 0)):
         knobs(seg, 0)
         for causal in (True, False):
             print("case optional", B, H, N, D, dtype, seg, causal, flush=True)
