@@ -235,6 +235,23 @@ def extras(torch, wl, la):
                                   cfg.b, cfg.causal, wsb), 30)}
     del t, wsf, wsb
     torch.cuda.empty_cache()
+    # the same with bf16 tensors (fp32 tiles on chip): the shape that stands in for an LLM layer
+    cfg4 = wl.CONFIGS[3]
+    t = make_device_inputs(cfg4, torch, 1)[0]
+    t["Q"] = (t["Q"] * 3.0).contiguous()
+    t["K"] = (t["K"] * 0.25).contiguous()
+    b6 = (cfg4.B, cfg4.H, cfg4.N, cfg4.D, la.LA_BF16, cfg4.causal)
+    wsf = torch.empty(la.la_workspace_bytes(*b6, 0), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(la.la_workspace_bytes(*b6, 1), dtype=torch.uint8, device="cuda")
+
+    def qknorm_step_bf16():
+        la.la_forward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg4.a, cfg4.b, cfg4.causal,
+                             wsf)
+        la.la_backward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
+                              t["dV"], cfg4.a, cfg4.b, cfg4.causal, wsb)
+    res["qknorm_fwd_bwd_" + cfg4.name] = {"ms_per_step": timed(qknorm_step_bf16, 30)}
+    del t, wsf, wsb
+    torch.cuda.empty_cache()
     # head size 256: the top of the paper's head-size sweep
     c = wl.find_workload("paper_causal_f32_B4_H16_N4096_D256")
     t = make_device_inputs(c, torch, 1)[0]

@@ -137,7 +137,9 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
  * Arguments, workspace sizes (la_workspace_bytes with is_backward 0 / 1, or 2 when O or G is
  * NULL) and error behaviour as for la_forward_traced / la_backward_traced; O and G are those
  * of la_forward_qknorm.  A row of zeros stays a row of zeros (and makes g_i = a n_i for it).
- * With bfloat16 the normalised rows are rounded to bfloat16 once more when they are staged.
+ * With bfloat16 tensors these calls keep their on-chip tiles in float32, so that the
+ * normalised rows are not rounded to bfloat16 again (about three times the time of the
+ * plain bfloat16 calls).
  */
 LA_API la_status la_forward_qknorm(const void *Q, const void *K, const void *V,
                      void *O, float *G,

@@ -144,11 +144,6 @@ static bool use_fast(const Problem &pr, int is_backward)
     return fast_supported(pr, is_backward);
 }
 
-// bfloat16 with the normalisation inside the call runs on the plain-ALU kernels, whose tiles
-// are float32: rounding the normalised rows back to bfloat16, as the matrix-core kernels'
-// tiles would, costs the early rows of dQ, dK up to twice the error allowance (measured on the
-// CPU with the oracle fed rounded normalised rows).
-static bool norm_needs_wide_tiles(const Problem &pr) { return pr.norm_qk && pr.dt == LA_BF16; }
 
 // Extra workspace of a backward pass that recomputes O and g (either handed in as NULL):
 // the forward pass's own workspace, then O, then g, each rounded up to 256 bytes.
@@ -255,7 +250,7 @@ static la_status forward_impl(const void *Q, const void *K, const void *V, void 
     if (!workspace || workspace_bytes < pl.total_bytes || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt, norm_qk};
-    const bool fast = la::use_fast(pr, 0) && !la::norm_needs_wide_tiles(pr);
+    const bool fast = la::use_fast(pr, 0);
     if (!fast) pl.map.cost_seg = 0;  // the plain-ALU kernels cut uniformly (same segment count)
     float *sv = nullptr;
     if (save && fast && la::use_fast(pr, 1)) {
@@ -309,7 +304,7 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
     if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255u))
         return LA_ERR_WORKSPACE;
     la::Problem pr{B * H, N, D, a, b, causal ? 1 : 0, dt, norm_qk};
-    const bool fast = la::use_fast(pr, 1) && !la::norm_needs_wide_tiles(pr);
+    const bool fast = la::use_fast(pr, 1);
     if (!fast) {  // the plain-ALU kernels cut uniformly (same segment count)
         pl.map.cost_seg = 0;
         pf.map.cost_seg = 0;
@@ -335,7 +330,7 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
         char *wsb = (char *)workspace;
         void *o2 = wsb + rc.o_off;
         float *g2 = (float *)(wsb + rc.g_off);
-        const bool ffast = la::use_fast(pr, 0) && !la::norm_needs_wide_tiles(pr);
+        const bool ffast = la::use_fast(pr, 0);
         s = ffast ? la::fast_forward(pr, pf, Q, K, V, o2, g2, (float *)(wsb + rc.fwd_ws_off),
                                      nullptr, st, tc)
             : D == 256

@@ -122,9 +122,15 @@ struct FC {
 // LD is the distance between consecutive rows of the tensors in memory, in elements: D for
 // the dense [N, D] slices of the library's own layout, more when a call works on a block of
 // columns of wider rows.
-template <typename T, int D, int LD = D>
+// TIO is the element type of the tensors in memory: T, or bfloat16 under fp32 tiles (the
+// calls that normalise Q and K inside the kernels keep the normalised rows in fp32).  A
+// thread's unit is then 8 bytes of memory, widened to four floats by widen() when the tile
+// is about to be written.
+template <typename T, int D, int LD = D, typename TIO = T>
 struct Stager {
     typedef FC<T, D> F;
+    static_assert(sizeof(TIO) == sizeof(T) || (sizeof(T) == 4 && sizeof(TIO) == 2), "I/O type");
+    static constexpr bool MIXED = sizeof(TIO) != sizeof(T);
     static constexpr int C = F::C;
     u4v raw[4];
 
@@ -145,17 +151,39 @@ struct Stager {
     // issue of their loads for a fifth of the chunk's time.  The kernels therefore request the
     // next chunk two rows per thread at a time, at points spread over the current chunk's work.
     template <int I0 = 0, int I1 = 4>
-    __device__ __forceinline__ void load(const T *X, long c0, int N)
+    __device__ __forceinline__ void load(const TIO *X, long c0, int N)
     {
         const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
         const long rows = (N - c0 < C) ? N - c0 : C;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<T *>(X + (size_t)c0 * LD), 0, (int)(((rows - 1) * LD + D) * sizeof(T)),
+            const_cast<TIO *>(X + (size_t)c0 * LD), 0, (int)(((rows - 1) * LD + D) * sizeof(TIO)),
             kBufferFlags);
-        const int off = (4 * rq * LD + dg * F::EPV) * (int)sizeof(T);
+        const int off = (4 * rq * LD + dg * F::EPV) * (int)sizeof(TIO);
 #pragma unroll
-        for (int i = I0; i < I1; ++i)
-            raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + i * LD * (int)sizeof(T), 0, 0);
+        for (int i = I0; i < I1; ++i) {
+            if constexpr (MIXED) {
+                const u2v h = __builtin_amdgcn_raw_buffer_load_b64(
+                    rsrc, off + i * LD * (int)sizeof(TIO), 0, 0);
+                raw[i][0] = h[0];
+                raw[i][1] = h[1];
+            } else {
+                raw[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rsrc, off + i * LD * (int)sizeof(TIO), 0, 0);
+            }
+        }
+    }
+
+    // bfloat16 units as loaded -> four floats each, in place (no-op unless MIXED).  Called at
+    // the start of staging, a chunk after the loads were issued.
+    __device__ __forceinline__ void widen()
+    {
+        if constexpr (MIXED) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w0 = raw[i][0], w1 = raw[i][1];
+                raw[i] = u4v{w0 << 16, w0 & 0xffff0000u, w1 << 16, w1 & 0xffff0000u};
+            }
+        }
     }
 
     // Element e of unit u as a float.
@@ -306,8 +334,8 @@ __device__ __forceinline__ float reduce_adjacent(float s)
 // Row normalisation of Sec. 3.3 on a stager's registers: each of the thread's four rows is
 // scaled to unit length (the row is held by the GPR consecutive lanes that share it) and, for
 // bf16, rounded back to the tile's type.  Rows of zeros (past the end of the slice) stay zeros.
-template <typename T, int D, int LD>
-__device__ __forceinline__ void normalise_rows(Stager<T, D, LD> &s)
+template <typename T, int D, int LD, typename TIO>
+__device__ __forceinline__ void normalise_rows(Stager<T, D, LD, TIO> &s)
 {
     typedef FC<T, D> F;
 #pragma unroll
@@ -718,9 +746,9 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
 // factors), written to state slot `seg + slot_shift` as [S | z | p].  The
 // backward pass takes the TRANSPOSED variant, [S^T | z], for its ascending sweep.
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool TRANSPOSED, int LD = D>
+template <typename T, int D, bool TRANSPOSED, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
-    const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ ws, int N, int nseg,
+    const TIO *__restrict__ K, const TIO *__restrict__ V, float *__restrict__ ws, int N, int nseg,
     int nseg_run, SegMap sm, size_t slot_floats, int slot_shift, int norm)
 {
     typedef FC<T, D> F;
@@ -728,7 +756,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     __shared__ __align__(16) T KTt[D * LDT];
     __shared__ __align__(16) T VTt[D * LDT];
     const int bh = blockIdx.x / nseg_run, seg = blockIdx.x % nseg_run;
-    const T *Kp = K + (size_t)bh * N * LD, *Vp = V + (size_t)bh * N * LD;
+    const TIO *Kp = K + (size_t)bh * N * LD, *Vp = V + (size_t)bh * N * LD;
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
     const int w = __builtin_amdgcn_readfirstlane(t / 64);  // wave index, known to be uniform
@@ -754,11 +782,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
     }
     float vec = 0.f;  // vector-ALU sums: t < D: p[t];  D <= t < 2D: z[t-D]
 
-    Stager<T, D, LD> s1;  // half 0: K, half 1: V
+    Stager<T, D, LD, TIO> s1;  // half 0: K, half 1: V
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     s1.load(h0 ? Kp : Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();
+        s1.widen();
         if (norm && h0) normalise_rows(s1);  // K
         s1.store_cols(h0 ? KTt : VTt);
         __syncthreads();
@@ -802,9 +831,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
 // launch's own share of g in G;  xflags & XF_ACC: add the f that O holds already and the share
 // of g in Gin before dividing.
 constexpr int XF_RAW = 1, XF_ACC = 2;
-template <typename T, int D, bool CAUSAL, int LD = D>
+template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
-    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, T *__restrict__ O,
+    const TIO *__restrict__ Q, const TIO *__restrict__ K, const TIO *__restrict__ V,
+    TIO *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
     int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b, int norm,
     int xflags, const float *__restrict__ Gin)
@@ -825,8 +855,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * LD;
-    const T *Qp = Q + base, *Kp = K + base, *Vp = V + base;
-    T *Op = O + base;
+    const TIO *Qp = Q + base, *Kp = K + base, *Vp = V + base;
+    TIO *Op = O + base;
     float *Gp = G + (size_t)bh * N;
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
@@ -873,14 +903,16 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     }
 
     // staging: half 0: Q (rows) then V (columns); half 1: K (rows and columns)
-    Stager<T, D, LD> s1, s2;
+    Stager<T, D, LD, TIO> s1, s2;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
-    const T *p1 = (h0 || !CAUSAL) ? Qp : Kp;
+    const TIO *p1 = (h0 || !CAUSAL) ? Qp : Kp;
     s1.load(p1, row0, N);
     if constexpr (CAUSAL) s2.load(Vp, row0, N);
     for (long c0 = row0; c0 < row1; c0 += C) {
         __syncthreads();  // every wave is done with the previous chunk's tiles
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of the weights: early rows
+        s1.widen();
+        if constexpr (CAUSAL) s2.widen();
         if (norm) normalise_rows(s1);  // Q or K, whichever this half stages
         if (h0) {
             s1.store_rows(Qs);
@@ -1025,7 +1057,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             const f4v p4 = a * pacc.v;
 #pragma unroll
             for (int ib = 0; ib < NB; ++ib)
-                store_block<T>(Op + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
+                store_block<TIO>(Op + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
                                (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi[ib],
                                (facc[ib].get(1) + p4[1]) * gi[ib],
                                (facc[ib].get(2) + p4[2]) * gi[ib],
@@ -1081,11 +1113,11 @@ struct BwdSlot {
 // that will start from them.
 // ---------------------------------------------------------------------------
 // With LD != D (see kf_fwd_apply): xflags & 1 adds the results to what dQ holds already.
-template <typename T, int D, bool CAUSAL, int LD = D>
+template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4) ? 2 : 3)) void kf_bwd_dq(
-    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
-    const T *__restrict__ O, const float *__restrict__ G, const T *__restrict__ dO,
-    T *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
+    const TIO *__restrict__ Q, const TIO *__restrict__ K, const TIO *__restrict__ V,
+    const TIO *__restrict__ O, const float *__restrict__ G, const TIO *__restrict__ dO,
+    TIO *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
     float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b,
     int norm, int xflags)
 {
@@ -1108,8 +1140,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * LD;
-    const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
-    T *dQp = dQ + base;
+    const TIO *Qp = Q + base, *Kp = K + base, *Vp = V + base, *Op = O + base, *dOp = dO + base;
+    TIO *dQp = dQ + base;
     const float *Gp = G + (size_t)bh * N;
     float *dp = dprime + (size_t)bh * N;
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
@@ -1154,9 +1186,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 
     // staging: half 0: dO (rows, scaled columns) and O (for dprime);
     //          half 1: V (rows and columns), K and Q (columns); unmasked: Q only
-    Stager<T, D, LD> s1, s2, s3;
+    Stager<T, D, LD, TIO> s1, s2, s3;
     float g_next;  // g of row t % C of the chunk being fetched
-    const T *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
+    const TIO *p1 = h0 ? dOp : (CAUSAL ? Vp : Qp), *p2 = (h0 || !CAUSAL) ? Op : Kp;
     const long c_last = row0 + (row1 - row0 - 1) / C * C;  // start of the segment's last chunk
     // Part k of the request for the chunk at c0 (see Stager::load): six parts with the mask,
     // four without; g comes with the first, it is needed before the chunk ends.
@@ -1203,6 +1235,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         __syncthreads();
         const float *rs = rsb[par];
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
+        s1.widen();
+        s2.widen();
+        if constexpr (CAUSAL) s3.widen();
         if (norm && !h0) {
             if constexpr (CAUSAL) {
                 normalise_rows(s2);  // K
@@ -1315,7 +1350,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
                 const float f = b * sc[ii];
-                store_block<T>(dQp + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
+                store_block<TIO>(dQp + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
                                (int)(row1 - c0) - ib * 16, l, f * (acc[ii].get(0) - di[ii] * z4[0]),
                                f * (acc[ii].get(1) - di[ii] * z4[1]),
                                f * (acc[ii].get(2) - di[ii] * z4[2]),
@@ -1375,10 +1410,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 // second orientation from a copy in LDS (RL below).
 // ---------------------------------------------------------------------------
 // With LD != D (see kf_fwd_apply): xflags & 2 adds to what dK holds already, xflags & 4 to dV.
-template <typename T, int D, bool CAUSAL, int LD = D>
+template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
-    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V,
-    const float *__restrict__ G, const T *__restrict__ dO, T *__restrict__ dK, T *__restrict__ dV,
+    const TIO *__restrict__ Q, const TIO *__restrict__ K, const TIO *__restrict__ V,
+    const float *__restrict__ G, const TIO *__restrict__ dO, TIO *__restrict__ dK,
+    TIO *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, SegMap sm,
     size_t slot_floats, float a, float b, int norm, int xflags)
 {
@@ -1414,8 +1450,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
     const size_t base = (size_t)bh * N * LD;
-    const T *Qp = Q + base, *Kp = K + base, *Vp = V + base, *dOp = dO + base;
-    T *dKp = dK + base, *dVp = dV + base;
+    const TIO *Qp = Q + base, *Kp = K + base, *Vp = V + base, *dOp = dO + base;
+    TIO *dKp = dK + base, *dVp = dV + base;
     const float *Gp = G + (size_t)bh * N, *dp = dprime + (size_t)bh * N;
     const long row0 = seg_row(sm, seg, nseg, N), row1 = seg_row(sm, seg + 1, nseg, N);
     const int t = threadIdx.x, l = t % 64, c = l % 16, g = l / 16;
@@ -1473,8 +1509,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     // columns) and the row factors; unmasked: K and V only
     const long nchunks = (row1 - row0 + C - 1) / C;
     const int dg = (t % F::HT) % F::GPR, rq = F::row_quad(t % F::HT);  // staging unit and row quad
-    Stager<T, D, LD> s1, s2;
-    const T *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
+    Stager<T, D, LD, TIO> s1, s2;
+    const TIO *p1 = h0 ? Kp : Vp, *p2 = h0 ? Qp : dOp;
     float g_next = 1.f, d_next = 0.f;  // g, dprime of row t % C of the chunk being fetched
     // Part k of the request for the chunk at c0 (see Stager::load); the row factors come
     // with the first, they are needed before the chunk ends.  The unmasked kernel is bound
@@ -1520,6 +1556,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         const float *rs = fac + par * 3 * C, *dl = rs + C, *dls = dl + C;
         const bool lo_on = PP == 2 && c0 < sm.lo_rows;  // second plane of weights and OmegaHat
         __syncthreads();
+        s1.widen();
+        if constexpr (CAUSAL) s2.widen();
         if (norm && h0) {
             normalise_rows(s1);  // K
             if constexpr (CAUSAL) normalise_rows(s2);  // Q
@@ -1625,7 +1663,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                             chunk_product<T, D, 1, 1>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                     }
-                    store_block<T>(dKp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
+                    store_block<TIO>(dKp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
                                    b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
                                    b * (ak[m].get(3) - u4[3]),
@@ -1657,7 +1695,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                         }
                     }
-                    store_block<T>(dVp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
+                    store_block<TIO>(dVp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
                                    (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
                                    av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3],
                                    (LD != D && (xflags & 4)) ? 1 : 0);
@@ -1694,18 +1732,18 @@ inline la_status launch_status()
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
-template <typename T, int D, int LD = D>
+template <typename T, int D, int LD = D, typename TIO = T>
 la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, void *Ov, float *G, float *ws, float *saved, hipStream_t st,
                    Tracer &tc, int xflags = 0, const float *Gin = nullptr)
 {
     constexpr int NT = FC<T, D>::NT;
-    const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv;
-    T *O = (T *)Ov;
+    const TIO *Q = (const TIO *)Qv, *K = (const TIO *)Kv, *V = (const TIO *)Vv;
+    TIO *O = (TIO *)Ov;
     const int nseg = pl.nseg;
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (nrun > 0) {
-        kf_kv_state<T, D, false, LD><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
+        kf_kv_state<T, D, false, LD, TIO><<<dim3(pr.BH * nrun), dim3(NT), 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("fwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, 0, D * D + 2 * D, pr.causal ? 0 : 2,
@@ -1713,11 +1751,11 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
         tc.mark("scan_slots");
     }
     if (pr.causal)
-        kf_fwd_apply<T, D, true, LD><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
+        kf_fwd_apply<T, D, true, LD, TIO><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
             pr.b, pr.norm_qk, xflags, Gin);
     else
-        kf_fwd_apply<T, D, false, LD><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
+        kf_fwd_apply<T, D, false, LD, TIO><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
             pr.b, pr.norm_qk, xflags, Gin);
     tc.mark("fwd_apply");
@@ -1725,7 +1763,7 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
 }
 
 // dq_only: stop after the ascending sweep (dQ and the per-row o . dO); the caller wants dQ alone.
-template <typename T, int D, int LD = D>
+template <typename T, int D, int LD = D, typename TIO = T>
 la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
                    void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc,
@@ -1733,9 +1771,9 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
 {
     typedef BwdSlot<D> SL;
     constexpr int NT = FC<T, D>::NT;
-    const T *Q = (const T *)Qv, *K = (const T *)Kv, *V = (const T *)Vv, *O = (const T *)Ov,
-            *dO = (const T *)dOv;
-    T *dQ = (T *)dQv, *dK = (T *)dKv, *dV = (T *)dVv;
+    const TIO *Q = (const TIO *)Qv, *K = (const TIO *)Kv, *V = (const TIO *)Vv,
+              *O = (const TIO *)Ov, *dO = (const TIO *)dOv;
+    TIO *dQ = (TIO *)dQv, *dK = (TIO *)dKv, *dV = (TIO *)dVv;
     const int nseg = pl.nseg;
     float *dprime = ws + pl.delta_offset_floats;
     const dim3 grid(pr.BH * nseg), block(NT);
@@ -1743,7 +1781,7 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     // per-segment sums (none needed from a masked pass's last segment) and a scan here
     const int nrun = pr.causal ? nseg - 1 : nseg;
     if (!saved && nrun > 0) {
-        kf_kv_state<T, D, true, LD><<<dim3(pr.BH * nrun), block, 0, st>>>(
+        kf_kv_state<T, D, true, LD, TIO><<<dim3(pr.BH * nrun), block, 0, st>>>(
             K, V, ws, pr.N, nseg, nrun, pl.map, pl.slot_floats, pr.causal ? 1 : 0, pr.norm_qk);
         tc.mark("bwd_state");
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::ST, SL::R - SL::ST,
@@ -1753,11 +1791,11 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     const float *sinit = saved ? saved : ws;
     const size_t sinit_floats = saved ? pl.saved_floats : pl.slot_floats;
     if (pr.causal)
-        kf_bwd_dq<T, D, true, LD><<<grid, block, 0, st>>>(
+        kf_bwd_dq<T, D, true, LD, TIO><<<grid, block, 0, st>>>(
             Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
             pl.slot_floats, pr.b, pr.norm_qk, xflags);
     else
-        kf_bwd_dq<T, D, false, LD><<<grid, block, 0, st>>>(
+        kf_bwd_dq<T, D, false, LD, TIO><<<grid, block, 0, st>>>(
             Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
             pl.slot_floats, pr.b, pr.norm_qk, xflags);
     tc.mark("bwd_dq");
@@ -1769,14 +1807,14 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
                               (kSingleR<T, D, true> ? SL::RT : SL::END) - SL::R, 1, 0, nseg - 2, st);
             tc.mark("scan_slots_rev");
         }
-        kf_bwd_dkv<T, D, true, LD><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
+        kf_bwd_dkv<T, D, true, LD, TIO><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
                                                            pr.N, nseg, pl.map, pl.slot_floats,
                                                            pr.a, pr.b, pr.norm_qk, xflags);
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
-        kf_bwd_dkv<T, D, false, LD><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
+        kf_bwd_dkv<T, D, false, LD, TIO><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
                                                             pr.N, nseg, pl.map, pl.slot_floats,
                                                             pr.a, pr.b, pr.norm_qk, xflags);
     }
@@ -1895,6 +1933,14 @@ la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const 
                         void *dK, void *dV, float *ws, const float *saved, hipStream_t st,
                         Tracer &tc)
 {
+    if (pr.dt == LA_BF16 && pr.norm_qk) {  // normalised rows stay fp32: fp32 tiles, bf16 in memory
+        if (pr.D == 64)
+            return fast_bwd<float, 64, 64, __bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved,
+                                                   st, tc);
+        if (pr.D == 128)
+            return fast_bwd<float, 128, 128, __bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws,
+                                                     saved, st, tc);
+    }
     if (pr.dt == LA_F32 && pr.D == 64)
         return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_F32 && pr.D == 128)
@@ -1910,6 +1956,12 @@ la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const v
                        const void *V, void *O, float *G, float *ws, float *saved, hipStream_t st,
                        Tracer &tc)
 {
+    if (pr.dt == LA_BF16 && pr.norm_qk) {  // normalised rows stay fp32: fp32 tiles, bf16 in memory
+        if (pr.D == 64)
+            return fast_fwd<float, 64, 64, __bf16>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
+        if (pr.D == 128)
+            return fast_fwd<float, 128, 128, __bf16>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
+    }
     if (pr.dt == LA_F32) {
         if (pr.D == 64) return fast_fwd<float, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 128) return fast_fwd<float, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
