@@ -252,17 +252,22 @@ def extras(torch, wl, la):
     res["qknorm_fwd_bwd_" + cfg4.name] = {"ms_per_step": timed(qknorm_step_bf16, 30)}
     del t, wsf, wsb
     torch.cuda.empty_cache()
-    # head size 256: the top of the paper's head-size sweep
-    c = wl.find_workload("paper_causal_f32_B4_H16_N4096_D256")
-    t = make_device_inputs(c, torch, 1)[0]
-    a6 = (c.B, c.H, c.N, c.D, dt, c.causal)
-    wsf = torch.empty(la.la_workspace_bytes(*a6, 0), dtype=torch.uint8, device="cuda")
-    wsb = torch.empty(la.la_workspace_bytes(*a6, 1), dtype=torch.uint8, device="cuda")
-    fwd = timed(lambda: la.la_forward(t["Q"], t["K"], t["V"], t["O"], t["G"], c.a, c.b, c.causal,
-                                      wsf), 5, 2)
-    bwd = timed(lambda: la.la_backward(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
-                                       t["dK"], t["dV"], c.a, c.b, c.causal, wsb), 5, 2)
-    res[c.name] = {"forward_ms": fwd, "backward_ms": bwd}
+    # head size 256: the top of the paper's head-size sweep, and the same shape in bf16
+    c32 = wl.find_workload("paper_causal_f32_B4_H16_N4096_D256")
+    c16 = wl.Config("causal_bf16_B4_H16_N4096_D256", c32.B, c32.H, c32.N, c32.D, True, "bf16")
+    for c in (c32, c16):
+        t = make_device_inputs(c, torch, 1)[0]
+        a6 = (c.B, c.H, c.N, c.D, la.LA_F32 if c.dtype == "f32" else la.LA_BF16, c.causal)
+        wsf = torch.empty(la.la_workspace_bytes(*a6, 0), dtype=torch.uint8, device="cuda")
+        wsb = torch.empty(la.la_workspace_bytes(*a6, 1), dtype=torch.uint8, device="cuda")
+        fwd = timed(lambda: la.la_forward(t["Q"], t["K"], t["V"], t["O"], t["G"], c.a, c.b,
+                                          c.causal, wsf), 5, 2)
+        bwd = timed(lambda: la.la_backward(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"],
+                                           t["dQ"], t["dK"], t["dV"], c.a, c.b, c.causal, wsb),
+                    5, 2)
+        res[c.name] = {"forward_ms": fwd, "backward_ms": bwd}
+        del t, wsf, wsb
+        torch.cuda.empty_cache()
     return res
 
 

@@ -84,7 +84,10 @@ LA_API const char *la_status_string(la_status s);
  * unsupported arguments.  The workspace holds the per-segment running-sum
  * states (S = sum k v^T, z = sum k, p = sum v of Eq. xy; and the reverse sums
  * of Eq. endd for the backward pass) that let segments of one sequence run in
- * parallel; its size is O(B*H*(N/segment)*D^2 + B*H*N).
+ * parallel; its size is O(B*H*(N/segment)*D^2 + B*H*N).  D = 256 runs as passes over
+ * blocks of 128 columns; with bf16 tensors the shares that one pass hands to the next stay
+ * in float32 in the workspace: 512 more bytes per token-head for la_forward, 2048 for
+ * la_backward.
  */
 LA_API size_t la_workspace_bytes(int B, int H, int N, int D, la_dtype dt, int causal,
                           int is_backward);

@@ -66,23 +66,25 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
                                 : round_up(slots, 64) * 4;
     p.saved_floats = round_up(DD + D, 64);
     p.saved_bytes = (size_t)BH * p.nseg * p.saved_floats * 4;
-    // fp32 at D = 256 runs as passes of the D = 128 kernels (split_forward / split_backward):
-    // their workspace, plus one float per token-head in the forward pass
-    if (D == 256 && dt == LA_F32) {
+    // D = 256 runs as passes of the D = 128 kernels (split_forward / split_backward): their
+    // workspace, plus what the forward passes hand to each other
+    if (D == 256) {
         const Plan h = make_plan(B, H, N, 128, dt, causal, is_backward);
-        const size_t need = h.total_bytes + (is_backward ? 0 : round_up((size_t)BH * N, 64) * 4);
+        const size_t need =
+            split_scratch(h, (size_t)BH * N, dt, is_backward).total_floats * sizeof(float);
         if (need > p.total_bytes) p.total_bytes = need;
     }
     return p;
 }
 
-// Forward and backward pass at D = 256: fp32 on the matrix-core kernels of D = 128, column
-// block by column block; bf16 on the token-serial kernels.
+// Forward and backward pass at D = 256: column block by column block on the matrix-core
+// kernels of D = 128, or (test hook) on the token-serial kernels.  dK == nullptr: dQ only.
 static la_status forward_256(const Problem &pr, const Plan &pl, int B, int H, const void *Q,
                              const void *K, const void *V, void *O, float *G, float *ws,
                              hipStream_t st, Tracer &tc)
 {
-    if (pr.dt != LA_F32) return wide_forward(pr, pl, Q, K, V, O, G, ws, st, tc);
+    if (g_force_generic.load(std::memory_order_relaxed))
+        return wide_forward(pr, pl, Q, K, V, O, G, ws, st, tc);
     const Plan h = make_plan(B, H, pr.N, 128, pr.dt, pr.causal, 0);
     return split_forward(pr, h, Q, K, V, O, G, ws, st, tc);
 }
@@ -91,7 +93,8 @@ static la_status backward_256(const Problem &pr, const Plan &pl, int B, int H, c
                               const void *dO, void *dQ, void *dK, void *dV, float *ws,
                               hipStream_t st, Tracer &tc)
 {
-    if (pr.dt != LA_F32) return wide_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
+    if (g_force_generic.load(std::memory_order_relaxed))
+        return wide_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
     const Plan h = make_plan(B, H, pr.N, 128, pr.dt, pr.causal, 1);
     return split_backward(pr, h, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
 }
@@ -430,8 +433,8 @@ la_status la_backward_ab(const void *Q, const void *K, const void *V, const void
         s = la::fast_backward_dq(pr, pl, Q, K, V, O, G, dO, dq1, (float *)workspace, st);
     } else if (D == 256) {
         la::Tracer tc(nullptr, st);
-        s = la::wide_backward(pr, pl, Q, K, V, O, G, dO, dq1, nullptr, nullptr, (float *)workspace,
-                              st, tc);
+        s = la::backward_256(pr, pl, B, H, Q, K, V, O, G, dO, dq1, nullptr, nullptr,
+                             (float *)workspace, st, tc);
     } else {
         la::Tracer tc(nullptr, st);
         s = la::generic_backward(pr, pl, Q, K, V, O, G, dO, dq1, wsb + lay.dk_off,

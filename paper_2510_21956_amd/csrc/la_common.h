@@ -170,15 +170,39 @@ la_status decode_step(const void *Q, const void *K, const void *V, void *O, floa
 la_status state_from_totals(const float *ws, float *state, int BH, int D, int nseg,
                             size_t slot_floats, int N, int accumulate, hipStream_t st);
 
-// Head size 256 (la_wide.hip): token-serial kernels with the state in registers.
-// Head size 256 in fp32 as passes of the D = 128 matrix-core kernels over column blocks of
-// the 256-wide rows; `pl` is the plan of the D = 128 problem (la_fast.hip).
+// Head size 256 as passes of the D = 128 matrix-core kernels over column blocks of the
+// 256-wide rows; `pl` is the plan of the D = 128 problem (la_fast.hip).  dK == nullptr runs
+// the ascending sweeps (dQ) only.
+// What split_forward / split_backward keep behind the D = 128 plan's workspace (offsets and
+// total in floats, T = token-heads).  Forward: one float per token-head (g_off) and, for bf16
+// tensors, 128 (f_off).  Backward, bf16 tensors only: 128 each for the dQ and dK block in
+// progress (q_off, k_off) and 2 x 128 for the two dV blocks (v_off).
+struct SplitScratch {
+    size_t g_off, f_off, q_off, k_off, v_off, total_floats;
+};
+inline SplitScratch split_scratch(const Plan &pl128, size_t T, la_dtype dt, int is_backward)
+{
+    SplitScratch s{};
+    const size_t base = pl128.total_bytes / sizeof(float), wide = dt == LA_BF16 ? T * 128 : 0;
+    if (!is_backward) {
+        s.g_off = base;
+        s.f_off = s.g_off + ((T + 63) / 64) * 64;
+        s.total_floats = s.f_off + wide;
+    } else {
+        s.q_off = base;
+        s.k_off = s.q_off + wide;
+        s.v_off = s.k_off + wide;
+        s.total_floats = s.v_off + 2 * wide;
+    }
+    return s;
+}
 la_status split_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                         const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
 la_status split_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                          const void *V, const void *O, const float *G, const void *dO, void *dQ,
                          void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc);
-// wide_backward with dK == nullptr runs the ascending sweep (dQ) only.
+// Head size 256 (la_wide.hip): token-serial kernels with the state in registers, behind the
+// test hook.  wide_backward with dK == nullptr runs the ascending sweep (dQ) only.
 la_status wide_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                        const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
 la_status wide_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,

@@ -708,13 +708,15 @@ __device__ __forceinline__ void store_weight_block(T *tile, int plane, int col0,
 // descriptor that covers its first `rows_valid` rows (at most 16, possibly none): stores
 // to rows beyond them are dropped by the address check, without a branch, and the lane's
 // address is one 32-bit offset that does not change from block to block.
-// acc = 1 adds what the block holds already, acc = 2 adds it times old_scale[row] (fp32 only):
-// the calls that work on a block of columns of wider rows build their results up over several
-// launches.
+// acc = 1 adds what the block holds already, acc = 2 adds it times old_scale[row]: the calls
+// that work on a block of columns of wider rows build their results up over several launches.
+// A bf16 block takes the values to add from an fp32 array instead (old32: rows old_ld floats
+// apart, the same columns), so that the result is rounded once.
 template <typename T>
 __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_valid, int l,
                                             float x0, float x1, float x2, float x3, int acc = 0,
-                                            const float *old_scale = nullptr)
+                                            const float *old_scale = nullptr,
+                                            const float *old32 = nullptr, int old_ld = 0)
 {
     const int src = 16 * (l % 4) + l / 4;  // lane that holds (row l/4, column quad l%4)
     const int row = l / 4, cq = l % 4;
@@ -733,12 +735,42 @@ __device__ __forceinline__ void store_block(T *base, int ld, int col0, int rows_
         const u4v v = {__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]),
                        __float_as_uint(y[3])};
         __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, off, 0, 0);
+    } else if (acc) {  // bf16: what is added comes from old32, see above
+        f4v y = {__shfl(x0, src), __shfl(x1, src), __shfl(x2, src), __shfl(x3, src)};
+        const float sc = acc == 2 ? old_scale[row] : 1.f;
+        const __amdgpu_buffer_rsrc_t r32 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(old32), 0, nrows * old_ld * 4, kBufferFlags);
+        const u4v o =
+            __builtin_amdgcn_raw_buffer_load_b128(r32, (row * old_ld + col0 + 4 * cq) * 4, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] += sc * __uint_as_float(o[e]);
+        bf4v p = to_bf4(y);
+        __builtin_amdgcn_raw_buffer_store_b64(*reinterpret_cast<u2v *>(&p), rsrc, off, 0, 0);
     } else {
         bf4v p = to_bf4(f4v{x0, x1, x2, x3});
         u2v u = *reinterpret_cast<u2v *>(&p);
         const u2v v = {(unsigned)__shfl((int)u[0], src), (unsigned)__shfl((int)u[1], src)};
         __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, off, 0, 0);
     }
+}
+
+// One 16-row block of a gradient.  With LD != D (a block of D columns of rows LD wide) the
+// gradient is the sum of two launches: fp32 tensors add in place (`add` in the second launch);
+// bf16 tensors keep the first launch's share in `part` (fp32, rows of D: early rows of a masked
+// pass are small differences of large shares) and the second launch adds it and rounds once.
+template <typename TIO, int D, int LD>
+__device__ __forceinline__ void store_grad_block(TIO *out, float *part, bool add, int col0,
+                                                 int rows_valid, int l, float x0, float x1,
+                                                 float x2, float x3)
+{
+    if constexpr (LD == D)
+        store_block<TIO>(out, LD, col0, rows_valid, l, x0, x1, x2, x3);
+    else if constexpr (sizeof(TIO) == 4)
+        store_block<TIO>(out, LD, col0, rows_valid, l, x0, x1, x2, x3, add ? 1 : 0);
+    else if (!add)
+        store_block<float>(part, D, col0, rows_valid, l, x0, x1, x2, x3);
+    else
+        store_block<TIO>(out, LD, col0, rows_valid, l, x0, x1, x2, x3, 1, nullptr, part, D);
 }
 
 // ---------------------------------------------------------------------------
@@ -827,9 +859,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_kv_state(
 //   then S += K_c^T V_c, z += sum k, p += sum v
 // ---------------------------------------------------------------------------
 // With LD != D the call works on D columns of rows LD wide and is one of several launches
-// that build O up (fp32 only):  xflags & XF_RAW: leave the numerator f undivided in O and the
+// that build O up:  xflags & XF_RAW: leave the numerator f undivided in O and the
 // launch's own share of g in G;  xflags & XF_ACC: add the f that O holds already and the share
-// of g in Gin before dividing.
+// of g in Gin before dividing.  With bf16 tensors the undivided f goes through Fraw instead of
+// O (fp32, B*H*N rows of D), so that O is rounded once.
 constexpr int XF_RAW = 1, XF_ACC = 2;
 template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
@@ -837,11 +870,12 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
     TIO *__restrict__ O,
     float *__restrict__ G, const float *__restrict__ ws, float *__restrict__ saved, int N,
     int nseg, SegMap sm, size_t slot_floats, size_t saved_floats, float a, float b, int norm,
-    int xflags, const float *__restrict__ Gin)
+    int xflags, const float *__restrict__ Gin, float *__restrict__ Fraw)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int C = F::C, NW = F::NW, NT = F::NT, NB = F::NB, NRB = F::NRB, KT = F::KT;
+    constexpr bool RAW32 = LD != D && sizeof(TIO) == 2;
     constexpr int LDR = F::LDR, LDT = F::LDT, PP = M::PLANES, PSZ = C * LDT;
     constexpr int TS = CAUSAL ? 1 : 0;  // tiles only the masked path needs shrink to nothing
     __shared__ __align__(16) T Qs[C * LDR];
@@ -1056,13 +1090,20 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             for (int ib = 0; ib < NB; ++ib) gi[ib] = ginv[w][ib * 16 + c];
             const f4v p4 = a * pacc.v;
 #pragma unroll
-            for (int ib = 0; ib < NB; ++ib)
-                store_block<TIO>(Op + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
-                               (int)(row1 - c0) - ib * 16, l, (facc[ib].get(0) + p4[0]) * gi[ib],
-                               (facc[ib].get(1) + p4[1]) * gi[ib],
-                               (facc[ib].get(2) + p4[2]) * gi[ib],
-                               (facc[ib].get(3) + p4[3]) * gi[ib],
-                               (LD != D && (xflags & XF_ACC)) ? 2 : 0, &ginv[w][ib * 16]);
+            for (int ib = 0; ib < NB; ++ib) {
+                const float y0 = (facc[ib].get(0) + p4[0]) * gi[ib],
+                            y1 = (facc[ib].get(1) + p4[1]) * gi[ib],
+                            y2 = (facc[ib].get(2) + p4[2]) * gi[ib],
+                            y3 = (facc[ib].get(3) + p4[3]) * gi[ib];
+                const int nrows = (int)(row1 - c0) - ib * 16;
+                float *fr = RAW32 ? Fraw + ((size_t)bh * N + c0 + ib * 16) * D : nullptr;
+                if (RAW32 && (xflags & XF_RAW))
+                    store_block<float>(fr, D, w * 16, nrows, l, y0, y1, y2, y3);
+                else
+                    store_block<TIO>(Op + (size_t)(c0 + ib * 16) * LD, LD, w * 16, nrows, l, y0, y1,
+                                     y2, y3, (LD != D && (xflags & XF_ACC)) ? 2 : 0,
+                                     &ginv[w][ib * 16], fr, D);
+            }
         }
         if constexpr (CAUSAL) {
             outer_update<T, D>(st, KTt, 0, VTt, 0, w, c, g, ql, wo, vs);
@@ -1112,14 +1153,15 @@ struct BwdSlot {
 // (Eq. endd without the factors), which it leaves in the slot of the segment
 // that will start from them.
 // ---------------------------------------------------------------------------
-// With LD != D (see kf_fwd_apply): xflags & 1 adds the results to what dQ holds already.
+// With LD != D (see kf_fwd_apply, store_grad_block): xflags & 1 marks the second of the two
+// launches that build dQ up; Pq holds the first one's share for bf16 tensors.
 template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4) ? 2 : 3)) void kf_bwd_dq(
     const TIO *__restrict__ Q, const TIO *__restrict__ K, const TIO *__restrict__ V,
     const TIO *__restrict__ O, const float *__restrict__ G, const TIO *__restrict__ dO,
     TIO *__restrict__ dQ, float *ws, const float *sinit, size_t sinit_floats,
     float *__restrict__ dprime, int N, int nseg, SegMap sm, size_t slot_floats, float b,
-    int norm, int xflags)
+    int norm, int xflags, float *__restrict__ Pq)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1350,12 +1392,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
                 const float f = b * sc[ii];
-                store_block<TIO>(dQp + (size_t)(c0 + ib * 16) * LD, LD, w * 16,
-                               (int)(row1 - c0) - ib * 16, l, f * (acc[ii].get(0) - di[ii] * z4[0]),
-                               f * (acc[ii].get(1) - di[ii] * z4[1]),
-                               f * (acc[ii].get(2) - di[ii] * z4[2]),
-                               f * (acc[ii].get(3) - di[ii] * z4[3]),
-                               (LD != D && (xflags & 1)) ? 1 : 0);
+                store_grad_block<TIO, D, LD>(
+                    dQp + (size_t)(c0 + ib * 16) * LD, Pq + ((size_t)bh * N + c0 + ib * 16) * D,
+                    xflags & 1, w * 16, (int)(row1 - c0) - ib * 16, l,
+                    f * (acc[ii].get(0) - di[ii] * z4[0]), f * (acc[ii].get(1) - di[ii] * z4[1]),
+                    f * (acc[ii].get(2) - di[ii] * z4[2]), f * (acc[ii].get(3) - di[ii] * z4[3]));
             }
             if (i0 == 0) fetch_part(cn, std::integral_constant<int, 2>());
         }
@@ -1409,14 +1450,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 // columns r for dK (contraction over j); fp32 at D = 64 holds it once and takes the
 // second orientation from a copy in LDS (RL below).
 // ---------------------------------------------------------------------------
-// With LD != D (see kf_fwd_apply): xflags & 2 adds to what dK holds already, xflags & 4 to dV.
+// With LD != D (see kf_fwd_apply, store_grad_block): xflags & 2 marks the second of the two
+// launches that build dK up, xflags & 4 the same for dV; Pk, Pv hold the first one's share
+// for bf16 tensors.
 template <typename T, int D, bool CAUSAL, int LD = D, typename TIO = T>
 __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSAL) ? 1 : 2)) void kf_bwd_dkv(
     const TIO *__restrict__ Q, const TIO *__restrict__ K, const TIO *__restrict__ V,
     const float *__restrict__ G, const TIO *__restrict__ dO, TIO *__restrict__ dK,
     TIO *__restrict__ dV,
     const float *__restrict__ ws, const float *__restrict__ dprime, int N, int nseg, SegMap sm,
-    size_t slot_floats, float a, float b, int norm, int xflags)
+    size_t slot_floats, float a, float b, int norm, int xflags, float *__restrict__ Pk,
+    float *__restrict__ Pv)
 {
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
@@ -1663,11 +1707,11 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                             chunk_product<T, D, 1, 1>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                     }
-                    store_block<TIO>(dKp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
-                                   (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
-                                   b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
-                                   b * (ak[m].get(3) - u4[3]),
-                                   (LD != D && (xflags & 2)) ? 1 : 0);
+                    store_grad_block<TIO, D, LD>(
+                        dKp + (size_t)(c0 + nb * 16) * LD, Pk + ((size_t)bh * N + c0 + nb * 16) * D,
+                        xflags & 2, w * 16, (int)(row1 - c0) - nb * 16, l,
+                        b * (ak[m].get(0) - u4[0]), b * (ak[m].get(1) - u4[1]),
+                        b * (ak[m].get(2) - u4[2]), b * (ak[m].get(3) - u4[3]));
                 }
             }
             fetch_part(cn, std::integral_constant<int, 3>());
@@ -1695,10 +1739,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                         }
                     }
-                    store_block<TIO>(dVp + (size_t)(c0 + nb * 16) * LD, LD, w * 16,
-                                   (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
-                                   av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3],
-                                   (LD != D && (xflags & 4)) ? 1 : 0);
+                    store_grad_block<TIO, D, LD>(
+                        dVp + (size_t)(c0 + nb * 16) * LD, Pv + ((size_t)bh * N + c0 + nb * 16) * D,
+                        xflags & 4, w * 16, (int)(row1 - c0) - nb * 16, l, av[m].get(0) + w4[0],
+                        av[m].get(1) + w4[1], av[m].get(2) + w4[2], av[m].get(3) + w4[3]);
                 }
             }
         }
@@ -1735,7 +1779,7 @@ inline la_status launch_status()
 template <typename T, int D, int LD = D, typename TIO = T>
 la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, void *Ov, float *G, float *ws, float *saved, hipStream_t st,
-                   Tracer &tc, int xflags = 0, const float *Gin = nullptr)
+                   Tracer &tc, int xflags = 0, const float *Gin = nullptr, float *Fraw = nullptr)
 {
     constexpr int NT = FC<T, D>::NT;
     const TIO *Q = (const TIO *)Qv, *K = (const TIO *)Kv, *V = (const TIO *)Vv;
@@ -1753,11 +1797,11 @@ la_status fast_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_fwd_apply<T, D, true, LD, TIO><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, pr.norm_qk, xflags, Gin);
+            pr.b, pr.norm_qk, xflags, Gin, Fraw);
     else
         kf_fwd_apply<T, D, false, LD, TIO><<<dim3(pr.BH * nseg), dim3(NT), 0, st>>>(
             Q, K, V, O, G, ws, saved, pr.N, nseg, pl.map, pl.slot_floats, pl.saved_floats, pr.a,
-            pr.b, pr.norm_qk, xflags, Gin);
+            pr.b, pr.norm_qk, xflags, Gin, Fraw);
     tc.mark("fwd_apply");
     return launch_status();
 }
@@ -1767,7 +1811,8 @@ template <typename T, int D, int LD = D, typename TIO = T>
 la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
                    void *dKv, void *dVv, float *ws, const float *saved, hipStream_t st, Tracer &tc,
-                   bool dq_only = false, int xflags = 0)
+                   bool dq_only = false, int xflags = 0, float *Pq = nullptr, float *Pk = nullptr,
+                   float *Pv = nullptr)
 {
     typedef BwdSlot<D> SL;
     constexpr int NT = FC<T, D>::NT;
@@ -1793,11 +1838,11 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     if (pr.causal)
         kf_bwd_dq<T, D, true, LD, TIO><<<grid, block, 0, st>>>(
             Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
-            pl.slot_floats, pr.b, pr.norm_qk, xflags);
+            pl.slot_floats, pr.b, pr.norm_qk, xflags, Pq);
     else
         kf_bwd_dq<T, D, false, LD, TIO><<<grid, block, 0, st>>>(
             Q, K, V, O, G, dO, dQ, ws, sinit, sinit_floats, dprime, pr.N, nseg, pl.map,
-            pl.slot_floats, pr.b, pr.norm_qk, xflags);
+            pl.slot_floats, pr.b, pr.norm_qk, xflags, Pq);
     tc.mark("bwd_dq");
     if (dq_only) return launch_status();
     // reverse-running sums left by the ascending sweep
@@ -1809,14 +1854,14 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
         }
         kf_bwd_dkv<T, D, true, LD, TIO><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
                                                            pr.N, nseg, pl.map, pl.slot_floats,
-                                                           pr.a, pr.b, pr.norm_qk, xflags);
+                                                           pr.a, pr.b, pr.norm_qk, xflags, Pk, Pv);
     } else {
         launch_scan_slots(ws, pr.BH, nseg, pl.slot_floats, SL::R, SL::END - SL::R, 2, 0, nseg - 1,
                           st);
         tc.mark("scan_slots_rev");
         kf_bwd_dkv<T, D, false, LD, TIO><<<grid, block, 0, st>>>(Q, K, V, G, dO, dK, dV, ws, dprime,
                                                             pr.N, nseg, pl.map, pl.slot_floats,
-                                                            pr.a, pr.b, pr.norm_qk, xflags);
+                                                            pr.a, pr.b, pr.norm_qk, xflags, Pk, Pv);
     }
     tc.mark("bwd_dkv");
     return launch_status();
@@ -1864,62 +1909,93 @@ la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, con
     return LA_ERR_UNSUPPORTED;
 }
 
-// Head size 256 in fp32 on the D = 128 kernels.  With q = [q1 q2], k = [k1 k2] (halves of
-// 128) the weight a + b q.k is (a + b q1.k1) + (0 + b q2.k2), and with v = [v1 v2] every sum
-// of Sec. 3.1 / 3.2 splits into blocks: the numerator of output half j is the sum over i of
+// Head size 256 on the D = 128 kernels.  With q = [q1 q2], k = [k1 k2] (halves of 128) the
+// weight a + b q.k is (a + b q1.k1) + (0 + b q2.k2), and with v = [v1 v2] every sum of
+// Sec. 3.1 / 3.2 splits into blocks: the numerator of output half j is the sum over i of
 // the numerators of the D = 128 problems (q_i, k_i, v_j) with coefficients (a, b) for i = 1
 // and (0, b) for i = 2, g is the sum of their denominators, and likewise
 //   dq_i = sum_j dq(q_i, k_i, v_j; o_j, dO_j, g),   dk_i = sum_j dk(...),   dv_j = sum_i dv(...)
 // where the blocks (o_j, dO_j) and the full g stand for the stored set of the block problem
 // (delta = o . OmegaHat splits over j as well).  Four passes of the D = 128 kernels over column
 // blocks of the 256-wide rows, each adding to what the previous ones left in the outputs.
-// `pl` is the plan of the D = 128 problem; the forward pass keeps the first pass's share of g
-// in B*H*N floats behind that plan's workspace.
-la_status split_forward(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
-                        const void *Vv, void *Ov, float *G, float *ws, hipStream_t st, Tracer &tc)
+// `pl` is the plan of the D = 128 problem; behind that plan's workspace the forward pass keeps
+// the first pass's share of g and, for bf16, its undivided numerator in fp32, and the backward
+// pass, for bf16, the first share of every gradient block in fp32 (split_scratch).
+namespace {
+
+template <typename T, typename TIO = T>
+la_status split_fwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
+                    const void *Vv, void *Ov, float *G, float *ws, hipStream_t st, Tracer &tc)
 {
-    const float *Q = (const float *)Qv, *K = (const float *)Kv, *V = (const float *)Vv;
-    float *O = (float *)Ov;
-    float *gpart = ws + pl.total_bytes / sizeof(float);
+    const TIO *Q = (const TIO *)Qv, *K = (const TIO *)Kv, *V = (const TIO *)Vv;
+    TIO *O = (TIO *)Ov;
+    const SplitScratch sc = split_scratch(pl, (size_t)pr.BH * pr.N, pr.dt, 0);
+    float *gpart = ws + sc.g_off, *fraw = ws + sc.f_off;
     Problem p = pr;
     p.D = 128;
     Tracer quiet(nullptr, st);  // the caller's trace gets one mark per pass, not per kernel
     for (int j = 0; j < 2; ++j) {
         p.a = pr.a;
-        la_status s = fast_fwd<float, 128, 256>(p, pl, Q, K, V + 128 * j, O + 128 * j, gpart, ws,
-                                                nullptr, st, quiet, XF_RAW, nullptr);
+        la_status s = fast_fwd<T, 128, 256, TIO>(p, pl, Q, K, V + 128 * j, O + 128 * j, gpart, ws,
+                                            nullptr, st, quiet, XF_RAW, nullptr, fraw);
         if (s != LA_OK) return s;
         tc.mark("fwd_block_pass");
         p.a = 0.f;
-        s = fast_fwd<float, 128, 256>(p, pl, Q + 128, K + 128, V + 128 * j, O + 128 * j,
-                                      j == 1 ? G : nullptr, ws, nullptr, st, quiet, XF_ACC, gpart);
+        s = fast_fwd<T, 128, 256, TIO>(p, pl, Q + 128, K + 128, V + 128 * j, O + 128 * j,
+                                  j == 1 ? G : nullptr, ws, nullptr, st, quiet, XF_ACC, gpart,
+                                  fraw);
         if (s != LA_OK) return s;
         tc.mark("fwd_block_pass");
     }
     return LA_OK;
 }
 
-la_status split_backward(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
-                         const void *Vv, const void *Ov, const float *G, const void *dOv,
-                         void *dQv, void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
+// dK == nullptr: the ascending sweeps only (dQ).
+template <typename T, typename TIO = T>
+la_status split_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void *Kv,
+                    const void *Vv, const void *Ov, const float *G, const void *dOv, void *dQv,
+                    void *dKv, void *dVv, float *ws, hipStream_t st, Tracer &tc)
 {
-    const float *Q = (const float *)Qv, *K = (const float *)Kv, *V = (const float *)Vv,
-                *O = (const float *)Ov, *dO = (const float *)dOv;
-    float *dQ = (float *)dQv, *dK = (float *)dKv, *dV = (float *)dVv;
+    const TIO *Q = (const TIO *)Qv, *K = (const TIO *)Kv, *V = (const TIO *)Vv,
+              *O = (const TIO *)Ov, *dO = (const TIO *)dOv;
+    TIO *dQ = (TIO *)dQv, *dK = (TIO *)dKv, *dV = (TIO *)dVv;
+    const bool dq_only = dKv == nullptr;
+    const SplitScratch sc = split_scratch(pl, (size_t)pr.BH * pr.N, pr.dt, 1);
     Problem p = pr;
     p.D = 128;
     Tracer quiet(nullptr, st);  // the caller's trace gets one mark per pass, not per kernel
     for (int i = 0; i < 2; ++i)
         for (int j = 0; j < 2; ++j) {
             p.a = i == 0 ? pr.a : 0.f;
+            // dQ_i and dK_i are complete after j = 1, dV_j after i = 1
             const int xflags = (j == 1 ? 1 | 2 : 0) | (i == 1 ? 4 : 0);
-            const la_status s = fast_bwd<float, 128, 256>(
+            const la_status s = fast_bwd<T, 128, 256, TIO>(
                 p, pl, Q + 128 * i, K + 128 * i, V + 128 * j, O + 128 * j, G, dO + 128 * j,
-                dQ + 128 * i, dK + 128 * i, dV + 128 * j, ws, nullptr, st, quiet, false, xflags);
+                dQ + 128 * i, dq_only ? nullptr : dK + 128 * i, dq_only ? nullptr : dV + 128 * j,
+                ws, nullptr, st, quiet, dq_only, xflags, ws + sc.q_off, ws + sc.k_off,
+                ws + sc.v_off + (size_t)j * pr.BH * pr.N * 128);
             if (s != LA_OK) return s;
             tc.mark("bwd_block_pass");
         }
     return LA_OK;
+}
+
+}  // namespace
+
+la_status split_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                        const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc)
+{
+    return pr.dt == LA_F32 ? split_fwd<float>(pr, pl, Q, K, V, O, G, ws, st, tc)
+                           : split_fwd<__bf16>(pr, pl, Q, K, V, O, G, ws, st, tc);
+}
+
+la_status split_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
+                         const void *V, const void *O, const float *G, const void *dO, void *dQ,
+                         void *dK, void *dV, float *ws, hipStream_t st, Tracer &tc)
+{
+    return pr.dt == LA_F32
+               ? split_bwd<float>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc)
+               : split_bwd<__bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, st, tc);
 }
 
 bool fast_supported(const Problem &pr, int is_backward)

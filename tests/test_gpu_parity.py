@@ -85,7 +85,7 @@ SMALL = [
     # matrix-core path at its edges: a single row, one short chunk, one row past a chunk,
     # exactly one chunk, one row past a 64-row segment boundary
     (1, 1, 1, 64), (1, 1, 31, 64), (1, 2, 33, 128), (1, 1, 64, 64), (3, 1, 65, 64), (1, 1, 1, 128),
-    # head size 256 (token-serial kernels)
+    # head size 256 (four passes of the D = 128 kernels over column blocks)
     (1, 1, 1, 256), (1, 2, 70, 256), (2, 1, 300, 256),
 ]
 
@@ -131,10 +131,10 @@ def test_other_coefficients(oracle_mod, la, knobs, D, dtype, ab):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [64, 128, 256])
 def test_plain_alu_path_at_large_heads(oracle_mod, la, knobs, D, dtype):
-    """The plain-ALU kernels are compiled for every head size; force them where the
-    matrix-core kernels would normally run."""
+    """The plain-ALU kernels are compiled for every head size (token-serial ones at D = 256);
+    force them where the matrix-core kernels would normally run."""
     knobs(128, 1)
     for causal in (True, False):
         slices = [0, 1, 2]
@@ -205,6 +205,21 @@ def test_cost_balanced_segments(oracle_mod, la, knobs, shape):
     print("case", tag, flush=True)
     dev, ref = upload_case(B, H, N, D, "bf16", 4100 + N, slices)
     check_against_oracle(oracle_mod, la, dev, ref, slices, "bf16", 1.0, 0.5, True, tag)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_head_size_256_bf16(oracle_mod, la, knobs, causal):
+    """bf16 at D = 256 in the plan the library picks for a mid-sized shape: every output is
+    built up over passes on column blocks and rounded to bf16 in between; N is no multiple of
+    a tile, and with the mask the first rows (second planes on chip) share a segment with
+    later ones."""
+    knobs(0, 0)
+    B, H, N, D = 2, 8, 4100, 256
+    slices = [0, 9, B * H - 1]
+    tag = "D256 bf16 B%d H%d N%d causal=%d" % (B, H, N, causal)
+    print("case", tag, flush=True)
+    dev, ref = upload_case(B, H, N, D, "bf16", 2560 + causal, slices)
+    check_against_oracle(oracle_mod, la, dev, ref, slices, "bf16", 1.0, 0.5, causal, tag)
 
 
 # The paper's own benchmark shapes (Sec. 5.1), the ones the oracle finishes in seconds on a
