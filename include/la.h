@@ -198,7 +198,6 @@ LA_API la_status la_backward_ab(const void *Q, const void *K, const void *V,
  *       state the sums over the N rows of K, V [B,H,N,D] in one parallel pass:
  *       the state after a prompt that was run through la_forward.  workspace as
  *       for la_forward without the mask: la_workspace_bytes(B,H,N,D,dt,0,0).
- *       D in {16, 32, 64, 128}.
  * Error behaviour as for la_forward; a missing, misaligned or short state is
  * LA_ERR_WORKSPACE.
  */

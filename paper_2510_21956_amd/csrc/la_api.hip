@@ -503,7 +503,6 @@ la_status la_decode_prefill(const void *K, const void *V, float *state, size_t s
 {
     la_status s = la::check_shape(B, H, N, D, dt);
     if (s != LA_OK) return s;
-    if (D == 256) return LA_ERR_UNSUPPORTED;
     if (!K || !V) return LA_ERR_NULL;
     if (!la::aligned16(K) || !la::aligned16(V)) return LA_ERR_ALIGN;
     const size_t need = la_decode_state_bytes(B, H, D);
@@ -521,6 +520,9 @@ la_status la_decode_prefill(const void *K, const void *V, float *state, size_t s
     if (hipPeekAtLastError() != hipSuccess) return LA_ERR_LAUNCH;
     la::Problem pr{B * H, N, D, 1.f, 0.f, 0, dt};
     hipStream_t st = (hipStream_t)hip_stream;
+    if (D == 256)
+        return la::split_prefill(pr, la::make_plan(B, H, N, 128, dt, 0, 0), K, V,
+                                 (float *)workspace, state, accumulate ? 1 : 0, st);
     s = la::use_fast(pr, 0) ? la::fast_kv_totals(pr, pl, K, V, (float *)workspace, st)
                             : la::generic_kv_totals(pr, pl, K, V, (float *)workspace, st);
     if (s != LA_OK) return s;

@@ -167,6 +167,11 @@ la_status generic_kv_totals(const Problem &pr, const Plan &pl, const void *K, co
 size_t decode_state_floats(int D);
 la_status decode_step(const void *Q, const void *K, const void *V, void *O, float *G, float *state,
                       int BH, int Tn, int D, float a, float b, la_dtype dt, hipStream_t st);
+// D = 256: block (bi, bj) of the state from the totals of the D = 128 problem on k block bi,
+// v block bj.
+la_status state_block_from_totals(const float *ws, float *state, int BH, int nseg,
+                                  size_t slot_floats, int bi, int bj, int N, int accumulate,
+                                  hipStream_t st);
 la_status state_from_totals(const float *ws, float *state, int BH, int D, int nseg,
                             size_t slot_floats, int N, int accumulate, hipStream_t st);
 
@@ -196,6 +201,10 @@ inline SplitScratch split_scratch(const Plan &pl128, size_t T, la_dtype dt, int 
     }
     return s;
 }
+// The decode state of a D = 256 problem (+)= the sums over its N rows of K, V: four passes
+// of the D = 128 sums kernels, each followed by state_block_from_totals.
+la_status split_prefill(const Problem &pr, const Plan &pl, const void *K, const void *V, float *ws,
+                        float *state, int accumulate, hipStream_t st);
 la_status split_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                         const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc);
 la_status split_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,

@@ -117,6 +117,41 @@ __global__ __launch_bounds__(256) void k_state_from_totals(const float *__restri
     }
 }
 
+// The same for D = 256 from the totals of the block problem (k block i, v block j) at D = 128:
+// S block (i, j); z block i (taken when j = 0); p block j (when i = 0); the count once.
+__global__ __launch_bounds__(256) void k_state_block_from_totals(const float *__restrict__ ws,
+                                                                 float *__restrict__ state,
+                                                                 int nseg, size_t slot_floats,
+                                                                 size_t state_floats, int bi,
+                                                                 int bj, int N, int accumulate)
+{
+    constexpr int H = 128, D = 256;
+    const int bh = blockIdx.x, len = H * H + 2 * H;
+    const float *src = ws + (size_t)bh * nseg * slot_floats;
+    float *dst = state + (size_t)bh * state_floats;
+    for (int e = blockIdx.y * 256 + threadIdx.x; e <= len; e += gridDim.y * 256) {
+        float x;
+        int to;
+        if (e < H * H) {
+            x = src[e];
+            to = (bi * H + e / H) * D + bj * H + e % H;
+        } else if (e < H * H + H) {
+            if (bj != 0) continue;
+            x = src[e];
+            to = D * D + bi * H + (e - H * H);
+        } else if (e < len) {
+            if (bi != 0) continue;
+            x = src[e];
+            to = D * D + D + bj * H + (e - H * H - H);
+        } else {
+            if (bi != 0 || bj != 0) continue;
+            x = (float)N;
+            to = D * D + 2 * D;
+        }
+        dst[to] = accumulate ? dst[to] + x : x;
+    }
+}
+
 // Stage 1 of sum(X * Y): workgroup w sums a fixed contiguous share into partials[w].
 constexpr int kDotBlocks = 1024;
 template <typename T>
@@ -250,6 +285,16 @@ la_status state_from_totals(const float *ws, float *state, int BH, int D, int ns
     const int len = D * D + 2 * D + 1;
     k_state_from_totals<0><<<dim3(BH, (len + 255) / 256), dim3(256), 0, st>>>(
         ws, state, D, nseg, slot_floats, decode_state_floats(D), N, accumulate);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+la_status state_block_from_totals(const float *ws, float *state, int BH, int nseg,
+                                  size_t slot_floats, int bi, int bj, int N, int accumulate,
+                                  hipStream_t st)
+{
+    const int len = 128 * 128 + 2 * 128 + 1;
+    k_state_block_from_totals<<<dim3(BH, (len + 255) / 256), dim3(256), 0, st>>>(
+        ws, state, nseg, slot_floats, decode_state_floats(256), bi, bj, N, accumulate);
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 

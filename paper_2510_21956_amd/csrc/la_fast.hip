@@ -1867,12 +1867,12 @@ la_status fast_bwd(const Problem &pr, const Plan &pl, const void *Qv, const void
     return launch_status();
 }
 
-template <typename T, int D>
+template <typename T, int D, int LD = D>
 la_status fast_totals(const Problem &pr, const Plan &pl, const void *Kv, const void *Vv, float *ws,
                       hipStream_t st)
 {
     constexpr int NT = FC<T, D>::NT;
-    kf_kv_state<T, D, false><<<dim3(pr.BH * pl.nseg), dim3(NT), 0, st>>>(
+    kf_kv_state<T, D, false, LD><<<dim3(pr.BH * pl.nseg), dim3(NT), 0, st>>>(
         (const T *)Kv, (const T *)Vv, ws, pr.N, pl.nseg, pl.nseg, pl.map, pl.slot_floats, 0, pr.norm_qk);
     launch_scan_slots(ws, pr.BH, pl.nseg, pl.slot_floats, 0, D * D + 2 * D, 2, 0, pl.nseg - 1, st);
     return launch_status();
@@ -1981,6 +1981,25 @@ la_status split_bwd(const Problem &pr, const Plan &pl, const void *Qv, const voi
 }
 
 }  // namespace
+
+la_status split_prefill(const Problem &pr, const Plan &pl, const void *K, const void *V, float *ws,
+                        float *state, int accumulate, hipStream_t st)
+{
+    Problem p = pr;
+    p.D = 128;
+    const size_t es = pr.dt == LA_F32 ? 4 : 2;
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            const void *Kb = (const char *)K + 128 * i * es, *Vb = (const char *)V + 128 * j * es;
+            la_status s = pr.dt == LA_F32 ? fast_totals<float, 128, 256>(p, pl, Kb, Vb, ws, st)
+                                          : fast_totals<__bf16, 128, 256>(p, pl, Kb, Vb, ws, st);
+            if (s != LA_OK) return s;
+            s = state_block_from_totals(ws, state, pr.BH, pl.nseg, pl.slot_floats, i, j, pr.N,
+                                        accumulate, st);
+            if (s != LA_OK) return s;
+        }
+    return LA_OK;
+}
 
 la_status split_forward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
                         const void *V, void *O, float *G, float *ws, hipStream_t st, Tracer &tc)

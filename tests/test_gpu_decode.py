@@ -73,7 +73,8 @@ def test_decode_steps(oracle_mod, la, D, dtype):
         assert es <= 1.0
 
 
-@pytest.mark.parametrize("dtype,D,N0", [("f32", 64, 700), ("bf16", 128, 1000), ("f32", 32, 300)])
+@pytest.mark.parametrize("dtype,D,N0", [("f32", 64, 700), ("bf16", 128, 1000), ("f32", 32, 300),
+                                        ("f32", 256, 700), ("bf16", 256, 400)])
 def test_prefill_then_decode(oracle_mod, la, dtype, D, N0):
     """la_decode_prefill over a prompt (in two parts, the second accumulated), then single
     decode steps: outputs must equal the rows of the causal forward pass over the whole
