@@ -30,7 +30,7 @@
  *   - Outputs are overwritten, never accumulated into.  No written buffer
  *     (outputs, workspace, hand-over buffer) may overlap any other buffer of
  *     the call: this is checked and reported as LA_ERR_ALIAS.
- *   - Supported: D in {16, 32, 64, 128}; B, H, N >= 1 with B*H*N*D < 2^40;
+ *   - Supported: D in {16, 32, 64, 128, 256}; B, H, N >= 1 with B*H*N*D < 2^40;
  *     any N (a ragged last chunk is handled).
  *   - Errors are reported by return code only.  Every argument check happens
  *     before anything is enqueued, so a failed call has no side effect.
@@ -259,8 +259,8 @@ LA_API void la_debug_override(int seg_len, int force_generic);
  * floats, small next to the tensors.
  *
  *   la_saved_state_bytes: size of the `saved` buffer for this problem (0 for
- *       invalid arguments, and 0 when the library would not use one -- head
- *       sizes handled by the plain-ALU kernels; a zero-size buffer may be NULL).
+ *       invalid arguments, and 0 when the library would not use one -- D = 16
+ *       and D = 256; a zero-size buffer may be NULL).
  *   la_forward_save:   la_forward, and additionally fills `saved` (device
  *       memory, 256-byte aligned, at least la_saved_state_bytes bytes).
  *   la_backward_saved: la_backward, reading `saved` as written by

@@ -18,9 +18,9 @@ static size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
 static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 128 || D == 256; }
 
-// Segment length.  The masked apply kernels keep one (D = 128) or two (fp32, D = 64)
-// workgroups resident per compute unit (the unmasked ones, which hold no tiles of K and
-// V, four), and a workgroup walks its segment serially, so the launch is balanced when
+// Segment length.  The masked apply kernels keep one (D = 128), two (fp32, D = 64) or four
+// (D = 32) workgroups resident per compute unit (the unmasked ones, which hold no tiles of K
+// and V, four), and a workgroup walks its segment serially, so the launch is balanced when
 // slices x segments is about 256 x that residency: every compute unit then gets the
 // same number of equally long segments in a single round.
 // Segments are also kept long enough that the D x D state a segment hands over stays
@@ -30,7 +30,10 @@ Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backw
     Plan p;
     const long BH = (long)B * H;
     const int min_len = (D >= 128) ? 512 : 256;
-    const long resident = D == 256 ? 1 : !causal ? 4 : (dt == LA_F32 && D <= 64) ? 2 : 1;
+    const long resident = D == 256                      ? 1
+                          : (!causal || D <= 32)        ? 4
+                          : (dt == LA_F32 && D <= 64) ? 2
+                                                        : 1;
     const long target = 256 * resident;
     long want = (target + BH / 2) / BH;  // nearest number of segments per slice
     long max_by_len = N / min_len;

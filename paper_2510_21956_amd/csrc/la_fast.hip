@@ -372,14 +372,15 @@ __device__ __forceinline__ float reduce_lane_groups(float x)
 // rows, one wave each.  The NPAIRS weight blocks of phase A are dealt round-robin from
 // wave 0, so the last waves carry one block less than the first; the jobs go to those,
 // from the last wave downwards.  Job (kind, part) covers rows [64 part, 64 part + 64) of
-// vector number `kind`.
+// vector number `kind` (as far as there are rows: D = 32 has half a job), lane l its row
+// 64 part + l.
 template <int NW, int D, int NPAIRS>
 struct VecJobs {
-    static constexpr int PER = D / 64;
+    static constexpr int PER = (D + 63) / 64;
     static constexpr int LIGHT = (NPAIRS % NW) ? NW - NPAIRS % NW : NW;  // waves with fewer blocks
-    static __device__ __forceinline__ bool mine(int kind, int part, int w)
+    static __device__ __forceinline__ bool mine(int kind, int part, int w, int l)
     {
-        return w == NW - 1 - (kind * PER + part) % LIGHT;
+        return w == NW - 1 - (kind * PER + part) % LIGHT && (D % 64 == 0 || 64 * part + l < D);
     }
 };
 
@@ -417,7 +418,7 @@ struct VecSums {
     const float *wa = nullptr, *wb = nullptr;
     int wplanes = 1;
 };
-template <typename T, int D, int GRP = 4, int NAP = 1, int NBP = 1>  // GRP row blocks per pass
+template <typename T, int D, int GRP = 4, int NAP = 1, int NBP = 1>  // up to GRP row blocks per pass
 __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int aps, const T *bt,
                                              int bps, int w, int c, int g, const SwzLane &ql,
                                              SwzOff wo, const VecSums sums = VecSums())
@@ -425,8 +426,10 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
     typedef FC<T, D> F;
     typedef Mma<T, 16> M;
     constexpr int NRB = F::NRB, KT = F::KT, LDT = F::LDT, C = F::C;
+    constexpr int GR = GRP < NRB ? GRP : NRB;  // row blocks per pass
     static_assert(NAP == 1 || NBP == 1, "products of two second planes are never needed");
-    typedef XsYs<M, GRP * NAP, NBP> B;
+    static_assert(NRB % GR == 0, "whole passes");
+    typedef XsYs<M, GR * NAP, NBP> B;
     // weight fragment of k-tile kt: the lane's contraction indices of that tile
     auto weights = [&](const float *wgt, int kt) {
         if (!wgt) return M::ones2();
@@ -439,7 +442,7 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
     int lane0 = c * LDT;
     asm volatile("" : "+v"(lane0));
 #pragma unroll
-    for (int r0 = 0; r0 < NRB; r0 += GRP) {
+    for (int r0 = 0; r0 < NRB; r0 += GR) {
         pipeline<C / KT>(
             C / KT,
             [&](int kt) {
@@ -448,7 +451,7 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
                 for (int q = 0; q < NBP; ++q)
                     b.y[q] = M::load_off(bt + q * bps + w * 16 * LDT + lane0, kt, wo);
 #pragma unroll
-                for (int rb = 0; rb < GRP; ++rb)
+                for (int rb = 0; rb < GR; ++rb)
 #pragma unroll
                     for (int q = 0; q < NAP; ++q)
                         b.x[rb * NAP + q] =
@@ -458,7 +461,7 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
             },
             [&](int kt, const B &b) {
 #pragma unroll
-                for (int rb = 0; rb < GRP; ++rb)
+                for (int rb = 0; rb < GR; ++rb)
 #pragma unroll
                     for (int qa = 0; qa < NAP; ++qa)
 #pragma unroll
@@ -473,10 +476,10 @@ __device__ __forceinline__ void outer_update(Blk (&st)[D / 16], const T *at, int
                             M::mma(*sums.sum_b, b.y[qb], M::lo_of(wf));
                     }
                 }
-                if (sums.sum_a && w >= r0 && w < r0 + GRP) {
+                if (sums.sum_a && w >= r0 && w < r0 + GR) {
                     const typename M::Frag2 wf = weights(sums.wa, kt);
 #pragma unroll
-                    for (int rb = 0; rb < GRP; ++rb)
+                    for (int rb = 0; rb < GR; ++rb)
                         if (r0 + rb == w) {
 #pragma unroll
                             for (int qa = 0; qa < NAP; ++qa) {
@@ -1016,9 +1019,9 @@ __global__ __launch_bounds__((FC<T, D>::NT), 2) void kf_fwd_apply(
             if constexpr (!F::MS) {
 #pragma unroll
                 for (int part = 0; part < VJ::PER; ++part) {
-                    if (VJ::mine(0, part, w))
+                    if (VJ::mine(0, part, w, l))
                         csv[64 * part + l] = tile_row_sum<T, D>(VTt, 64 * part + l);
-                    if (VJ::mine(1, part, w))
+                    if (VJ::mine(1, part, w, l))
                         csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
                 }
             }
@@ -1350,7 +1353,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             if constexpr (!F::MS) {
 #pragma unroll
                 for (int part = 0; part < VJ::PER; ++part)
-                    if (VJ::mine(0, part, w))
+                    if (VJ::mine(0, part, w, l))
                         csk[64 * part + l] = tile_row_sum<T, D>(KTt, 64 * part + l);
             }
         }
@@ -1361,8 +1364,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
 #pragma unroll
                 for (int part = 0; part < VJ::PER; ++part) {
                     const int r = 64 * part + l;
-                    if (VJ::mine(1, part, w)) vw += tile_row_sum<T, D>(OHt, r);
-                    if (VJ::mine(2, part, w)) vu += tile_row_dot<T, D>(QTt, r, dls);
+                    if (VJ::mine(1, part, w, l)) vw += tile_row_sum<T, D>(OHt, r);
+                    if (VJ::mine(2, part, w, l)) vu += tile_row_dot<T, D>(QTt, r, dls);
                 }
             }
         }
@@ -1434,8 +1437,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         } else {
 #pragma unroll
             for (int part = 0; part < VJ::PER; ++part) {
-                if (VJ::mine(1, part, w)) out[SL::W + 64 * part + l] = vw;
-                if (VJ::mine(2, part, w)) out[SL::U + 64 * part + l] = vu;
+                if (VJ::mine(1, part, w, l)) out[SL::W + 64 * part + l] = vw;
+                if (VJ::mine(2, part, w, l)) out[SL::U + 64 * part + l] = vu;
             }
         }
     }
@@ -1666,8 +1669,8 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
 #pragma unroll
                 for (int part = 0; part < VJ::PER; ++part) {
                     const int r = 64 * part + l;
-                    if (VJ::mine(0, part, w)) csw[r] = tile_row_sum<T, D>(OHt, r);
-                    if (VJ::mine(1, part, w)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
+                    if (VJ::mine(0, part, w, l)) csw[r] = tile_row_sum<T, D>(OHt, r);
+                    if (VJ::mine(1, part, w, l)) csu[r] = tile_row_dot<T, D>(QTt, r, dls);
                 }
             }
         }
@@ -1884,9 +1887,11 @@ la_status fast_kv_totals(const Problem &pr, const Plan &pl, const void *K, const
                          float *ws, hipStream_t st)
 {
     if (pr.dt == LA_F32) {
+        if (pr.D == 32) return fast_totals<float, 32>(pr, pl, K, V, ws, st);
         if (pr.D == 64) return fast_totals<float, 64>(pr, pl, K, V, ws, st);
         if (pr.D == 128) return fast_totals<float, 128>(pr, pl, K, V, ws, st);
     } else {
+        if (pr.D == 32) return fast_totals<__bf16, 32>(pr, pl, K, V, ws, st);
         if (pr.D == 64) return fast_totals<__bf16, 64>(pr, pl, K, V, ws, st);
         if (pr.D == 128) return fast_totals<__bf16, 128>(pr, pl, K, V, ws, st);
     }
@@ -1898,6 +1903,10 @@ la_status fast_backward_dq(const Problem &pr, const Plan &pl, const void *Q, con
                            float *ws, hipStream_t st)
 {
     Tracer tc(nullptr, st);
+    if (pr.dt == LA_F32 && pr.D == 32)
+        return fast_bwd<float, 32>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
+    if (pr.dt == LA_BF16 && pr.D == 32)
+        return fast_bwd<__bf16, 32>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
     if (pr.dt == LA_F32 && pr.D == 64)
         return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, nullptr, nullptr, ws, nullptr, st, tc, true);
     if (pr.dt == LA_F32 && pr.D == 128)
@@ -2020,7 +2029,7 @@ la_status split_backward(const Problem &pr, const Plan &pl, const void *Q, const
 bool fast_supported(const Problem &pr, int is_backward)
 {
     (void)is_backward;
-    return pr.D == 64 || pr.D == 128;
+    return pr.D == 32 || pr.D == 64 || pr.D == 128;
 }
 
 la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const void *K,
@@ -2029,6 +2038,9 @@ la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const 
                         Tracer &tc)
 {
     if (pr.dt == LA_BF16 && pr.norm_qk) {  // normalised rows stay fp32: fp32 tiles, bf16 in memory
+        if (pr.D == 32)
+            return fast_bwd<float, 32, 32, __bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved,
+                                                   st, tc);
         if (pr.D == 64)
             return fast_bwd<float, 64, 64, __bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved,
                                                    st, tc);
@@ -2036,6 +2048,10 @@ la_status fast_backward(const Problem &pr, const Plan &pl, const void *Q, const 
             return fast_bwd<float, 128, 128, __bf16>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws,
                                                      saved, st, tc);
     }
+    if (pr.dt == LA_F32 && pr.D == 32)
+        return fast_bwd<float, 32>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
+    if (pr.dt == LA_BF16 && pr.D == 32)
+        return fast_bwd<__bf16, 32>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_F32 && pr.D == 64)
         return fast_bwd<float, 64>(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, ws, saved, st, tc);
     if (pr.dt == LA_F32 && pr.D == 128)
@@ -2052,15 +2068,19 @@ la_status fast_forward(const Problem &pr, const Plan &pl, const void *Q, const v
                        Tracer &tc)
 {
     if (pr.dt == LA_BF16 && pr.norm_qk) {  // normalised rows stay fp32: fp32 tiles, bf16 in memory
+        if (pr.D == 32)
+            return fast_fwd<float, 32, 32, __bf16>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 64)
             return fast_fwd<float, 64, 64, __bf16>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 128)
             return fast_fwd<float, 128, 128, __bf16>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     }
     if (pr.dt == LA_F32) {
+        if (pr.D == 32) return fast_fwd<float, 32>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 64) return fast_fwd<float, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 128) return fast_fwd<float, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     } else {
+        if (pr.D == 32) return fast_fwd<__bf16, 32>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 64) return fast_fwd<__bf16, 64>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
         if (pr.D == 128) return fast_fwd<__bf16, 128>(pr, pl, Q, K, V, O, G, ws, saved, st, tc);
     }

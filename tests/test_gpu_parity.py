@@ -131,7 +131,7 @@ def test_other_coefficients(oracle_mod, la, knobs, D, dtype, ab):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("D", [32, 64, 128, 256])
 def test_plain_alu_path_at_large_heads(oracle_mod, la, knobs, D, dtype):
     """The plain-ALU kernels are compiled for every head size (token-serial ones at D = 256);
     force them where the matrix-core kernels would normally run."""
