@@ -24,12 +24,13 @@ static bool supported_d(int D) { return D == 16 || D == 32 || D == 64 || D == 12
 // slices x segments is about 256 x that residency: every compute unit then gets the
 // same number of equally long segments in a single round.
 // Segments are also kept long enough that the D x D state a segment hands over stays
-// small next to the rows it covers.  la_debug_override can force a length (rounded up to 64).
+// small next to the rows it covers (a sixth of their bytes at the shortest: short
+// sequences in few slices would otherwise leave most of the chip idle).  la_debug_override can force a length (rounded up to 64).
 Plan make_plan(int B, int H, int N, int D, la_dtype dt, int causal, int is_backward)
 {
     Plan p;
     const long BH = (long)B * H;
-    const int min_len = (D >= 128) ? 512 : 256;
+    const int min_len = (D >= 128) ? 192 : 128;
     const long resident = D == 256                      ? 1
                           : (!causal || D <= 32)        ? 4
                           : (dt == LA_F32 && D <= 64) ? 2
