@@ -356,9 +356,10 @@ static la_status backward_impl(const void *Q, const void *K, const void *V, cons
                                tc)
             : la::generic_backward(pr, pl, Q, K, V, O, G, dO, dQ, dK, dV, (float *)workspace, st,
                                    tc);
-    if (s != LA_OK || !norm_qk) return s;
-    // the kernels left the gradients for the normalised rows: take them through the backward of
-    // the normalisation, in place
+    // the matrix-core kernels take dQ, dK through the backward of the normalisation before
+    // they store them
+    if (s != LA_OK || !norm_qk || fast) return s;
+    // the plain-ALU kernels left the gradients for the normalised rows: the same, in place
     s = la::project_rows(Q, dQ, T, D, dt, st);
     if (s != LA_OK) return s;
     tc.mark("project_dq");

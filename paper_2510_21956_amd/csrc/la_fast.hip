@@ -334,10 +334,12 @@ __device__ __forceinline__ float reduce_adjacent(float s)
 // Row normalisation of Sec. 3.3 on a stager's registers: each of the thread's four rows is
 // scaled to unit length (the row is held by the GPR consecutive lanes that share it) and, for
 // bf16, rounded back to the tile's type.  Rows of zeros (past the end of the slice) stay zeros.
+// inv_out (C floats in LDS, if given) receives 1 / |row| of the chunk's rows.
 template <typename T, int D, int LD, typename TIO>
-__device__ __forceinline__ void normalise_rows(Stager<T, D, LD, TIO> &s)
+__device__ __forceinline__ void normalise_rows(Stager<T, D, LD, TIO> &s, float *inv_out = nullptr)
 {
     typedef FC<T, D> F;
+    const int th = threadIdx.x % F::HT, dg = th % F::GPR, rq = F::row_quad(th);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float x[F::EPV], ss = 0.f;
@@ -348,6 +350,7 @@ __device__ __forceinline__ void normalise_rows(Stager<T, D, LD, TIO> &s)
         }
         ss = reduce_adjacent<F::GPR>(ss);
         const float inv = ss > 0.f ? 1.f / sqrtf(ss) : 0.f;
+        if (inv_out && dg == 0) inv_out[4 * rq + i] = inv;
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) s.raw[i][e] = __float_as_uint(x[e] * inv);
@@ -776,6 +779,34 @@ __device__ __forceinline__ void store_grad_block(TIO *out, float *part, bool add
         store_block<TIO>(out, LD, col0, rows_valid, l, x0, x1, x2, x3, 1, nullptr, part, D);
 }
 
+// Backward of the row normalisation (Sec. 3.3) on gradient blocks still in registers:
+//   dx = (dxhat - xhat (xhat . dxhat)) / |x|     for every row of the chunk.
+// Lane (c, g) holds dxhat[row 16 m + c][columns 16 w + 4 g .. + 3] of NBK row blocks in x[m] and
+// the same elements of xhat in xh[m].  The row's dot product runs over all D columns, i.e.
+// over the lane groups of a wave and over the waves: per-wave shares meet in dots[NW][C]
+// (LDS), which costs one workgroup barrier.  Every thread of the workgroup must call this.
+template <int NW, int C, int NBK>
+__device__ __forceinline__ void project_blocks(float (&x)[NBK][4], const float (&xh)[NBK][4],
+                                               float *dots, const float *inv, int w, int c, int g)
+{
+#pragma unroll
+    for (int m = 0; m < NBK; ++m) {
+        float s = (x[m][0] * xh[m][0] + x[m][1] * xh[m][1]) + (x[m][2] * xh[m][2] + x[m][3] * xh[m][3]);
+        s = reduce_lane_groups(s);
+        if (g == 0) dots[w * C + m * 16 + c] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < NBK; ++m) {
+        float dot = 0.f;
+#pragma unroll
+        for (int v = 0; v < NW; ++v) dot += dots[v * C + m * 16 + c];
+        const float iv = inv[m * 16 + c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[m][e] = (x[m][e] - xh[m][e] * dot) * iv;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Phase 1: per-segment S = sum k v^T, z = sum k, p = sum v (Eq. xy without the
 // factors), written to state slot `seg + slot_shift` as [S | z | p].  The
@@ -1181,6 +1212,10 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
     // 1/g of the chunk's rows (two buffers: the next chunk's are written while this one's
     // are still read), dprime, delta, sum k
     __shared__ __align__(16) float rsb[2][C], dl[C], dls[C], csk[F::MS ? 4 : D];
+    // fp32 tiles with `norm`: 1 / |q| of the chunk's rows and the per-wave shares of qhat . dqhat
+    constexpr bool PROJ = sizeof(T) == 4 && LD == D;
+    static_assert(!PROJ || NB == 2, "the projection takes the chunk's two row blocks at once");
+    __shared__ float qinv[PROJ ? C : 1], dots[PROJ ? NW * C : 1];
     typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
 
     const int bh = blockIdx.x / nseg, seg = blockIdx.x % nseg;
@@ -1283,12 +1318,15 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
         s1.widen();
         s2.widen();
         if constexpr (CAUSAL) s3.widen();
+        // with `norm` every segment needs the normalised Q: dQ goes through the backward of the
+        // normalisation before it is stored
+        const bool need_Q = need_R || (PROJ && norm);
         if (norm && !h0) {
             if constexpr (CAUSAL) {
                 normalise_rows(s2);  // K
-                if (need_R) normalise_rows(s3);  // Q
+                if (need_Q) normalise_rows(s3, PROJ ? qinv : nullptr);  // Q
             } else {
-                normalise_rows(s1);  // Q
+                normalise_rows(s1, PROJ ? qinv : nullptr);  // Q
             }
         }
         if (h0) {
@@ -1315,7 +1353,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
             s1.store_rows(Vs);
             s1.store_cols(VTt);
             s2.store_cols(KTt);
-            if (need_R) s3.store_cols(QTt);
+            if (need_Q) s3.store_cols(QTt);
         } else {
             s1.store_cols(QTt);
         }
@@ -1391,15 +1429,33 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((CAUSAL || D > 64 || sizeof(T) < 4
                 if (lo_on) chunk_products_lower<T, D, 2, PP>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
                 else chunk_products_lower<T, D, 2, 1>(acc, i0, KTt, w * 16, Cms, PSZ, c, g, wo);
             }
+            float x[2][4];
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const float f = b * sc[ii];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[ii][e] = f * (acc[ii].get(e) - di[ii] * z4[e]);
+            }
+            if constexpr (PROJ) {
+                if (norm) {  // the same for the whole workgroup
+                    float qh[2][4];  // qhat[row 16 ii + c][column 16 w + 4 g + e], from its columns
+#pragma unroll
+                    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int r = w * 16 + 4 * g + e, i = ii * 16 + c;
+                            qh[ii][e] = to_float(QTt[r * LDT + F::tr_pos(i / 4, r) + i % 4]);
+                        }
+                    project_blocks<NW, C, 2>(x, qh, dots, qinv, w, c, g);
+                }
+            }
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
                 const int ib = i0 + ii;
-                const float f = b * sc[ii];
                 store_grad_block<TIO, D, LD>(
                     dQp + (size_t)(c0 + ib * 16) * LD, Pq + ((size_t)bh * N + c0 + ib * 16) * D,
-                    xflags & 1, w * 16, (int)(row1 - c0) - ib * 16, l,
-                    f * (acc[ii].get(0) - di[ii] * z4[0]), f * (acc[ii].get(1) - di[ii] * z4[1]),
-                    f * (acc[ii].get(2) - di[ii] * z4[2]), f * (acc[ii].get(3) - di[ii] * z4[3]));
+                    xflags & 1, w * 16, (int)(row1 - c0) - ib * 16, l, x[ii][0], x[ii][1], x[ii][2],
+                    x[ii][3]);
             }
             if (i0 == 0) fetch_part(cn, std::integral_constant<int, 2>());
         }
@@ -1484,13 +1540,17 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
     constexpr bool RL = kSingleR<T, D, CAUSAL>;
     constexpr int NELEM = 2 * RM + TS * (2 * RM + TSZ + PP * TSZ + 2 * PP * PSZ) + (RL ? D * LDR : 0);
     constexpr int NCS = F::MS ? 0 : 2 * D;  // vector-ALU sums: u and w of the chunk
-    __shared__ __align__(16) unsigned char lds[(6 * C + NCS) * 4 + NELEM * sizeof(T)];
+    // fp32 tiles with `norm`: 1 / |k| of the chunk's rows and the per-wave shares of khat . dkhat
+    constexpr bool PROJ = sizeof(T) == 4 && LD == D;
+    constexpr int NPJ = PROJ ? C + NW * C : 0;
+    __shared__ __align__(16) unsigned char lds[(6 * C + NCS + NPJ) * 4 + NELEM * sizeof(T)];
     // 1/g, dprime, delta of the chunk's rows: two buffers of [3][C], the next chunk's being
     // written while this one's are still read
     float *fac = reinterpret_cast<float *>(lds);
     float *csu = fac + 6 * C, *csw = csu + NCS / 2;
+    float *kinv = fac + 6 * C + NCS, *dots = kinv + (PROJ ? C : 0);
     typedef VecJobs<NW, D, CAUSAL ? NB * (NB + 1) / 2 : 0> VJ;
-    T *CmT = reinterpret_cast<T *>(fac + 6 * C + NCS), *WT = CmT + TS * PP * PSZ;
+    T *CmT = reinterpret_cast<T *>(fac + 6 * C + NCS + NPJ), *WT = CmT + TS * PP * PSZ;
     T *QTt = WT + TS * PP * PSZ, *OHt = QTt + TS * TSZ;
     T *Ks = OHt + TS * PP * TSZ, *Vs = Ks + RM, *Qs = Vs + RM, *dOs = Qs + TS * RM;
     T *Rs = dOs + TS * RM;  // [D][LDR], only if RL
@@ -1606,7 +1666,7 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
         s1.widen();
         if constexpr (CAUSAL) s2.widen();
         if (norm && h0) {
-            normalise_rows(s1);  // K
+            normalise_rows(s1, PROJ ? kinv : nullptr);  // K
             if constexpr (CAUSAL) normalise_rows(s2);  // Q
         }
         if (h0) {
@@ -1710,11 +1770,38 @@ __global__ __launch_bounds__((FC<T, D>::NT), ((sizeof(T) < 4 && D == 64 && CAUSA
                             chunk_product<T, D, 1, 1>(ak[m], QTt, 0, w * 16, CmT, PSZ, nb * 16,
                                                       (nb * 16) / KT, C / KT, c, g, wo);
                     }
-                    store_grad_block<TIO, D, LD>(
-                        dKp + (size_t)(c0 + nb * 16) * LD, Pk + ((size_t)bh * N + c0 + nb * 16) * D,
-                        xflags & 2, w * 16, (int)(row1 - c0) - nb * 16, l,
-                        b * (ak[m].get(0) - u4[0]), b * (ak[m].get(1) - u4[1]),
-                        b * (ak[m].get(2) - u4[2]), b * (ak[m].get(3) - u4[3]));
+                    if (!(PROJ && norm))
+                        store_grad_block<TIO, D, LD>(
+                            dKp + (size_t)(c0 + nb * 16) * LD,
+                            Pk + ((size_t)bh * N + c0 + nb * 16) * D, xflags & 2, w * 16,
+                            (int)(row1 - c0) - nb * 16, l, b * (ak[m].get(0) - u4[0]),
+                            b * (ak[m].get(1) - u4[1]), b * (ak[m].get(2) - u4[2]),
+                            b * (ak[m].get(3) - u4[3]));
+                }
+                if constexpr (PROJ) {
+                    if (norm) {  // the same for the whole workgroup: dK through the backward of
+                                 // the normalisation before it is stored
+                        static_assert(!PROJ || NPB == 2, "two row blocks per chunk");
+                        float x[2][4], kh[2][4];
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) {
+                            // khat[row 16 m + c][columns 16 w + 4 g .. + 3]: one unit of its row
+                            const int n = m * 16 + c;
+                            const f4v k4 = *reinterpret_cast<const f4v *>(
+                                Ks + n * LDR + 4 * ((4 * w + g) ^ F::flip(n)));
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                x[m][e] = b * (ak[m].get(e) - u4[e]);
+                                kh[m][e] = to_float(k4[e]);
+                            }
+                        }
+                        project_blocks<NW, C, 2>(x, kh, dots, kinv, w, c, g);
+#pragma unroll
+                        for (int m = 0; m < 2; ++m)
+                            store_grad_block<TIO, D, LD>(
+                                dKp + (size_t)(c0 + m * 16) * LD, Pk, false, w * 16,
+                                (int)(row1 - c0) - m * 16, l, x[m][0], x[m][1], x[m][2], x[m][3]);
+                    }
                 }
             }
             fetch_part(cn, std::integral_constant<int, 3>());
