@@ -229,6 +229,15 @@ def extras(torch, wl, la):
         la.la_backward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
                               t["dV"], cfg.a, cfg.b, cfg.causal, wsb)
     res["qknorm_fwd_bwd_" + cfg.name] = {"ms_per_step": timed(qknorm_step, 30)}
+    nsv = la.la_saved_state_bytes(*args6)
+    sv = torch.empty(max(256, nsv), dtype=torch.uint8, device="cuda") if nsv else None
+
+    def qknorm_saved_step():
+        la.la_forward_qknorm_save(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg.a, cfg.b, cfg.causal,
+                                  wsf, sv)
+        la.la_backward_qknorm_saved(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
+                                    t["dK"], t["dV"], cfg.a, cfg.b, cfg.causal, wsb, sv)
+    res["qknorm_save_fwd_bwd_" + cfg.name] = {"ms_per_step": timed(qknorm_saved_step, 30)}
     dab = torch.zeros(2, device="cuda")
     res["backward_ab_" + cfg.name] = {"ms": timed(
         lambda: la.la_backward_ab(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], dab, cfg.a,
@@ -250,6 +259,15 @@ def extras(torch, wl, la):
         la.la_backward_qknorm(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"], t["dK"],
                               t["dV"], cfg4.a, cfg4.b, cfg4.causal, wsb)
     res["qknorm_fwd_bwd_" + cfg4.name] = {"ms_per_step": timed(qknorm_step_bf16, 30)}
+    nsv = la.la_saved_state_bytes(*b6)
+    sv = torch.empty(max(256, nsv), dtype=torch.uint8, device="cuda") if nsv else None
+
+    def qknorm_saved_step_bf16():
+        la.la_forward_qknorm_save(t["Q"], t["K"], t["V"], t["O"], t["G"], cfg4.a, cfg4.b,
+                                  cfg4.causal, wsf, sv)
+        la.la_backward_qknorm_saved(t["Q"], t["K"], t["V"], t["O"], t["G"], t["dO"], t["dQ"],
+                                    t["dK"], t["dV"], cfg4.a, cfg4.b, cfg4.causal, wsb, sv)
+    res["qknorm_save_fwd_bwd_" + cfg4.name] = {"ms_per_step": timed(qknorm_saved_step_bf16, 30)}
     del t, wsf, wsb
     torch.cuda.empty_cache()
     # head size 256: the top of the paper's head-size sweep, and the same shape in bf16

@@ -135,8 +135,8 @@ LA_API la_status la_backward(const void *Q, const void *K, const void *V,
  * are the raw rows, every kernel scales them to unit length (qhat = q / ||q||, khat = k /
  * ||k||) as it stages them, so that no normalised copy of Q and K is ever written or read
  * back, and la_backward_qknorm returns the gradients for the raw rows,
- *     dq = (dqhat - qhat (qhat . dqhat)) / ||q||   (likewise dk),
- * by passing the kernels' dqhat, dkhat through that map in place before it returns.
+ *     dq = (dqhat - qhat (qhat . dqhat)) / ||q||   (likewise dk):
+ * the kernels pass their dqhat, dkhat through that map before they store them.
  * Arguments, workspace sizes (la_workspace_bytes with is_backward 0 / 1, or 2 when O or G is
  * NULL) and error behaviour as for la_forward_traced / la_backward_traced; O and G are those
  * of la_forward_qknorm.  A row of zeros stays a row of zeros (and makes g_i = a n_i for it).
@@ -157,6 +157,30 @@ LA_API la_status la_backward_qknorm(const void *Q, const void *K, const void *V,
                       int B, int H, int N, int D,
                       float a, float b, int causal, la_dtype dt,
                       void *workspace, size_t workspace_bytes, void *hip_stream,
+                      struct la_trace *trace);
+
+/*
+ * The same pair with the hand-over of la_forward_save / la_backward_saved: the running
+ * sums of the normalised rows at the segment boundaries go from the forward call to the
+ * backward call through `saved` (la_saved_state_bytes bytes, 256-byte aligned; NULL where
+ * that size is 0), which then skips their recomputation.  What a training step with the
+ * normalisation of Sec. 3.3 runs.
+ */
+LA_API la_status la_forward_qknorm_save(const void *Q, const void *K, const void *V,
+                     void *O, float *G,
+                     int B, int H, int N, int D,
+                     float a, float b, int causal, la_dtype dt,
+                     void *workspace, size_t workspace_bytes,
+                     void *saved, size_t saved_bytes, void *hip_stream,
+                     struct la_trace *trace);
+
+LA_API la_status la_backward_qknorm_saved(const void *Q, const void *K, const void *V,
+                      const void *O, const float *G, const void *dO,
+                      void *dQ, void *dK, void *dV,
+                      int B, int H, int N, int D,
+                      float a, float b, int causal, la_dtype dt,
+                      void *workspace, size_t workspace_bytes,
+                      const void *saved, size_t saved_bytes, void *hip_stream,
                       struct la_trace *trace);
 
 /*

@@ -4,8 +4,9 @@ Plumbing only: it allocates the outputs, the workspaces and the hand-over buffer
 torch, keeps the set {Q, K, V, O, g} of Sec. 3.2 (plus the forward pass's running sums at
 the segment boundaries) for the backward pass, and calls la_forward_save /
 la_backward_saved.  Every arithmetic step runs in the HIP library; there is no fallback.
-Gradients are with respect to the Q, K, V handed in (row normalisation of Q and K,
-Sec. 3.3, is the caller's job); a and b are constants.
+Gradients are with respect to the Q, K, V handed in; with ``normalize_qk`` the rows of Q and
+K are scaled to unit length inside the kernels (Sec. 3.3) and the gradients are those for the
+raw rows.  a and b are constants.
 """
 import torch
 
@@ -24,7 +25,7 @@ class LinearAttentionFunction(torch.autograd.Function):
     """O = LA(Q, K, V) with kernel f(x) = a + b x; Q, K, V: [B, H, N, D] device tensors."""
 
     @staticmethod
-    def forward(ctx, Q, K, V, a, b, causal):
+    def forward(ctx, Q, K, V, a, b, causal, normalize_qk=False):
         Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
         B, H, N, D = Q.shape
         dt = _code(Q)
@@ -33,24 +34,27 @@ class LinearAttentionFunction(torch.autograd.Function):
         ws = _bytes(_b.la_workspace_bytes(B, H, N, D, dt, causal, 0), Q.device)
         ns = _b.la_saved_state_bytes(B, H, N, D, dt, causal)
         saved = _bytes(ns, Q.device) if ns else None
-        _b.la_forward_save(Q, K, V, O, G, a, b, causal, ws, saved)
+        fwd = _b.la_forward_qknorm_save if normalize_qk else _b.la_forward_save
+        fwd(Q, K, V, O, G, a, b, causal, ws, saved)
         ctx.save_for_backward(Q, K, V, O, G)
         ctx.la_saved = saved
-        ctx.la_args = (float(a), float(b), bool(causal))
+        ctx.la_args = (float(a), float(b), bool(causal), bool(normalize_qk))
         return O
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, O, G = ctx.saved_tensors
-        a, b, causal = ctx.la_args
+        a, b, causal, normalize_qk = ctx.la_args
         B, H, N, D = Q.shape
         dO = dO.contiguous()
         dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
         ws = _bytes(_b.la_workspace_bytes(B, H, N, D, _code(Q), causal, 1), Q.device)
-        _b.la_backward_saved(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, ws, ctx.la_saved)
-        return dQ, dK, dV, None, None, None
+        bwd = _b.la_backward_qknorm_saved if normalize_qk else _b.la_backward_saved
+        bwd(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, ws, ctx.la_saved)
+        return dQ, dK, dV, None, None, None, None
 
 
-def linear_attention(Q, K, V, a=1.0, b=0.5, causal=True):
-    """Differentiable linear attention on [B, H, N, D] float32 or bfloat16 device tensors."""
-    return LinearAttentionFunction.apply(Q, K, V, a, b, causal)
+def linear_attention(Q, K, V, a=1.0, b=0.5, causal=True, normalize_qk=False):
+    """Differentiable linear attention on [B, H, N, D] float32 or bfloat16 device tensors;
+    ``normalize_qk`` scales the rows of Q and K to unit length inside the kernels (D <= 128)."""
+    return LinearAttentionFunction.apply(Q, K, V, a, b, causal, normalize_qk)

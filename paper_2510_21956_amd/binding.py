@@ -21,7 +21,7 @@ EXPORTS = ("la_version", "la_status_string", "la_workspace_bytes", "la_forward",
            "la_forward_traced", "la_backward_traced", "la_saved_state_bytes", "la_forward_save",
            "la_backward_saved", "la_debug_override", "la_forward_static", "la_decode_state_bytes",
            "la_decode_step", "la_decode_prefill", "la_backward_ab", "la_forward_qknorm",
-           "la_backward_qknorm")
+           "la_backward_qknorm", "la_forward_qknorm_save", "la_backward_qknorm_saved")
 
 
 class la_trace(ctypes.Structure):
@@ -87,6 +87,10 @@ def load_library():
     lib.la_forward_qknorm.argtypes = lib.la_forward_traced.argtypes
     lib.la_backward_qknorm.restype = i
     lib.la_backward_qknorm.argtypes = lib.la_backward_traced.argtypes
+    lib.la_forward_qknorm_save.restype = i
+    lib.la_forward_qknorm_save.argtypes = lib.la_forward_save.argtypes
+    lib.la_backward_qknorm_saved.restype = i
+    lib.la_backward_qknorm_saved.argtypes = lib.la_backward_saved.argtypes
     lib.la_backward_ab.restype = i
     lib.la_backward_ab.argtypes = [vp] * 7 + [i, i, i, i, f, f, i, i, vp, sz, vp]
     lib.la_debug_override.restype = None
@@ -211,6 +215,9 @@ def _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, save)
     tr = ctypes.byref(trace) if trace is not None else None
     if save == "qknorm":
         rc = lib.la_forward_qknorm(*head, _stream_ptr(stream, Q.device), tr)
+    elif save == "qknorm_save":
+        sp, sb = _saved_args(saved, Q)
+        rc = lib.la_forward_qknorm_save(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
     elif save:
         sp, sb = _saved_args(saved, Q)
         rc = lib.la_forward_save(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
@@ -261,6 +268,9 @@ def _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, str
     tr = ctypes.byref(trace) if trace is not None else None
     if use_saved == "qknorm":
         rc = lib.la_backward_qknorm(*head, _stream_ptr(stream, Q.device), tr)
+    elif use_saved == "qknorm_save":
+        sp, sb = _saved_args(saved, Q)
+        rc = lib.la_backward_qknorm_saved(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
     elif use_saved:
         sp, sb = _saved_args(saved, Q)
         rc = lib.la_backward_saved(*head, sp, sb, _stream_ptr(stream, Q.device), tr)
@@ -343,3 +353,15 @@ def la_backward_qknorm(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, s
     """la_backward_qknorm of include/la.h: gradients for the raw Q, K."""
     _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, None, stream, trace,
               "qknorm")
+
+
+def la_forward_qknorm_save(Q, K, V, O, G, a, b, causal, workspace, saved, stream=None, trace=None):
+    """la_forward_qknorm_save of include/la.h (``saved`` as for la_forward_save)."""
+    _forward(Q, K, V, O, G, a, b, causal, workspace, saved, stream, trace, "qknorm_save")
+
+
+def la_backward_qknorm_saved(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved,
+                             stream=None, trace=None):
+    """la_backward_qknorm_saved of include/la.h; ``saved`` as filled by la_forward_qknorm_save."""
+    _backward(Q, K, V, O, G, dO, dQ, dK, dV, a, b, causal, workspace, saved, stream, trace,
+              "qknorm_save")

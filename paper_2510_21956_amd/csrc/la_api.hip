@@ -460,6 +460,26 @@ la_status la_forward_qknorm(const void *Q, const void *K, const void *V, void *O
                         false, nullptr, 0, hip_stream, trace, 1);
 }
 
+la_status la_forward_qknorm_save(const void *Q, const void *K, const void *V, void *O, float *G,
+                                 int B, int H, int N, int D, float a, float b, int causal,
+                                 la_dtype dt, void *workspace, size_t workspace_bytes, void *saved,
+                                 size_t saved_bytes, void *hip_stream, la_trace *trace)
+{
+    return forward_impl(Q, K, V, O, G, B, H, N, D, a, b, causal, dt, workspace, workspace_bytes,
+                        true, saved, saved_bytes, hip_stream, trace, 1);
+}
+
+la_status la_backward_qknorm_saved(const void *Q, const void *K, const void *V, const void *O,
+                                   const float *G, const void *dO, void *dQ, void *dK, void *dV,
+                                   int B, int H, int N, int D, float a, float b, int causal,
+                                   la_dtype dt, void *workspace, size_t workspace_bytes,
+                                   const void *saved, size_t saved_bytes, void *hip_stream,
+                                   la_trace *trace)
+{
+    return backward_impl(Q, K, V, O, G, dO, dQ, dK, dV, B, H, N, D, a, b, causal, dt, workspace,
+                         workspace_bytes, true, saved, saved_bytes, hip_stream, trace, 1);
+}
+
 la_status la_backward_qknorm(const void *Q, const void *K, const void *V, const void *O,
                              const float *G, const void *dO, void *dQ, void *dK, void *dV, int B,
                              int H, int N, int D, float a, float b, int causal, la_dtype dt,

@@ -1,5 +1,5 @@
-"""GPU parity of la_forward_qknorm / la_backward_qknorm (row normalisation of Q and K inside
-the call, Sec. 3.3) against the oracle: normalisation, running-sum passes, backward of the
+"""GPU parity of la_forward_qknorm / la_backward_qknorm and of the pair with the hand-over
+(row normalisation of Q and K inside the call, Sec. 3.3) against the oracle: normalisation, running-sum passes, backward of the
 normalisation, all in fp64.  Inputs are raw Gaussian rows of widely different lengths."""
 import numpy as np
 import pytest
@@ -73,14 +73,57 @@ def test_qknorm(oracle_mod, la, case, causal, dtype):
         la.la_backward_qknorm(dev["Q"], dev["K"], dev["V"], None, None, dev["dO"], g2[0], g2[1],
                               g2[2], a, b, causal,
                               scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 2), "cuda"))
+        # the pair with the hand-over: same forward outputs bit for bit, gradients from the
+        # sums the forward pass handed over
+        O3 = torch.full((B, H, N, D), float("nan"), dtype=td, device="cuda")
+        G3 = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+        nsv = la.la_saved_state_bytes(B, H, N, D, dt, causal)
+        saved = scratch(nsv, "cuda") if nsv else None
+        la.la_forward_qknorm_save(dev["Q"], dev["K"], dev["V"], O3, G3, a, b, causal,
+                                  scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 0), "cuda"),
+                                  saved)
+        g3 = [torch.full((B, H, N, D), float("nan"), dtype=td, device="cuda") for _ in range(3)]
+        la.la_backward_qknorm_saved(dev["Q"], dev["K"], dev["V"], O_in, G_in, dev["dO"], g3[0],
+                                    g3[1], g3[2], a, b, causal,
+                                    scratch(la.la_workspace_bytes(B, H, N, D, dt, causal, 1),
+                                            "cuda"), saved)
         torch.cuda.synchronize()
+        assert torch.equal(O3, O) and torch.equal(G3, G), "%s hand-over forward differs" % tag
         worst = {"O": excess(to_f64(O.reshape(BH, N, D)), O_ref, tol),
                  "G": excess(to_f64(G.reshape(BH, N)), G_ref, TOL["f32"])}
-        for nm, x, y, want in zip(("dQ", "dK", "dV"), g, g2, grads_ref):
+        for nm, x, y, z, want in zip(("dQ", "dK", "dV"), g, g2, g3, grads_ref):
             worst[nm] = excess(to_f64(x.reshape(BH, N, D)), want, tol)
             worst[nm + "_recomputed"] = excess(to_f64(y.reshape(BH, N, D)), want, tol)
+            worst[nm + "_saved"] = excess(to_f64(z.reshape(BH, N, D)), want, tol)
         print(tag, {k: round(v, 4) for k, v in worst.items()}, flush=True)
         for nm, e in worst.items():
             assert e <= 1.0, "%s %s exceeds tolerance by factor %.3g" % (tag, nm, e)
     finally:
         la.la_debug_override(0, 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_autograd_wrapper_normalised(oracle_mod, la, dtype):
+    """linear_attention(..., normalize_qk=True): gradients through torch's backward() for the raw
+    rows against the oracle's.  The wrapper's backward consumes its own stored O and g; the
+    oracle's backward is given its O rounded to the I/O type and its g in float32, the same
+    stored set up to the rare element the two forward passes round differently."""
+    B, H, N, D = 2, 2, 500, 64
+    BH = B * H
+    a, b, causal = 1.0, 0.5, True
+    dev, ref = draw_raw(BH, N, D, dtype, 7900)
+    dev = {n: t.reshape(B, H, N, D).contiguous() for n, t in dev.items()}
+    O_ref, G_ref = oracle_mod.forward_qknorm(ref["Q"], ref["K"], ref["V"], a, b, causal)
+    _, O_64, _, G_64 = saved_set(O_ref, G_ref, dtype)
+    grads_ref = oracle_mod.backward_qknorm(ref["Q"], ref["K"], ref["V"], O_64, G_64, ref["dO"], a,
+                                           b, causal)
+    Q, K, V = (dev[n].clone().requires_grad_(True) for n in ("Q", "K", "V"))
+    O = la.linear_attention(Q, K, V, a, b, causal, normalize_qk=True)
+    (O.float() * dev["dO"].float()).sum().backward()
+    torch.cuda.synchronize()
+    got = {"O": O.detach(), "dQ": Q.grad, "dK": K.grad, "dV": V.grad}
+    want = {"O": O_ref, "dQ": grads_ref[0], "dK": grads_ref[1], "dV": grads_ref[2]}
+    for name in got:
+        e = excess(to_f64(got[name].reshape(BH, N, D)), want[name], TOL[dtype])
+        print("autograd normalised", dtype, name, round(e, 4), flush=True)
+        assert e <= 1.0, "%s exceeds tolerance by factor %.3g" % (name, e)
