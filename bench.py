@@ -494,6 +494,9 @@ def measure(cfg, args, steps, warmup, torch, wl, la):
                        "algorithmic_flops": pass_flops, "achieved_TFLOPs": pass_tflops,
                        "mfma_peak_TFLOPs": mfma_peak, "frac_of_mfma_peak": pass_tflops / mfma_peak},
         "kernels_ms": kernels_ms,
+        # the two passes separately: sums of the traced kernel intervals
+        "forward_ms_traced": sum(v for k, v in kernels_ms.items() if k.startswith("fwd:")),
+        "backward_ms_traced": sum(v for k, v in kernels_ms.items() if k.startswith("bwd:")),
         "peak_allocated_device_bytes": int(peak_bytes),
         "workspace_bytes": {"forward": wsf.numel(), "backward": wsb.numel(), "saved": nsv},
         "roofline": roofline,
