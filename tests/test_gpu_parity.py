@@ -222,6 +222,25 @@ def test_head_size_256_bf16(oracle_mod, la, knobs, causal):
     check_against_oracle(oracle_mod, la, dev, ref, slices, "bf16", 1.0, 0.5, causal, tag)
 
 
+UNUSUAL = [(64, 32, 3, 64, "f32", True), (64, 32, 3, 32, "bf16", True), (1, 1, 70000, 32, "f32", True),
+           (2, 300, 100, 128, "bf16", True), (1, 2, 5, 256, "f32", False), (1, 600, 64, 32, "f32", True),
+           (1, 1, 20000, 256, "bf16", True), (1, 1, 2, 32, "f32", True)]
+
+
+@pytest.mark.parametrize("case", UNUSUAL)
+def test_unusual_shapes(oracle_mod, la, knobs, case):
+    """Shapes far from the benchmark's, in the plan the library picks: thousands of slices of a
+    few rows, hundreds of heads, one long slice, two rows; three sampled slices each."""
+    knobs(0, 0)
+    B, H, N, D, dtype, causal = case
+    BH = B * H
+    slices = sorted(set([0, BH // 2, BH - 1]))
+    tag = "unusual B%d H%d N%d D%d %s causal=%d" % (B, H, N, D, dtype, causal)
+    print("case", tag, flush=True)
+    dev, ref = upload_case(B, H, N, D, dtype, 9100 + N + D, slices)
+    check_against_oracle(oracle_mod, la, dev, ref, slices, dtype, 1.0, 0.5, causal, tag)
+
+
 # The paper's own benchmark shapes (Sec. 5.1), the ones the oracle finishes in seconds on a
 # few sampled slices: the two shorter lengths of the D = 128 sweep (N = 10000 is not a
 # multiple of any tile size) and the three head sizes at N = 4096.
