@@ -1,4 +1,5 @@
-// Matrix-core linear-attention kernels for gfx950 (D = 64 or 128).
+// Matrix-core linear-attention kernels for gfx950: D = 32, 64, 128, and D = 256 as passes of
+// the D = 128 kernels over blocks of 128 columns (split_forward / split_backward below).
 //
 // Same chunk algebra and the same three phases as the generic kernels (per-
 // segment sums, scan over segments, apply), with every dense contraction on
@@ -11,6 +12,8 @@
 // row factors 1/g_i are applied in fp32 to accumulators and intermediates, never
 // to a bf16 tile of inputs, so that bf16 I/O loses nothing beyond its own
 // storage rounding.  Intermediates that become bf16 operands are split hi + lo.
+// (The tile type T and the type in memory TIO are separate template parameters: the calls
+// that normalise Q and K inside the kernels run bf16 tensors on fp32 tiles.)
 //
 // Output blocks are computed transposed (accumulator rows = output columns), so
 // that a lane ends up with four consecutive columns of one output row and
