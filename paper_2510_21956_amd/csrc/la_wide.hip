@@ -1,7 +1,7 @@
 // Head size 256: token-serial kernels with the D x D running state in registers.  The
 // library runs D = 256 on the matrix-core kernels (la_fast.hip); these are what
 // la_debug_override(.., 1) switches to, as it does to the plain-ALU kernels at the other
-// head sizes, and the reference the tests hold that path against on the GPU.
+// head sizes; the parity tests run them under that setting.
 //
 // A 256 x 256 float state is 256 KB: more than the LDS of a compute unit, and more tile
 // space than the chunked matrix-core kernels can afford next to it.  It does fit the
